@@ -1,0 +1,235 @@
+"""Float64 CPU oracle for UNComp's prefill-time KV compression pass.
+
+TEST INFRASTRUCTURE ONLY.  This module is the slow, plain statement of what the
+hot path computes, written from the paper.  It shares no code with the HIP
+library and must never be imported by the product package: only tests, the
+smoke check and the bench's cpu_baseline leg may call it.
+
+Everything is numpy float64.  Library primitives used as single steps:
+``numpy.linalg.eigvalsh`` (eigenvalues of a symmetric matrix), ``@`` (matmul),
+``numpy.argsort`` (stable sort).  No blocking, fusion or reordering beyond what
+the definitions state.
+
+Parity status of each function (what pins it lives in tests/test_oracle_*.py):
+
+* head_entropy      pinned: closed-form spectra, isotropic / rank-1 closed
+                    forms, 2x2 analytic eigenvalues, Lemma-4 bounds, invariances.
+* assign_budgets    head budgets pinned by the paper's printed budget vectors
+                    (Sec. 4.2 "Main Results"; App. "Number of Head Groups" table).
+                    layer_group / layer_tokens: PARITY UNPINNED (the paper prints
+                    no worked example for Eq. 8-10; only the arithmetic of the
+                    reading below is checked, by a hand-worked case).
+* window_score      pinned: uniform-attention closed form (causal harmonic sums),
+                    single-row reduction to a library softmax, probability-mass
+                    conservation, spike -> plateau behaviour of the max-pool.
+* select_gather     pinned: exhaustive subset search on tiny inputs, structural
+                    invariants, byte compare of gathered rows.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+# Flag bits (same numeric values as the C header so tests can pass one integer
+# to both sides; the values are interface, not arithmetic).
+FLAG_CENTER = 1          # Eq. 1 centred covariance (otherwise X^T X, as in the proof of Lemma 3)
+FLAG_TRUNC_RENORM = 2    # renormalise the top-k eigenvalues to sum to one
+FLAG_LAYER_DELTA_INCREASE = 4  # Alg. 2 sign for the layer partition instead of Eq. 8
+DEFAULT_FLAGS = FLAG_CENTER | FLAG_TRUNC_RENORM
+
+
+# --------------------------------------------------------------------------
+# O1  truncated matrix entropy  (Sec. 3.1 Eq. 1, Lemma 2; Sec. 3.2 Eq. 5-6;
+#     trace-one normalisation from the proof of Lemma 4)
+# --------------------------------------------------------------------------
+def covariance(X: np.ndarray, center: bool = True) -> np.ndarray:
+    """Sec. 3.1 Eq. 1: Sigma = 1/(N-1) sum_i (x_i - xbar)(x_i - xbar)^T for the
+    token matrix X (N rows = tokens, D columns).  With ``center=False`` the
+    uncentred form X^T X/(N-1) used in the proof of Lemma 3.  N < 2 gives the
+    zero matrix (no spread can be measured from one token)."""
+    X = np.asarray(X, dtype=np.float64)
+    N, D = X.shape
+    if N < 2:
+        return np.zeros((D, D))
+    if center:
+        xbar = X.mean(axis=0)
+        Xc = X - xbar
+    else:
+        Xc = X
+    return (Xc.T @ Xc) / (N - 1)
+
+
+def spectrum(Sigma: np.ndarray) -> np.ndarray:
+    """Eigenvalues of Sigma scaled to unit trace (proof of Lemma 4: Tr Sigma = 1),
+    sorted descending; rounding negatives are clamped to zero.  A zero matrix
+    returns all zeros."""
+    lam = np.linalg.eigvalsh(np.asarray(Sigma, dtype=np.float64))[::-1].copy()
+    lam[lam < 0.0] = 0.0
+    tr = lam.sum()
+    if tr <= 0.0:
+        return np.zeros_like(lam)
+    return lam / tr
+
+
+def truncated_entropy(p: np.ndarray, k: int, renorm: bool = True) -> float:
+    """Sec. 3.2 Eq. 5: H_k = - sum_{i<=k} s_i log s_i over the k largest
+    eigenvalues (natural log; 0 log 0 = 0).  ``p`` is the unit-trace spectrum,
+    descending.  renorm=True: s_i = p_i / sum_{j<=k} p_j (the top-k block treated
+    as a density of its own, so the bound H_k <= log k of Lemma 4 is attained by
+    an isotropic matrix); renorm=False: s_i = p_i, Eq. 5 symbol for symbol."""
+    k = int(min(k, p.shape[0]))
+    s = np.asarray(p[:k], dtype=np.float64)
+    if renorm:
+        tot = s.sum()
+        if tot <= 0.0:
+            return 0.0
+        s = s / tot
+    s = s[s > 0.0]
+    return float(-(s * np.log(s)).sum())
+
+
+def head_entropy(X: np.ndarray, k_trunc: int = 32, flags: int = DEFAULT_FLAGS):
+    """Truncated matrix entropy of each token matrix in X [n_mat, N, D].
+    Returns (H [n_mat] float64, eig [n_mat, D] unit-trace spectrum descending).
+    erank_k = exp(H) (Eq. 6)."""
+    X = np.asarray(X, dtype=np.float64)
+    n_mat, N, D = X.shape
+    H = np.zeros(n_mat)
+    eig = np.zeros((n_mat, D))
+    for m in range(n_mat):
+        p = spectrum(covariance(X[m], center=bool(flags & FLAG_CENTER)))
+        eig[m] = p
+        H[m] = truncated_entropy(p, k_trunc, renorm=bool(flags & FLAG_TRUNC_RENORM))
+    return H, eig
+
+
+# --------------------------------------------------------------------------
+# O2  budgets  (Sec. 3.3.3 "Design", Eq. 11; Sec. 3.3.2 Eq. 8-10)
+# --------------------------------------------------------------------------
+def assign_budgets(entropy, M: int, n_max: int, step: int, N: int, w: int,
+                   eps: float, delta_n: int, flags: int = DEFAULT_FLAGS):
+    """entropy [L, B, H] (the float32 values the entropy stage emitted; they are
+    widened to float64 here, so both sides rank the same numbers).
+
+    Head budgets, per (layer, batch): heads are ranked by truncated entropy,
+    largest first (ties: lower head index first), cut into M groups of H/M heads
+    in rank order, and group g (0-based) gets N_{i,1} - g*step tokens (Eq. 11:
+    an arithmetic progression starting from n_max for the highest-entropy
+    group), clamped to [min(w, N), N].
+
+    Layer stages: e_l = mean over (b, h) of erank_k = exp(H); walking the layers,
+    a new compression stage starts after layer l when e_l - e_{l+1} > eps
+    (Eq. 8-9; with FLAG_LAYER_DELTA_INCREASE the sign of Alg. 2's prefill test,
+    e_{l+1} - e_l > eps).  layer_group[l] = number of boundaries before l;
+    layer_tokens[l] = max(N - layer_group[l]*delta_n, w): the first stage keeps
+    all tokens, each later stage delta_n fewer (Eq. 10 read so that it
+    compresses).  Returns int32 arrays head_budget [L,B,H], head_group [L,B,H],
+    layer_group [L], layer_tokens [L]."""
+    e = np.asarray(entropy, dtype=np.float32).astype(np.float64)
+    L, B, H = e.shape
+    assert H % M == 0
+    per = H // M
+    head_budget = np.zeros((L, B, H), dtype=np.int32)
+    head_group = np.zeros((L, B, H), dtype=np.int32)
+    lo = min(w, N)
+    for l in range(L):
+        for b in range(B):
+            order = sorted(range(H), key=lambda h: (-e[l, b, h], h))
+            for rank, h in enumerate(order):
+                g = rank // per
+                head_group[l, b, h] = g
+                head_budget[l, b, h] = min(max(n_max - g * step, lo), N)
+    erank = np.exp(e)
+    layer_mean = np.array([erank[l].sum() / (B * H) for l in range(L)])
+    layer_group = np.zeros(L, dtype=np.int32)
+    layer_tokens = np.zeros(L, dtype=np.int32)
+    c = 0
+    for l in range(L):
+        if l > 0:
+            d = layer_mean[l - 1] - layer_mean[l]
+            if flags & FLAG_LAYER_DELTA_INCREASE:
+                d = -d
+            if d > eps:
+                c += 1
+        layer_group[l] = c
+        layer_tokens[l] = max(N - c * delta_n, w)
+    return head_budget, head_group, layer_group, layer_tokens
+
+
+# --------------------------------------------------------------------------
+# O3  observation-window score  (Sec. 3.3.3 "Dynamic KV Cache Eviction":
+#     sum of the attention of the last l tokens; pooling and GQA group sum are
+#     the benchmark's statement of the scoring step)
+# --------------------------------------------------------------------------
+def window_score(Qwin: np.ndarray, K: np.ndarray, G: int, pool: int) -> np.ndarray:
+    """Qwin [B, Hq, w, D] are the queries of the last w positions, K [B, H, N, D]
+    all keys (Hq = G*H, query head q reads KV head q // G).  For window row i at
+    position P+i (P = N-w) the attention row is softmax_j(q_i . k_j / sqrt(D))
+    over the causal range j <= P+i.  vote_q[j] = sum_i p_ij for prefix tokens
+    j < P; pooled_q[j] = max of vote_q over the |j'-j| <= pool//2 neighbours that
+    lie inside the prefix; score[b,h,j] = sum of pooled_q over the G query heads
+    of KV head h.  Returns [B, H, P] float64."""
+    Qwin = np.asarray(Qwin, dtype=np.float64)
+    K = np.asarray(K, dtype=np.float64)
+    B, Hq, w, D = Qwin.shape
+    _, H, N, _ = K.shape
+    assert Hq == G * H and pool % 2 == 1 and 0 < w < N
+    P = N - w
+    half = pool // 2
+    score = np.zeros((B, H, P))
+    for b in range(B):
+        for q in range(Hq):
+            h = q // G
+            logits = (Qwin[b, q] @ K[b, h].T) / np.sqrt(D)      # [w, N]
+            vote = np.zeros(P)
+            for i in range(w):
+                row = logits[i, : P + i + 1]
+                ex = np.exp(row - row.max())
+                prob = ex / ex.sum()
+                vote += prob[:P]
+            pooled = np.empty(P)
+            for j in range(P):
+                pooled[j] = vote[max(0, j - half): min(P, j + half + 1)].max()
+            score[b, h] += pooled
+    return score
+
+
+# --------------------------------------------------------------------------
+# O4  per-head top-k and compaction  (Sec. 3.3.3: keep the N_{i,g} tokens with
+#     the highest scores; Alg. 2 prefill: compress each head by its group)
+# --------------------------------------------------------------------------
+def select_indices(score_row: np.ndarray, budget: int, N: int, w: int) -> np.ndarray:
+    """Kept positions of one head, ascending.  The w window positions are always
+    kept and count towards the budget; the remaining budget-w slots go to the
+    prefix tokens of largest score, equal scores resolved towards the lower
+    position.  budget is clamped to [min(w,N), N]; if it is below w only the last
+    ``budget`` positions survive."""
+    P = N - w
+    budget = int(min(max(int(budget), min(w, N)), N))
+    keep_prefix = min(max(budget - w, 0), P)
+    order = np.argsort(-np.asarray(score_row, dtype=np.float64), kind="stable")
+    chosen = np.sort(order[:keep_prefix])
+    n_win = min(budget, w)
+    window = np.arange(N - n_win, N)
+    return np.concatenate([chosen, window]).astype(np.int32)
+
+
+def select_gather(score, budget, K, V, w: int, cap: int):
+    """score [B,H,P], budget [B,H] int, K/V [B,H,N,D] (any dtype; rows are copied
+    verbatim).  Returns K_out, V_out [B,H,cap,D] (rows >= len zero), idx
+    [B,H,cap] int32 (entries >= len are -1), length [B,H] int32."""
+    B, H, N, D = K.shape
+    K_out = np.zeros((B, H, cap, D), dtype=K.dtype)
+    V_out = np.zeros((B, H, cap, D), dtype=V.dtype)
+    idx = np.full((B, H, cap), -1, dtype=np.int32)
+    length = np.zeros((B, H), dtype=np.int32)
+    for b in range(B):
+        for h in range(H):
+            sel = select_indices(score[b, h], budget[b, h], N, w)
+            n = sel.shape[0]
+            assert n <= cap
+            length[b, h] = n
+            idx[b, h, :n] = sel
+            for r in range(n):
+                K_out[b, h, r] = K[b, h, sel[r]]
+                V_out[b, h, r] = V[b, h, sel[r]]
+    return K_out, V_out, idx, length
