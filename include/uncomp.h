@@ -1,0 +1,160 @@
+/*
+ * libuncomp -- UNComp's prefill-time KV-cache compression pass for AMD MI355X (gfx950).
+ *
+ * Four hot calls, in the order a caller enqueues them on one HIP stream:
+ *
+ *   uncomp_head_entropy    truncated matrix entropy of every token matrix
+ *   uncomp_assign_budgets  entropies -> per-head token budgets and per-layer stages
+ *   uncomp_window_score    observation-window attention score of every prefix token
+ *   uncomp_select_gather   per-head top-k of the scores, compaction of K and V
+ *
+ * Conventions that hold for every call:
+ *   - Pointers named X, K, V, Qwin, *_out, entropy, score, budget are DEVICE pointers
+ *     owned by the caller; the library never allocates, frees or keeps them.  The
+ *     context, stride arrays and strings are HOST memory.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only
+ *     enqueue work on it and never synchronise; outputs are valid once the stream has
+ *     reached the end of the call's work.
+ *   - All temporary device memory comes from the context's workspace, allocated once in
+ *     uncomp_create.  A call that needs more returns UNCOMP_ERR_WORKSPACE and launches
+ *     nothing.  One context serves one stream at a time (calls on it share the workspace).
+ *   - Arguments are validated on the host before anything is launched; a failing call
+ *     returns a negative status, launches nothing and leaves outputs untouched.
+ *     uncomp_last_error gives a one-line reason.
+ *   - Supported: D == 128; dtype bf16 or fp32; 1 <= k_trunc; pool odd, 1 <= pool <= 15;
+ *     0 < w < N; M >= 1 dividing H.  Anything else is UNCOMP_ERR_UNSUPPORTED.
+ */
+#ifndef UNCOMP_H
+#define UNCOMP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct uncomp_ctx uncomp_ctx;
+
+typedef enum {
+    UNCOMP_OK = 0,
+    UNCOMP_ERR_INVALID_ARG = -1,  /* NULL pointer, non-positive size, inconsistent sizes */
+    UNCOMP_ERR_UNSUPPORTED = -2,  /* a value outside the supported set listed above      */
+    UNCOMP_ERR_WORKSPACE = -3,    /* the context's workspace is too small for this call  */
+    UNCOMP_ERR_HIP = -4           /* a HIP runtime call failed (text in uncomp_last_error) */
+} uncomp_status;
+
+typedef enum { UNCOMP_BF16 = 0, UNCOMP_F32 = 1 } uncomp_dtype;
+
+enum {
+    /* Sec. 3.1 Eq. 1: subtract the mean token before forming the covariance.  Without
+     * it the uncentred form X^T X/(N-1) from the proof of Lemma 3 is used.             */
+    UNCOMP_CENTER = 1u,
+    /* Sec. 3.2 Eq. 5 summed over the top-k eigenvalues after rescaling THEM to sum to
+     * one (so an isotropic matrix reaches the bound H_k = log k of Lemma 4).  Without
+     * it the eigenvalues keep their share of the full unit trace, Eq. 5 as printed.    */
+    UNCOMP_TRUNC_RENORM = 2u,
+    /* Layer partition: count a boundary where erank rises by more than eps (the test in
+     * Alg. 2's prefill loop) instead of where it falls by more than eps (Eq. 8-9).     */
+    UNCOMP_LAYER_DELTA_INCREASE = 4u
+};
+#define UNCOMP_DEFAULT_FLAGS (UNCOMP_CENTER | UNCOMP_TRUNC_RENORM)
+
+/* Creates a context on HIP device `device` with `workspace_bytes` of device scratch
+ * (0 = a default of 64 MiB).  Sets *ctx_out; the caller destroys it with uncomp_destroy. */
+uncomp_status uncomp_create(uncomp_ctx** ctx_out, int device, size_t workspace_bytes);
+uncomp_status uncomp_destroy(uncomp_ctx* ctx);
+
+/* Workspace (bytes) that one round of the four calls needs for the given problem:
+ * n_mat token matrices of N rows in uncomp_head_entropy, and B*H KV heads with G query
+ * heads each in uncomp_window_score / uncomp_select_gather.  Pass 0 for a call that will
+ * not be made with this context. */
+size_t uncomp_workspace_bytes(int n_mat, int N, int D, int B, int H, int G, int w);
+
+/* Host string describing the last failing call on this context (never NULL, owned by
+ * the context, valid until the next call on it). */
+const char* uncomp_last_error(const uncomp_ctx* ctx);
+
+/*
+ * Truncated matrix entropy (Sec. 3.1 Eq. 1 and Lemma 2; Sec. 3.2 Eq. 5-6; unit trace as
+ * in the proof of Lemma 4).
+ *
+ * X holds n_mat token matrices; matrix m starts at element m*mat_stride, its token t at
+ * element t*ldx further on, and the D features of a token are contiguous.  For each
+ * matrix: covariance over the N tokens (centred unless UNCOMP_CENTER is cleared), scaled
+ * to unit trace; eigenvalues sigma_1 >= ... >= sigma_D (negatives from rounding clamped to
+ * zero); entropy_out[m] = - sum_{i <= min(k_trunc, D)} s_i ln s_i with s_i per
+ * UNCOMP_TRUNC_RENORM; 0 ln 0 = 0; a zero covariance (e.g. N == 1) gives 0.
+ * erank_k = exp(entropy).  eig_out, if not NULL, receives the D unit-trace eigenvalues of
+ * each matrix in descending order ([n_mat][D] floats).
+ * Requires ldx >= D, ldx and mat_stride multiples of 8 elements, X 16-byte aligned.
+ */
+uncomp_status uncomp_head_entropy(uncomp_ctx* ctx, const void* X, uncomp_dtype dtype,
+                                  int n_mat, int N, int D, int64_t mat_stride, int64_t ldx,
+                                  int k_trunc, unsigned flags,
+                                  float* entropy_out, float* eig_out, void* stream);
+
+/*
+ * Budgets from entropies (Sec. 3.3.3 "Design", Eq. 11; Sec. 3.3.2 Eq. 8-10).
+ *
+ * entropy is [n_layer][n_batch][H] floats.  Per (layer, batch): heads are ranked by entropy,
+ * largest first, equal values by lower head index; rank r falls in group g = r / (H/M);
+ * head_budget = clamp(n_max - g*step, min(w, N), N)  (n_max is N_{i,1}, step is Delta n_g).
+ * Per layer: e_l = mean over batch and heads of exp(entropy), evaluated in double
+ * precision; stage counter c_0 = 0, c_{l} = c_{l-1} + [e_{l-1} - e_l > eps] (sign flipped
+ * under UNCOMP_LAYER_DELTA_INCREASE); layer_group[l] = c_l;
+ * layer_tokens[l] = max(N - c_l*delta_n, w).
+ * Outputs (device, int32): head_budget and head_group [n_layer][n_batch][H];
+ * layer_group and layer_tokens [n_layer] (either pair may be NULL to skip it).
+ * Limits: H <= 1024, n_layer <= 4096.
+ */
+uncomp_status uncomp_assign_budgets(uncomp_ctx* ctx, const float* entropy,
+                                    int n_layer, int n_batch, int H, int M,
+                                    int n_max, int step, int N, int w,
+                                    float eps, int delta_n, unsigned flags,
+                                    int32_t* head_budget, int32_t* head_group,
+                                    int32_t* layer_group, int32_t* layer_tokens, void* stream);
+
+/*
+ * Observation-window score (Sec. 3.3.3 "Dynamic KV Cache Eviction": the attention the last
+ * w tokens pay to each earlier token, summed; followed by a 1-D max-pool over token
+ * positions and a sum over the G query heads that share a KV head).
+ *
+ * Qwin [B][H*G][w][D] dense: the queries at positions P..N-1, P = N - w; query head q reads
+ * KV head q / G.  K: head (b,h) starts at element b*k_strides[0] + h*k_strides[1], token t at
+ * t*k_strides[2] further on, features contiguous.  For window row i (position P+i):
+ * p_ij = softmax over the causal range j <= P+i of q_i . k_j / sqrt(D), in fp32;
+ * vote_q[j] = sum_i p_ij for j < P; pooled_q[j] = max of vote_q over |j' - j| <= pool/2,
+ * 0 <= j' < P; score_out[b][h][j] = sum over the G query heads of pooled_q[j], j in [0, P).
+ * score_out is dense [B][H][P] floats.  Strides are multiples of 8 elements, K and Qwin
+ * 16-byte aligned; G*w <= 512.
+ */
+uncomp_status uncomp_window_score(uncomp_ctx* ctx, const void* Qwin, const void* K,
+                                  uncomp_dtype dtype, int B, int H, int G, int N, int D,
+                                  int w, int pool, const int64_t k_strides[3],
+                                  float* score_out, void* stream);
+
+/*
+ * Per-head top-k and compaction (Sec. 3.3.3: keep the N_{i,g} highest-scoring tokens;
+ * Alg. 2 prefill: compress each head's KV by its group's budget).
+ *
+ * score [B][H][P] floats, no NaNs (P = N - w), budget [B][H] int32 (device).  Per head:
+ * b = clamp(budget, w, min(N, cap)); the b - w prefix positions of largest score are
+ * kept, equal scores by lower position, followed by the w window positions.
+ * idx_out[b][h][0..len) lists the kept positions in ascending order, len_out[b][h] = b;
+ * K_out/V_out[b][h][r][:] = K/V[b][h][idx[r]][:] copied bit for bit.  Rows and indices at
+ * r >= len are left untouched.  K and V share kv_strides (element strides of batch, head,
+ * token; features contiguous); outputs are dense [B][H][cap][D] / [B][H][cap].
+ * Requires w <= cap.  K/V/K_out/V_out may be NULL together to obtain indices only.
+ */
+uncomp_status uncomp_select_gather(uncomp_ctx* ctx, const float* score, const int32_t* budget,
+                                   const void* K, const void* V, uncomp_dtype dtype,
+                                   int B, int H, int N, int D, int w,
+                                   const int64_t kv_strides[3], int cap,
+                                   void* K_out, void* V_out, int32_t* idx_out, int32_t* len_out,
+                                   void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* UNCOMP_H */

@@ -1,0 +1,189 @@
+"""ctypes binding of libuncomp: argument marshalling only.
+
+Each function takes torch CUDA tensors, passes their device pointers, sizes and
+strides to the C entry point of the same name and launches on torch's current
+stream.  All arithmetic happens in the HIP kernels; if the shared library has
+not been built this module raises at import of the library (there is no
+fallback path).
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libuncomp.so")
+
+OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = 0, -1, -2, -3, -4
+BF16, F32 = 0, 1
+CENTER, TRUNC_RENORM, LAYER_DELTA_INCREASE = 1, 2, 4
+DEFAULT_FLAGS = CENTER | TRUNC_RENORM
+
+EXPORTS = (
+    "uncomp_create", "uncomp_destroy", "uncomp_workspace_bytes", "uncomp_last_error",
+    "uncomp_head_entropy", "uncomp_assign_budgets", "uncomp_window_score", "uncomp_select_gather",
+)
+
+_lib = None
+
+
+class UncompError(RuntimeError):
+    def __init__(self, status: int, msg: str):
+        super().__init__(f"libuncomp status {status}: {msg}")
+        self.status = status
+
+
+def load_library() -> ctypes.CDLL:
+    """Loads libuncomp.so from the package directory; raises if it is missing."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            f"{LIB_PATH} not found: build it with `python -m paper_2410_03090_amd.build` "
+            "(there is no non-HIP implementation to fall back to)")
+    lib = ctypes.CDLL(LIB_PATH)
+    c = ctypes
+    vp, i32, i64, u32, f32 = c.c_void_p, c.c_int, c.c_int64, c.c_uint, c.c_float
+    lib.uncomp_create.argtypes = [c.POINTER(vp), i32, c.c_size_t]
+    lib.uncomp_create.restype = i32
+    lib.uncomp_destroy.argtypes = [vp]
+    lib.uncomp_destroy.restype = i32
+    lib.uncomp_workspace_bytes.argtypes = [i32] * 7
+    lib.uncomp_workspace_bytes.restype = c.c_size_t
+    lib.uncomp_last_error.argtypes = [vp]
+    lib.uncomp_last_error.restype = c.c_char_p
+    lib.uncomp_head_entropy.argtypes = [vp, vp, i32, i32, i32, i32, i64, i64, i32, u32, vp, vp, vp]
+    lib.uncomp_head_entropy.restype = i32
+    lib.uncomp_assign_budgets.argtypes = [vp, vp, i32, i32, i32, i32, i32, i32, i32, i32, f32, i32, u32,
+                                          vp, vp, vp, vp, vp]
+    lib.uncomp_assign_budgets.restype = i32
+    lib.uncomp_window_score.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, i32,
+                                        c.POINTER(i64), vp, vp]
+    lib.uncomp_window_score.restype = i32
+    lib.uncomp_select_gather.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32,
+                                         c.POINTER(i64), i32, vp, vp, vp, vp, vp]
+    lib.uncomp_select_gather.restype = i32
+    _lib = lib
+    return lib
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.bfloat16:
+        return BF16
+    if t.dtype == torch.float32:
+        return F32
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _ptr(t):
+    return None if t is None else t.data_ptr()
+
+
+class Context:
+    """Owns one uncomp_ctx (device workspace).  ``workspace_bytes=0`` takes the library default."""
+
+    def __init__(self, device: int = 0, workspace_bytes: int = 0):
+        self.lib = load_library()
+        h = ctypes.c_void_p()
+        st = self.lib.uncomp_create(ctypes.byref(h), int(device), int(workspace_bytes))
+        if st != OK:
+            raise UncompError(st, "uncomp_create failed")
+        self.handle = h
+        self.device = device
+
+    @staticmethod
+    def workspace_bytes(n_mat: int, N: int, D: int, B: int, H: int, G: int, w: int) -> int:
+        return int(load_library().uncomp_workspace_bytes(n_mat, N, D, B, H, G, w))
+
+    def close(self):
+        if getattr(self, "handle", None) is not None and self.handle:
+            self.lib.uncomp_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _check(self, st: int):
+        if st != OK:
+            raise UncompError(st, self.lib.uncomp_last_error(self.handle).decode())
+
+    # -- the four hot calls ------------------------------------------------------------
+    def head_entropy(self, X: torch.Tensor, k_trunc: int = 32, flags: int = DEFAULT_FLAGS,
+                     want_eig: bool = False, entropy_out=None, eig_out=None):
+        """X [n_mat, N, D] (last dim contiguous).  Returns entropy [n_mat] (and eig [n_mat, D])."""
+        n_mat, N, D = X.shape
+        assert X.stride(2) == 1
+        if entropy_out is None:
+            entropy_out = torch.empty(n_mat, dtype=torch.float32, device=X.device)
+        if want_eig and eig_out is None:
+            eig_out = torch.empty(n_mat, D, dtype=torch.float32, device=X.device)
+        self._check(self.lib.uncomp_head_entropy(
+            self.handle, X.data_ptr(), _dtype_code(X), n_mat, N, D, X.stride(0), X.stride(1),
+            int(k_trunc), int(flags), entropy_out.data_ptr(), _ptr(eig_out), _stream()))
+        return (entropy_out, eig_out) if want_eig else entropy_out
+
+    def assign_budgets(self, entropy: torch.Tensor, M: int, n_max: int, step: int, N: int, w: int,
+                       eps: float = 0.4, delta_n: int = 512, flags: int = DEFAULT_FLAGS, out=None):
+        """entropy [L, B, H] float32.  Returns head_budget, head_group [L,B,H], layer_group, layer_tokens [L]."""
+        L, B, H = entropy.shape
+        assert entropy.is_contiguous() and entropy.dtype == torch.float32
+        if out is None:
+            kw = dict(dtype=torch.int32, device=entropy.device)
+            out = (torch.empty(L, B, H, **kw), torch.empty(L, B, H, **kw),
+                   torch.empty(L, **kw), torch.empty(L, **kw))
+        hb, hg, lg, lt = out
+        self._check(self.lib.uncomp_assign_budgets(
+            self.handle, entropy.data_ptr(), L, B, H, int(M), int(n_max), int(step), int(N), int(w),
+            float(eps), int(delta_n), int(flags), _ptr(hb), _ptr(hg), _ptr(lg), _ptr(lt), _stream()))
+        return hb, hg, lg, lt
+
+    def window_score(self, Qwin: torch.Tensor, K: torch.Tensor, G: int, pool: int = 7, out=None):
+        """Qwin [B, H*G, w, D] contiguous, K [B, H, N, D] (last dim contiguous).  Returns score [B,H,N-w]."""
+        B, Hq, w, D = Qwin.shape
+        _, H, N, _ = K.shape
+        assert Qwin.is_contiguous() and K.stride(3) == 1 and Hq == H * G and Qwin.dtype == K.dtype
+        if out is None:
+            out = torch.empty(B, H, N - w, dtype=torch.float32, device=K.device)
+        strides = (ctypes.c_int64 * 3)(K.stride(0), K.stride(1), K.stride(2))
+        self._check(self.lib.uncomp_window_score(
+            self.handle, Qwin.data_ptr(), K.data_ptr(), _dtype_code(K), B, H, int(G), N, D, w, int(pool),
+            strides, out.data_ptr(), _stream()))
+        return out
+
+    def select_gather(self, score: torch.Tensor, budget: torch.Tensor, K, V, w: int, cap: int, out=None,
+                      N: int | None = None):
+        """score [B,H,N-w] float32, budget [B,H] int32, K/V [B,H,N,D] or None.
+        Returns K_out, V_out [B,H,cap,D] (None without K/V), idx [B,H,cap] int32, len [B,H] int32.
+        Fresh outputs are zero-filled (idx with -1) so rows past len are defined."""
+        B, H, P = score.shape
+        assert score.is_contiguous() and budget.is_contiguous() and budget.dtype == torch.int32
+        if K is not None:
+            N, D = K.shape[2], K.shape[3]
+            assert K.stride() == V.stride() and K.stride(3) == 1 and K.dtype == V.dtype
+            strides = (ctypes.c_int64 * 3)(K.stride(0), K.stride(1), K.stride(2))
+            code = _dtype_code(K)
+        else:
+            N, D = (P + w if N is None else N), 128
+            strides = None
+            code = BF16
+        if out is None:
+            dev = score.device
+            Ko = torch.zeros(B, H, cap, D, dtype=K.dtype, device=dev) if K is not None else None
+            Vo = torch.zeros(B, H, cap, D, dtype=V.dtype, device=dev) if K is not None else None
+            out = (Ko, Vo, torch.full((B, H, cap), -1, dtype=torch.int32, device=dev),
+                   torch.zeros(B, H, dtype=torch.int32, device=dev))
+        Ko, Vo, idx, ln = out
+        self._check(self.lib.uncomp_select_gather(
+            self.handle, score.data_ptr(), budget.data_ptr(), _ptr(K), _ptr(V), code, B, H, N, D, int(w),
+            strides, int(cap), _ptr(Ko), _ptr(Vo), idx.data_ptr(), ln.data_ptr(), _stream()))
+        return Ko, Vo, idx, ln

@@ -1,0 +1,200 @@
+// C interface of libuncomp: argument checks, workspace carving and kernel launches.
+// Every entry point validates on the host, launches on the caller's stream and returns a
+// status; nothing here synchronises or allocates after uncomp_create.
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+
+#include "common.h"
+
+using namespace uncomp;
+
+namespace {
+
+uncomp_status fail(uncomp_ctx* ctx, uncomp_status st, const char* fmt, ...) {
+    if (ctx != nullptr) {
+        va_list ap;
+        va_start(ap, fmt);
+        vsnprintf(ctx->err, sizeof(ctx->err), fmt, ap);
+        va_end(ap);
+    }
+    return st;
+}
+
+uncomp_status hip_fail(uncomp_ctx* ctx, hipError_t e, const char* what) {
+    return fail(ctx, UNCOMP_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+constexpr size_t kDefaultWorkspace = 64ull << 20;
+constexpr size_t kBudgetScratch = 4096 * sizeof(double);
+
+}  // namespace
+
+extern "C" {
+
+uncomp_status uncomp_create(uncomp_ctx** ctx_out, int device, size_t workspace_bytes) {
+    if (ctx_out == nullptr) return UNCOMP_ERR_INVALID_ARG;
+    *ctx_out = nullptr;
+    int n_dev = 0;
+    hipError_t e = hipGetDeviceCount(&n_dev);
+    if (e != hipSuccess || device < 0 || device >= n_dev) return UNCOMP_ERR_INVALID_ARG;
+    uncomp_ctx* ctx = new (std::nothrow) uncomp_ctx();
+    if (ctx == nullptr) return UNCOMP_ERR_HIP;
+    ctx->device = device;
+    ctx->err[0] = 0;
+    ctx->ws = nullptr;
+    ctx->ws_bytes = workspace_bytes == 0 ? kDefaultWorkspace : align_up(workspace_bytes, 256);
+    if (ctx->ws_bytes < kBudgetScratch) ctx->ws_bytes = kBudgetScratch;
+    int prev = 0;
+    (void)hipGetDevice(&prev);
+    e = hipSetDevice(device);
+    hipDeviceProp_t prop;
+    if (e == hipSuccess) e = hipGetDeviceProperties(&prop, device);
+    if (e == hipSuccess) {
+        ctx->num_cu = prop.multiProcessorCount;
+        e = hipMalloc(reinterpret_cast<void**>(&ctx->ws), ctx->ws_bytes);
+    }
+    (void)hipSetDevice(prev);
+    if (e != hipSuccess) {
+        delete ctx;
+        return UNCOMP_ERR_HIP;
+    }
+    *ctx_out = ctx;
+    return UNCOMP_OK;
+}
+
+uncomp_status uncomp_destroy(uncomp_ctx* ctx) {
+    if (ctx == nullptr) return UNCOMP_ERR_INVALID_ARG;
+    hipError_t e = hipSuccess;
+    if (ctx->ws != nullptr) e = hipFree(ctx->ws);
+    delete ctx;
+    return e == hipSuccess ? UNCOMP_OK : UNCOMP_ERR_HIP;
+}
+
+size_t uncomp_workspace_bytes(int n_mat, int N, int D, int B, int H, int G, int w) {
+    (void)D;
+    size_t need = kBudgetScratch;
+    if (n_mat > 0 && N > 0) {
+        size_t b = plan_entropy(n_mat, N).bytes;
+        if (b > need) need = b;
+    }
+    if (B > 0 && H > 0 && G > 0 && N > 0 && w > 0 && w < N) {
+        size_t b = plan_score(B, H, G, N, w).bytes;
+        if (b > need) need = b;
+    }
+    return need;
+}
+
+const char* uncomp_last_error(const uncomp_ctx* ctx) { return ctx != nullptr ? ctx->err : "null context"; }
+
+uncomp_status uncomp_head_entropy(uncomp_ctx* ctx, const void* X, uncomp_dtype dtype, int n_mat,
+                                  int N, int D, int64_t mat_stride, int64_t ldx, int k_trunc,
+                                  unsigned flags, float* entropy_out, float* eig_out, void* stream) {
+    if (ctx == nullptr) return UNCOMP_ERR_INVALID_ARG;
+    if (X == nullptr || entropy_out == nullptr) return fail(ctx, UNCOMP_ERR_INVALID_ARG, "head_entropy: null pointer");
+    if (n_mat <= 0 || N <= 0) return fail(ctx, UNCOMP_ERR_INVALID_ARG, "head_entropy: n_mat and N must be positive");
+    if (dtype != UNCOMP_BF16 && dtype != UNCOMP_F32) return fail(ctx, UNCOMP_ERR_UNSUPPORTED, "head_entropy: dtype");
+    if (D != kD) return fail(ctx, UNCOMP_ERR_UNSUPPORTED, "head_entropy: D must be 128");
+    if (k_trunc < 1) return fail(ctx, UNCOMP_ERR_UNSUPPORTED, "head_entropy: k_trunc must be >= 1");
+    if (flags & ~(UNCOMP_CENTER | UNCOMP_TRUNC_RENORM | UNCOMP_LAYER_DELTA_INCREASE))
+        return fail(ctx, UNCOMP_ERR_UNSUPPORTED, "head_entropy: unknown flag bits");
+    if (ldx < D || (ldx & 7) || (mat_stride & 7) || mat_stride < 0 || !aligned16(X))
+        return fail(ctx, UNCOMP_ERR_INVALID_ARG, "head_entropy: strides must be multiples of 8 elements, ldx >= D, X 16-byte aligned");
+    if ((int64_t)n_mat * 64 > 0x7fffffffLL) return fail(ctx, UNCOMP_ERR_UNSUPPORTED, "head_entropy: too many matrices");
+    EntropyPlan p = plan_entropy(n_mat, N);
+    if (p.bytes > ctx->ws_bytes)
+        return fail(ctx, UNCOMP_ERR_WORKSPACE, "head_entropy: needs %zu workspace bytes, context has %zu", p.bytes, ctx->ws_bytes);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipError_t e = launch_gram(X, dtype, n_mat, N, mat_stride, ldx, p, ctx->ws, s);
+    if (e != hipSuccess) return hip_fail(ctx, e, "head_entropy: gram launch");
+    e = launch_jacobi_entropy(n_mat, N, k_trunc, flags, p, ctx->ws, entropy_out, eig_out, s);
+    if (e != hipSuccess) return hip_fail(ctx, e, "head_entropy: eigen launch");
+    return UNCOMP_OK;
+}
+
+uncomp_status uncomp_assign_budgets(uncomp_ctx* ctx, const float* entropy, int n_layer, int n_batch,
+                                    int H, int M, int n_max, int step, int N, int w, float eps,
+                                    int delta_n, unsigned flags, int32_t* head_budget,
+                                    int32_t* head_group, int32_t* layer_group, int32_t* layer_tokens,
+                                    void* stream) {
+    if (ctx == nullptr) return UNCOMP_ERR_INVALID_ARG;
+    if (entropy == nullptr) return fail(ctx, UNCOMP_ERR_INVALID_ARG, "assign_budgets: null entropy");
+    if ((head_budget == nullptr) != (head_group == nullptr) || (layer_group == nullptr) != (layer_tokens == nullptr))
+        return fail(ctx, UNCOMP_ERR_INVALID_ARG, "assign_budgets: outputs come in pairs");
+    if (head_budget == nullptr && layer_group == nullptr)
+        return fail(ctx, UNCOMP_ERR_INVALID_ARG, "assign_budgets: no output requested");
+    if (n_layer <= 0 || n_batch <= 0 || H <= 0 || N <= 0)
+        return fail(ctx, UNCOMP_ERR_INVALID_ARG, "assign_budgets: sizes must be positive");
+    if (H > 1024 || n_layer > 4096) return fail(ctx, UNCOMP_ERR_UNSUPPORTED, "assign_budgets: H <= 1024, n_layer <= 4096");
+    if (M < 1 || H % M != 0) return fail(ctx, UNCOMP_ERR_UNSUPPORTED, "assign_budgets: M must divide H");
+    if (w <= 0 || w >= N) return fail(ctx, UNCOMP_ERR_UNSUPPORTED, "assign_budgets: need 0 < w < N");
+    if (step < 0 || delta_n < 0 || n_max < 0) return fail(ctx, UNCOMP_ERR_INVALID_ARG, "assign_budgets: negative n_max, step or delta_n");
+    if ((int64_t)n_layer * n_batch * H > 0x7fffffffLL) return fail(ctx, UNCOMP_ERR_UNSUPPORTED, "assign_budgets: too many heads");
+    if (!(eps == eps)) return fail(ctx, UNCOMP_ERR_INVALID_ARG, "assign_budgets: eps is NaN");
+    hipError_t e = launch_budgets(entropy, n_layer, n_batch, H, M, n_max, step, N, w, eps, delta_n, flags,
+                                  head_budget, head_group, layer_group, layer_tokens, ctx->ws,
+                                  static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return hip_fail(ctx, e, "assign_budgets: launch");
+    return UNCOMP_OK;
+}
+
+uncomp_status uncomp_window_score(uncomp_ctx* ctx, const void* Qwin, const void* K, uncomp_dtype dtype,
+                                  int B, int H, int G, int N, int D, int w, int pool,
+                                  const int64_t k_strides[3], float* score_out, void* stream) {
+    if (ctx == nullptr) return UNCOMP_ERR_INVALID_ARG;
+    if (Qwin == nullptr || K == nullptr || score_out == nullptr || k_strides == nullptr)
+        return fail(ctx, UNCOMP_ERR_INVALID_ARG, "window_score: null pointer");
+    if (B <= 0 || H <= 0 || G <= 0 || N <= 0) return fail(ctx, UNCOMP_ERR_INVALID_ARG, "window_score: sizes must be positive");
+    if (dtype != UNCOMP_BF16 && dtype != UNCOMP_F32) return fail(ctx, UNCOMP_ERR_UNSUPPORTED, "window_score: dtype");
+    if (D != kD) return fail(ctx, UNCOMP_ERR_UNSUPPORTED, "window_score: D must be 128");
+    if (w <= 0 || w >= N) return fail(ctx, UNCOMP_ERR_UNSUPPORTED, "window_score: need 0 < w < N");
+    if (pool < 1 || pool > 15 || (pool & 1) == 0) return fail(ctx, UNCOMP_ERR_UNSUPPORTED, "window_score: pool must be odd in [1,15]");
+    if ((int64_t)G * w > 512) return fail(ctx, UNCOMP_ERR_UNSUPPORTED, "window_score: G*w must be <= 512");
+    if (k_strides[2] < D || (k_strides[0] & 7) || (k_strides[1] & 7) || (k_strides[2] & 7) || k_strides[0] < 0 ||
+        k_strides[1] < 0 || !aligned16(K) || !aligned16(Qwin))
+        return fail(ctx, UNCOMP_ERR_INVALID_ARG, "window_score: strides must be multiples of 8 elements, token stride >= D, 16-byte aligned pointers");
+    if ((int64_t)B * H * ((N + 255) / 256) > 0x7fffffffLL) return fail(ctx, UNCOMP_ERR_UNSUPPORTED, "window_score: problem too large");
+    ScorePlan p = plan_score(B, H, G, N, w);
+    if (p.bytes > ctx->ws_bytes)
+        return fail(ctx, UNCOMP_ERR_WORKSPACE, "window_score: needs %zu workspace bytes, context has %zu", p.bytes, ctx->ws_bytes);
+    hipError_t e = launch_window_score(Qwin, K, dtype, B, H, G, N, w, pool, k_strides, p, ctx->ws, score_out,
+                                       static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return hip_fail(ctx, e, "window_score: launch");
+    return UNCOMP_OK;
+}
+
+uncomp_status uncomp_select_gather(uncomp_ctx* ctx, const float* score, const int32_t* budget, const void* K,
+                                   const void* V, uncomp_dtype dtype, int B, int H, int N, int D, int w,
+                                   const int64_t kv_strides[3], int cap, void* K_out, void* V_out,
+                                   int32_t* idx_out, int32_t* len_out, void* stream) {
+    if (ctx == nullptr) return UNCOMP_ERR_INVALID_ARG;
+    if (score == nullptr || budget == nullptr || idx_out == nullptr || len_out == nullptr)
+        return fail(ctx, UNCOMP_ERR_INVALID_ARG, "select_gather: null pointer");
+    const bool any_kv = K != nullptr || V != nullptr || K_out != nullptr || V_out != nullptr;
+    const bool all_kv = K != nullptr && V != nullptr && K_out != nullptr && V_out != nullptr;
+    if (any_kv && !all_kv) return fail(ctx, UNCOMP_ERR_INVALID_ARG, "select_gather: K, V, K_out, V_out must be given together");
+    if (B <= 0 || H <= 0 || N <= 0 || cap <= 0) return fail(ctx, UNCOMP_ERR_INVALID_ARG, "select_gather: sizes must be positive");
+    if (dtype != UNCOMP_BF16 && dtype != UNCOMP_F32) return fail(ctx, UNCOMP_ERR_UNSUPPORTED, "select_gather: dtype");
+    if (D != kD) return fail(ctx, UNCOMP_ERR_UNSUPPORTED, "select_gather: D must be 128");
+    if (w <= 0 || w >= N) return fail(ctx, UNCOMP_ERR_UNSUPPORTED, "select_gather: need 0 < w < N");
+    if (cap < w) return fail(ctx, UNCOMP_ERR_INVALID_ARG, "select_gather: cap must be >= w");
+    if (all_kv) {
+        if (kv_strides == nullptr) return fail(ctx, UNCOMP_ERR_INVALID_ARG, "select_gather: null strides");
+        if (kv_strides[2] < D || (kv_strides[0] & 7) || (kv_strides[1] & 7) || (kv_strides[2] & 7) ||
+            kv_strides[0] < 0 || kv_strides[1] < 0 || !aligned16(K) || !aligned16(V) || !aligned16(K_out) ||
+            !aligned16(V_out))
+            return fail(ctx, UNCOMP_ERR_INVALID_ARG, "select_gather: strides must be multiples of 8 elements, token stride >= D, 16-byte aligned pointers");
+    }
+    if ((int64_t)B * H * ((cap + 7) / 8) > 0x7fffffffLL) return fail(ctx, UNCOMP_ERR_UNSUPPORTED, "select_gather: problem too large");
+    static const int64_t zero_strides[3] = {0, 0, 0};
+    hipError_t e = launch_select_gather(score, budget, all_kv ? K : nullptr, V, dtype, B, H, N, w,
+                                        all_kv ? kv_strides : zero_strides, cap, K_out, V_out, idx_out, len_out,
+                                        static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return hip_fail(ctx, e, "select_gather: launch");
+    return UNCOMP_OK;
+}
+
+}  // extern "C"

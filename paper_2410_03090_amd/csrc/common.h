@@ -1,0 +1,68 @@
+// Shared host-side declarations of libuncomp: the context, the workspace planner and the
+// launchers implemented by the kernel files.  Not part of the public interface.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <hip/hip_bf16.h>
+#include <stdint.h>
+#include <stddef.h>
+
+#include "../../include/uncomp.h"
+
+struct uncomp_ctx {
+    int device;
+    int num_cu;
+    char* ws;            // device workspace
+    size_t ws_bytes;
+    char err[256];
+};
+
+namespace uncomp {
+
+constexpr int kD = 128;                 // head dimension all kernels are written for
+constexpr int kGramTile = 128;          // tokens a Gram workgroup folds per inner step
+constexpr int kJacobiLd = kD + 4;       // padded column stride of the LDS matrix (floats)
+constexpr int kMaxSweeps = 30;          // hard stop of the Jacobi iteration
+
+// ---- workspace planning (host) -------------------------------------------------------
+struct EntropyPlan {
+    int n_chunks;        // token chunks per matrix (split of the Gram sum)
+    int chunk;           // tokens per chunk (multiple of kGramTile)
+    size_t gram_off;     // float [n_mat][n_chunks][D*D]
+    size_t sum_off;      // float [n_mat][n_chunks][D]
+    size_t bytes;
+};
+EntropyPlan plan_entropy(int n_mat, int N);
+
+struct ScorePlan {
+    int R;               // query rows per KV head = G*w
+    int n_chunks;        // token chunks per head for the softmax-statistics pass
+    int chunk;           // tokens per chunk
+    size_t stats_off;    // float2 [BH][n_chunks][R]   (running max, running sum)
+    size_t lse_off;      // float  [BH][R]
+    size_t vote_off;     // float  [BH][G][P]
+    size_t bytes;
+};
+ScorePlan plan_score(int B, int H, int G, int N, int w);
+
+// ---- launchers (each returns the hipError_t of its launches) ---------------------------
+hipError_t launch_gram(const void* X, uncomp_dtype dt, int n_mat, int N, int64_t mat_stride,
+                       int64_t ldx, const EntropyPlan& p, char* ws, hipStream_t s);
+hipError_t launch_jacobi_entropy(int n_mat, int N, int k_trunc, unsigned flags,
+                                 const EntropyPlan& p, char* ws, float* entropy_out,
+                                 float* eig_out, hipStream_t s);
+hipError_t launch_budgets(const float* entropy, int L, int B, int H, int M, int n_max, int step,
+                          int N, int w, float eps, int delta_n, unsigned flags,
+                          int32_t* head_budget, int32_t* head_group, int32_t* layer_group,
+                          int32_t* layer_tokens, char* ws, hipStream_t s);
+hipError_t launch_window_score(const void* Q, const void* K, uncomp_dtype dt, int B, int H, int G,
+                               int N, int w, int pool, const int64_t ks[3], const ScorePlan& p,
+                               char* ws, float* score_out, hipStream_t s);
+hipError_t launch_select_gather(const float* score, const int32_t* budget, const void* K,
+                                const void* V, uncomp_dtype dt, int B, int H, int N, int w,
+                                const int64_t ks[3], int cap, void* K_out, void* V_out,
+                                int32_t* idx_out, int32_t* len_out, hipStream_t s);
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+}  // namespace uncomp

@@ -1,0 +1,51 @@
+// Device helpers shared by the kernel files: element loads for the two storage types and
+// wavefront-level reductions.  gfx950 only (64-wide wavefronts).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <hip/hip_bf16.h>
+#include <stdint.h>
+
+namespace uncomp {
+
+typedef uint16_t bf16_bits;   // storage of one bf16 element
+
+__device__ __forceinline__ float bf16_to_f32(bf16_bits v) {
+    return __uint_as_float(((uint32_t)v) << 16);
+}
+
+// Loads 8 consecutive elements starting at p (16-byte aligned for bf16, 32-byte for
+// fp32 by the interface's stride rules) and widens them to fp32.
+__device__ __forceinline__ void load8(const bf16_bits* p, float out[8]) {
+    uint4 raw = *reinterpret_cast<const uint4*>(p);
+    uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        out[2 * i] = __uint_as_float(w[i] << 16);
+        out[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+    }
+}
+__device__ __forceinline__ void load8(const float* p, float out[8]) {
+    float4 a = *reinterpret_cast<const float4*>(p);
+    float4 b = *reinterpret_cast<const float4*>(p + 4);
+    out[0] = a.x; out[1] = a.y; out[2] = a.z; out[3] = a.w;
+    out[4] = b.x; out[5] = b.y; out[6] = b.z; out[7] = b.w;
+}
+
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+    return v;
+}
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+__device__ __forceinline__ double wave_sum(double v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+
+}  // namespace uncomp

@@ -1,0 +1,203 @@
+// Per-head top-k and compaction (Sec. 3.3.3: each head keeps its N_{i,g} highest-scoring
+// tokens; Alg. 2 prefill: compress each head's KV by its group).
+//
+// select_kernel, one workgroup per (batch, head):
+//   - the k-th largest score is found exactly by a most-significant-digit radix select on
+//     an order-preserving 32-bit image of the float (digits of 11, 11 and 10 bits, one
+//     LDS histogram per digit);
+//   - one more ordered pass writes the kept positions in ascending order: everything above
+//     the threshold, and of the scores equal to it the first (k - #above) by position;
+//   - the w window positions follow.
+// gather_kernel then copies the kept rows of K and V, 16 bytes per lane.
+#include "common.h"
+#include "device_utils.h"
+
+namespace uncomp {
+
+namespace {
+
+constexpr int kSelThreads = 1024;
+constexpr int kSelWaves = kSelThreads / 64;
+constexpr int kBins = 2048;
+
+// float -> uint32 whose unsigned order equals the float order (negative values included)
+__device__ __forceinline__ uint32_t order_key(float f) {
+    uint32_t u = __float_as_uint(f + 0.0f);      // -0.0 and +0.0 compare equal: same key
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+__device__ __forceinline__ uint32_t wave_incl_scan(uint32_t v, int lane) {
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        uint32_t n = __shfl_up(v, o, 64);
+        if (lane >= o) v += n;
+    }
+    return v;
+}
+
+struct SelSmem {
+    uint32_t hist[kBins];
+    uint32_t wsum[kSelWaves];
+    uint32_t bcast[4];
+};
+
+// Exclusive prefix sum of one value per thread over the workgroup; returns the exclusive
+// prefix and stores the grand total in *total.  Ends with a barrier.
+__device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, SelSmem& sm, uint32_t* total) {
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    uint32_t inc = wave_incl_scan(v, lane);
+    if (lane == 63) sm.wsum[wv] = inc;
+    __syncthreads();
+    uint32_t base = 0, tot = 0;
+#pragma unroll
+    for (int i = 0; i < kSelWaves; ++i) {
+        uint32_t s = sm.wsum[i];
+        if (i < wv) base += s;
+        tot += s;
+    }
+    __syncthreads();
+    *total = tot;
+    return base + inc - v;
+}
+
+}  // namespace
+
+__global__ __launch_bounds__(kSelThreads) void select_kernel(const float* __restrict__ score,
+                                                             const int32_t* __restrict__ budget, int N,
+                                                             int w, int cap, int32_t* __restrict__ idx_out,
+                                                             int32_t* __restrict__ len_out) {
+    __shared__ SelSmem sm;
+    const int bh = blockIdx.x;
+    const int tid = threadIdx.x;
+    const int P = N - w;
+    const float* sc = score + (int64_t)bh * P;
+    int32_t* idx = idx_out + (int64_t)bh * cap;
+
+    int bud = budget[bh];
+    const int hi = N < cap ? N : cap;
+    bud = bud < w ? w : bud;
+    bud = bud > hi ? hi : bud;
+    const int k = bud - w;                    // prefix positions to keep, 0 <= k <= P
+
+    uint32_t thr = 0;                         // key of the k-th largest score
+    uint32_t need_eq = 0;                     // how many keys equal to thr are kept
+    if (k > 0 && k < P) {
+        uint32_t prefix = 0, prefix_mask = 0;
+        uint32_t remaining = (uint32_t)k;     // rank still to be located among matching keys
+        const int shifts[3] = {21, 10, 0};
+        const int widths[3] = {11, 11, 10};
+        for (int pass = 0; pass < 3; ++pass) {
+            const int shift = shifts[pass];
+            const uint32_t nb = 1u << widths[pass];
+            for (int i = tid; i < kBins; i += kSelThreads) sm.hist[i] = 0;
+            __syncthreads();
+            for (int j = tid; j < P; j += kSelThreads) {
+                uint32_t key = order_key(sc[j]);
+                if ((key & prefix_mask) == prefix) atomicAdd(&sm.hist[(key >> shift) & (nb - 1)], 1u);
+            }
+            __syncthreads();
+            // walk the digits from the top: thread t owns digits nb-1-2t and nb-2-2t
+            uint32_t c0 = 0, c1 = 0;
+            const int d0 = (int)nb - 1 - 2 * tid, d1 = d0 - 1;
+            if (d0 >= 0) c0 = sm.hist[d0];
+            if (d1 >= 0) c1 = sm.hist[d1];
+            uint32_t total;
+            uint32_t before = block_excl_scan(c0 + c1, sm, &total);   // keys in higher digits
+            if (d0 >= 0 && before < remaining && remaining <= before + c0) {
+                sm.bcast[0] = (uint32_t)d0;
+                sm.bcast[1] = remaining - before;
+            } else if (d1 >= 0 && before + c0 < remaining && remaining <= before + c0 + c1) {
+                sm.bcast[0] = (uint32_t)d1;
+                sm.bcast[1] = remaining - before - c0;
+            }
+            __syncthreads();
+            prefix |= sm.bcast[0] << shift;
+            prefix_mask |= (nb - 1) << shift;
+            remaining = sm.bcast[1];
+            __syncthreads();
+        }
+        thr = prefix;
+        need_eq = remaining;
+    }
+
+    // ordered compaction, four consecutive positions per thread per step
+    if (k > 0) {
+        const bool all = (k >= P);
+        uint32_t kept_gt = 0, seen_eq = 0;    // running totals over the positions already passed
+        for (int base = 0; base < P; base += kSelThreads * 4) {
+            const int j0 = base + tid * 4;
+            uint32_t gt[4], eq[4], ngt = 0, neq = 0;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                gt[e] = eq[e] = 0;
+                if (j0 + e < P) {
+                    uint32_t key = order_key(sc[j0 + e]);
+                    gt[e] = (all || key > thr) ? 1u : 0u;
+                    eq[e] = (!all && key == thr) ? 1u : 0u;
+                }
+                ngt += gt[e];
+                neq += eq[e];
+            }
+            uint32_t total;
+            uint32_t ex = block_excl_scan((ngt << 16) | neq, sm, &total);
+            uint32_t g_before = kept_gt + (ex >> 16);
+            uint32_t e_before = seen_eq + (ex & 0xffffu);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                if (gt[e]) {
+                    uint32_t pos = g_before + (e_before < need_eq ? e_before : need_eq);
+                    idx[pos] = j0 + e;
+                    ++g_before;
+                } else if (eq[e]) {
+                    if (e_before < need_eq) idx[g_before + e_before] = j0 + e;
+                    ++e_before;
+                }
+            }
+            kept_gt += total >> 16;
+            seen_eq += total & 0xffffu;
+        }
+    }
+    for (int i = tid; i < w; i += kSelThreads) idx[k + i] = P + i;
+    if (tid == 0) len_out[bh] = bud;
+}
+
+// Copies row idx[r] of K and V to row r of the outputs; `lanes` lanes of 16 bytes per row.
+__global__ __launch_bounds__(256) void gather_kernel(const uint4* __restrict__ K, const uint4* __restrict__ V,
+                                                     const int32_t* __restrict__ idx,
+                                                     const int32_t* __restrict__ len, int H, int cap,
+                                                     int lanes, int64_t sb, int64_t sh, int64_t st,
+                                                     int n_row_tiles, uint4* __restrict__ K_out,
+                                                     uint4* __restrict__ V_out) {
+    const int bh = blockIdx.x / n_row_tiles, tile = blockIdx.x % n_row_tiles;
+    const int b = bh / H, h = bh % H;
+    const int rows_per_block = 256 / lanes;
+    const int r = tile * rows_per_block + threadIdx.x / lanes;
+    const int l = threadIdx.x % lanes;
+    if (r >= len[bh]) return;
+    const int64_t src = b * sb + h * sh + (int64_t)idx[(int64_t)bh * cap + r] * st + l;   // in 16-byte units
+    const int64_t dst = ((int64_t)bh * cap + r) * lanes + l;
+    K_out[dst] = K[src];
+    V_out[dst] = V[src];
+}
+
+hipError_t launch_select_gather(const float* score, const int32_t* budget, const void* K,
+                                const void* V, uncomp_dtype dt, int B, int H, int N, int w,
+                                const int64_t ks[3], int cap, void* K_out, void* V_out,
+                                int32_t* idx_out, int32_t* len_out, hipStream_t s) {
+    const int BH = B * H;
+    select_kernel<<<dim3(BH), dim3(kSelThreads), 0, s>>>(score, budget, N, w, cap, idx_out, len_out);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || K == nullptr) return e;
+    const int esz = dt == UNCOMP_BF16 ? 2 : 4;
+    const int per16 = 16 / esz;                       // elements per 16-byte unit
+    const int lanes = kD / per16;                     // 16 (bf16) or 32 (fp32)
+    const int rows_per_block = 256 / lanes;
+    const int n_row_tiles = (cap + rows_per_block - 1) / rows_per_block;
+    gather_kernel<<<dim3((unsigned)(BH * n_row_tiles)), dim3(256), 0, s>>>(
+        static_cast<const uint4*>(K), static_cast<const uint4*>(V), idx_out, len_out, H, cap, lanes,
+        ks[0] / per16, ks[1] / per16, ks[2] / per16, n_row_tiles, static_cast<uint4*>(K_out),
+        static_cast<uint4*>(V_out));
+    return hipGetLastError();
+}
+
+}  // namespace uncomp
