@@ -1,0 +1,190 @@
+"""Benchmark of libuncomp's compression hot path on one MI355X.
+
+One step = the four C-ABI calls (entropy -> budgets -> window score -> select+gather) over
+ALL layers of one synthetic prefill, inputs resident in HBM.  Prints one JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
+
+
+def algorithmic_work(cfg, name):
+    """(bytes, flops) one launch of kernel `name` must move / compute, over all L*B*H heads.
+    Per (layer, batch, KV head): N tokens of D features at e bytes each."""
+    e = 2 if cfg.dtype == "bf16" else 4
+    heads = cfg.L * cfg.B * cfg.H
+    N, D, w, G = cfg.N, cfg.D, cfg.w, cfg.G
+    P = N - w
+    R = G * w
+    if name.startswith("gram"):
+        return heads * N * D * e, heads * 2.0 * N * D * D
+    if name.startswith("score_stats"):
+        return heads * N * D * e, heads * 2.0 * R * D * N
+    if name.startswith("score_vote"):
+        return heads * (P * D * e + 4 * P), heads * 2.0 * R * D * P
+    if name.startswith("score_pool"):
+        return heads * (G * P * 4 + 4 * P), 0.0
+    if name == "select":
+        return heads * 4 * P, 0.0
+    if name == "gather":
+        return heads * 4 * cfg.avg_budget * D * e, 0.0
+    return 0, 0.0
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=3, help="index into BASELINE.json configs (default: the 128K prefill)")
+    ap.add_argument("--seed", type=int, default=2410)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-heads", type=int, default=0, help="heads in the oracle sample (0 = auto)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU only: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    from paper_2410_03090_amd import binding, synth
+
+    cfg = synth.CONFIGS[args.config]
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    t_gen = time.time()
+    K, V, Q = synth.gen_all(cfg, args.seed, device=dev)
+    torch.cuda.synchronize()
+    t_gen = time.time() - t_gen
+    L, B, H, N, D, G, w = cfg.L, cfg.B, cfg.H, cfg.N, cfg.D, cfg.G, cfg.w
+    LB = L * B
+    Kf, Vf, Qf = K.reshape(LB, H, N, D), V.reshape(LB, H, N, D), Q.reshape(LB, H * G, w, D)
+
+    ws = binding.Context.workspace_bytes(LB * H, N, D, LB, H, G, w)
+    ctx = binding.Context(0, ws)
+    i32 = dict(dtype=torch.int32, device=dev)
+    ent = torch.empty(L, B, H, dtype=torch.float32, device=dev)
+    bud = (torch.empty(L, B, H, **i32), torch.empty(L, B, H, **i32), torch.empty(L, **i32), torch.empty(L, **i32))
+    score = torch.empty(LB, H, N - w, dtype=torch.float32, device=dev)
+    cap = cfg.cap
+    outs = (torch.zeros(LB, H, cap, D, dtype=K.dtype, device=dev), torch.zeros(LB, H, cap, D, dtype=K.dtype, device=dev),
+            torch.full((LB, H, cap), -1, **i32), torch.zeros(LB, H, **i32))
+
+    def step():
+        ctx.head_entropy(Kf.reshape(LB * H, N, D), k_trunc=cfg.k_trunc, entropy_out=ent.reshape(-1))
+        ctx.assign_budgets(ent, cfg.M, cfg.n_max, cfg.step, N, w, 0.4, 512, out=bud)
+        ctx.window_score(Qf, Kf, G, cfg.pool, out=score)
+        ctx.select_gather(score, bud[0].reshape(LB, H), Kf, Vf, w, cap, out=outs)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ctx.profile(True)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    recs = ctx.profile_read()
+    ctx.profile(False)
+
+    ms_per_step = elapsed * 1e3 / args.steps
+    value = B * N / (elapsed / args.steps)
+
+    # per-kernel averages from the HIP events recorded inside the timed region
+    per = {}
+    for name, ms in recs:
+        per.setdefault(name, []).append(ms)
+    kernels = {}
+    for name, v in per.items():
+        avg = sum(v) / len(v)
+        byt, flops = algorithmic_work(cfg, name)
+        kernels[name] = {"ms": round(avg, 4), "launches": len(v),
+                         "GBps": round(byt / avg / 1e6, 1) if byt else None,
+                         "TFLOPs": round(flops / avg / 1e9, 1) if flops else None}
+    dominant = max(kernels, key=lambda n: kernels[n]["ms"]) if kernels else None
+    roofline = None
+    if dominant is not None:
+        byt, flops = algorithmic_work(cfg, dominant)
+        avg_ms = kernels[dominant]["ms"]
+        if byt:
+            ach = byt / avg_ms / 1e6
+            roofline = {"kernel": dominant, "bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBS,
+                        "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": None}
+        else:
+            roofline = {"kernel": dominant, "bound": "alu", "achieved": None, "peak": None, "unit": "TFLOP/s",
+                        "frac": None, "traffic": None}
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline(cfg, K, V, Q, args)
+
+    kept = float(outs[3].float().mean().item())
+    out = {
+        "metric": "kv_tokens_compressed_per_sec", "value": round(value, 1), "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": cfg.dtype,
+        "data": "synthetic",
+        "config": {"workload": cfg.name, "layers": L, "batch": B, "kv_heads": H, "q_per_kv": G, "seq_len": N,
+                   "head_dim": D, "window": w, "pool": cfg.pool, "k_trunc": cfg.k_trunc,
+                   "avg_budget": cfg.avg_budget, "mean_kept": round(kept, 1), "rho": round(kept / N, 5),
+                   "head_tokens_per_s": round(value * L * H, 1)},
+        "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels,
+        "gen_seconds": round(t_gen, 1),
+    }
+    print(json.dumps(out))
+
+
+def cpu_baseline(cfg, K, V, Q, args):
+    """Times the float64 oracle on a few (layer, batch, head) units of the same inputs and
+    scales to the whole job.  Baseline only."""
+    import numpy as np
+    import torch
+
+    from oracle import uncomp_oracle as O
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    L, B, H, N, D, G, w = cfg.L, cfg.B, cfg.H, cfg.N, cfg.D, cfg.G, cfg.w
+    units = L * B * H
+    # one head of the 128K config costs the oracle a few seconds: take enough heads for ~20 s
+    est = 2.3 * (N / 131072.0) * (G * w / 256.0)             # seconds per unit, measured once on 8 cores
+    n_heads = args.cpu_heads or int(max(1, min(units, 64, round(20.0 / est))))
+    f64 = lambda t: t.detach().cpu().to(torch.float64).numpy()
+    bits = lambda t: t.detach().cpu().contiguous().view(torch.int16 if t.dtype == torch.bfloat16 else torch.int32).numpy()
+    t_total = 0.0
+    for u in range(n_heads):
+        l, b, h = (u * 7) % L, u % B, (u * 3) % H
+        Kh, Vh = K[l, b, h], V[l, b, h]
+        Qh = Q[l, b, h * G:(h + 1) * G]
+        Kn, Qn = f64(Kh)[None, None], f64(Qh)[None]
+        Kb, Vb = bits(Kh)[None, None], bits(Vh)[None, None]
+        t0 = time.perf_counter()
+        Hh, _ = O.head_entropy(Kn[0], k_trunc=cfg.k_trunc)
+        ent = np.repeat(Hh.astype(np.float32)[None, None], 1, axis=2)
+        hb, _, _, _ = O.assign_budgets(ent.reshape(1, 1, 1), 1, cfg.avg_budget, 0, N, w, 0.4, 512)
+        s = O.window_score(Qn, Kn, G, cfg.pool)
+        O.select_gather(s, hb[0], Kb, Vb, w, cfg.cap)
+        t_total += time.perf_counter() - t0
+    t_job = t_total / n_heads * units
+    return {"value": round(B * N / t_job, 2), "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"{n_heads} of {units} (layer,batch,head) units of {cfg.name}, all four stages, "
+                      f"{t_total:.1f} s measured, scaled linearly to the whole job"}
+
+
+if __name__ == "__main__":
+    main()

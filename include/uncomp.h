@@ -75,6 +75,16 @@ size_t uncomp_workspace_bytes(int n_mat, int N, int D, int B, int H, int G, int 
  * the context, valid until the next call on it). */
 const char* uncomp_last_error(const uncomp_ctx* ctx);
 
+/* Per-kernel timing for benchmarks (not a paper operation).  uncomp_profile(ctx, 1) makes
+ * every later hot call bracket each of its kernel launches with two HIP events on the
+ * caller's stream and clears earlier records; uncomp_profile(ctx, 0) stops it.  After the
+ * caller has synchronised the stream, uncomp_profile_read copies up to max_records
+ * (kernel name, milliseconds) pairs in launch order into the HOST arrays names / ms (either
+ * may be NULL), clears the records and returns their count (negative = status).  At most
+ * 256 launches are kept between reads; later ones go untimed.  Names are static strings. */
+uncomp_status uncomp_profile(uncomp_ctx* ctx, int on);
+int uncomp_profile_read(uncomp_ctx* ctx, int max_records, const char** names, float* ms);
+
 /*
  * Truncated matrix entropy (Sec. 3.1 Eq. 1 and Lemma 2; Sec. 3.2 Eq. 5-6; unit trace as
  * in the proof of Lemma 4).

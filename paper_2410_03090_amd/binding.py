@@ -23,6 +23,7 @@ DEFAULT_FLAGS = CENTER | TRUNC_RENORM
 
 EXPORTS = (
     "uncomp_create", "uncomp_destroy", "uncomp_workspace_bytes", "uncomp_last_error",
+    "uncomp_profile", "uncomp_profile_read",
     "uncomp_head_entropy", "uncomp_assign_budgets", "uncomp_window_score", "uncomp_select_gather",
 )
 
@@ -55,6 +56,10 @@ def load_library() -> ctypes.CDLL:
     lib.uncomp_workspace_bytes.restype = c.c_size_t
     lib.uncomp_last_error.argtypes = [vp]
     lib.uncomp_last_error.restype = c.c_char_p
+    lib.uncomp_profile.argtypes = [vp, i32]
+    lib.uncomp_profile.restype = i32
+    lib.uncomp_profile_read.argtypes = [vp, i32, c.POINTER(c.c_char_p), c.POINTER(f32)]
+    lib.uncomp_profile_read.restype = i32
     lib.uncomp_head_entropy.argtypes = [vp, vp, i32, i32, i32, i32, i64, i64, i32, u32, vp, vp, vp]
     lib.uncomp_head_entropy.restype = i32
     lib.uncomp_assign_budgets.argtypes = [vp, vp, i32, i32, i32, i32, i32, i32, i32, i32, f32, i32, u32,
@@ -116,6 +121,18 @@ class Context:
     def _check(self, st: int):
         if st != OK:
             raise UncompError(st, self.lib.uncomp_last_error(self.handle).decode())
+
+    def profile(self, on: bool):
+        self._check(self.lib.uncomp_profile(self.handle, 1 if on else 0))
+
+    def profile_read(self, max_records: int = 256):
+        """(kernel name, ms) of every launch since the last read; synchronise the stream first."""
+        names = (ctypes.c_char_p * max_records)()
+        ms = (ctypes.c_float * max_records)()
+        n = self.lib.uncomp_profile_read(self.handle, max_records, names, ms)
+        if n < 0:
+            self._check(n)
+        return [(names[i].decode(), float(ms[i])) for i in range(n)]
 
     # -- the four hot calls ------------------------------------------------------------
     def head_entropy(self, X: torch.Tensor, k_trunc: int = 32, flags: int = DEFAULT_FLAGS,

@@ -70,6 +70,10 @@ uncomp_status uncomp_destroy(uncomp_ctx* ctx) {
     if (ctx == nullptr) return UNCOMP_ERR_INVALID_ARG;
     hipError_t e = hipSuccess;
     if (ctx->ws != nullptr) e = hipFree(ctx->ws);
+    for (int i = 0; i < ctx->prof.n_events; ++i) {
+        (void)hipEventDestroy(ctx->prof.start[i]);
+        (void)hipEventDestroy(ctx->prof.stop[i]);
+    }
     delete ctx;
     return e == hipSuccess ? UNCOMP_OK : UNCOMP_ERR_HIP;
 }
@@ -86,6 +90,27 @@ size_t uncomp_workspace_bytes(int n_mat, int N, int D, int B, int H, int G, int 
         if (b > need) need = b;
     }
     return need;
+}
+
+uncomp_status uncomp_profile(uncomp_ctx* ctx, int on) {
+    if (ctx == nullptr) return UNCOMP_ERR_INVALID_ARG;
+    ctx->prof.on = on != 0;
+    ctx->prof.n = 0;
+    return UNCOMP_OK;
+}
+
+int uncomp_profile_read(uncomp_ctx* ctx, int max_records, const char** names, float* ms) {
+    if (ctx == nullptr || max_records < 0) return UNCOMP_ERR_INVALID_ARG;
+    int n = ctx->prof.n < max_records ? ctx->prof.n : max_records;
+    for (int i = 0; i < n; ++i) {
+        float t = 0.f;
+        hipError_t e = hipEventElapsedTime(&t, ctx->prof.start[i], ctx->prof.stop[i]);
+        if (e != hipSuccess) return hip_fail(ctx, e, "profile_read: hipEventElapsedTime");
+        if (names != nullptr) names[i] = ctx->prof.name[i];
+        if (ms != nullptr) ms[i] = t;
+    }
+    ctx->prof.n = 0;
+    return n;
 }
 
 const char* uncomp_last_error(const uncomp_ctx* ctx) { return ctx != nullptr ? ctx->err : "null context"; }
@@ -107,10 +132,10 @@ uncomp_status uncomp_head_entropy(uncomp_ctx* ctx, const void* X, uncomp_dtype d
     EntropyPlan p = plan_entropy(n_mat, N);
     if (p.bytes > ctx->ws_bytes)
         return fail(ctx, UNCOMP_ERR_WORKSPACE, "head_entropy: needs %zu workspace bytes, context has %zu", p.bytes, ctx->ws_bytes);
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    hipError_t e = launch_gram(X, dtype, n_mat, N, mat_stride, ldx, p, ctx->ws, s);
+    Env env{static_cast<hipStream_t>(stream), &ctx->prof};
+    hipError_t e = launch_gram(X, dtype, n_mat, N, mat_stride, ldx, p, ctx->ws, env);
     if (e != hipSuccess) return hip_fail(ctx, e, "head_entropy: gram launch");
-    e = launch_jacobi_entropy(n_mat, N, k_trunc, flags, p, ctx->ws, entropy_out, eig_out, s);
+    e = launch_jacobi_entropy(n_mat, N, k_trunc, flags, p, ctx->ws, entropy_out, eig_out, env);
     if (e != hipSuccess) return hip_fail(ctx, e, "head_entropy: eigen launch");
     return UNCOMP_OK;
 }
@@ -136,7 +161,7 @@ uncomp_status uncomp_assign_budgets(uncomp_ctx* ctx, const float* entropy, int n
     if (!(eps == eps)) return fail(ctx, UNCOMP_ERR_INVALID_ARG, "assign_budgets: eps is NaN");
     hipError_t e = launch_budgets(entropy, n_layer, n_batch, H, M, n_max, step, N, w, eps, delta_n, flags,
                                   head_budget, head_group, layer_group, layer_tokens, ctx->ws,
-                                  static_cast<hipStream_t>(stream));
+                                  Env{static_cast<hipStream_t>(stream), &ctx->prof});
     if (e != hipSuccess) return hip_fail(ctx, e, "assign_budgets: launch");
     return UNCOMP_OK;
 }
@@ -161,7 +186,7 @@ uncomp_status uncomp_window_score(uncomp_ctx* ctx, const void* Qwin, const void*
     if (p.bytes > ctx->ws_bytes)
         return fail(ctx, UNCOMP_ERR_WORKSPACE, "window_score: needs %zu workspace bytes, context has %zu", p.bytes, ctx->ws_bytes);
     hipError_t e = launch_window_score(Qwin, K, dtype, B, H, G, N, w, pool, k_strides, p, ctx->ws, score_out,
-                                       static_cast<hipStream_t>(stream));
+                                       Env{static_cast<hipStream_t>(stream), &ctx->prof});
     if (e != hipSuccess) return hip_fail(ctx, e, "window_score: launch");
     return UNCOMP_OK;
 }
@@ -192,7 +217,7 @@ uncomp_status uncomp_select_gather(uncomp_ctx* ctx, const float* score, const in
     static const int64_t zero_strides[3] = {0, 0, 0};
     hipError_t e = launch_select_gather(score, budget, all_kv ? K : nullptr, V, dtype, B, H, N, w,
                                         all_kv ? kv_strides : zero_strides, cap, K_out, V_out, idx_out, len_out,
-                                        static_cast<hipStream_t>(stream));
+                                        Env{static_cast<hipStream_t>(stream), &ctx->prof});
     if (e != hipSuccess) return hip_fail(ctx, e, "select_gather: launch");
     return UNCOMP_OK;
 }

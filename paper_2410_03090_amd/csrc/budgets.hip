@@ -62,18 +62,23 @@ __global__ __launch_bounds__(256) void layer_stage_kernel(const float* __restric
 hipError_t launch_budgets(const float* entropy, int L, int B, int H, int M, int n_max, int step,
                           int N, int w, float eps, int delta_n, unsigned flags,
                           int32_t* head_budget, int32_t* head_group, int32_t* layer_group,
-                          int32_t* layer_tokens, char* ws, hipStream_t s) {
+                          int32_t* layer_tokens, char* ws, const Env& env) {
+    hipStream_t s = env.s;
     if (head_budget != nullptr) {
         int total = L * B * H;
         int blocks = (total + 255) / 256;
         if (blocks > 1024) blocks = 1024;
+        env.begin("head_budget");
         head_budget_kernel<<<blocks, 256, 0, s>>>(entropy, L * B, H, M, n_max, step, N, w,
                                                   head_budget, head_group);
+        env.end();
     }
     if (layer_group != nullptr) {
+        env.begin("layer_stage");
         layer_stage_kernel<<<1, 256, 0, s>>>(entropy, L, B * H, N, w, eps, delta_n,
                                              (flags & UNCOMP_LAYER_DELTA_INCREASE) ? 1 : 0,
                                              reinterpret_cast<double*>(ws), layer_group, layer_tokens);
+        env.end();
     }
     return hipGetLastError();
 }

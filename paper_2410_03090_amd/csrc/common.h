@@ -9,12 +9,26 @@
 
 #include "../../include/uncomp.h"
 
+namespace uncomp {
+// Optional per-kernel timing: when switched on, each kernel launch of a hot call is put
+// between two HIP events recorded on the caller's stream.
+struct Profiler {
+    static constexpr int kMax = 256;
+    bool on = false;
+    int n = 0;                       // records used since the last reset
+    int n_events = 0;                // event pairs created so far
+    const char* name[kMax];
+    hipEvent_t start[kMax], stop[kMax];
+};
+}  // namespace uncomp
+
 struct uncomp_ctx {
     int device;
     int num_cu;
     char* ws;            // device workspace
     size_t ws_bytes;
     char err[256];
+    uncomp::Profiler prof;
 };
 
 namespace uncomp {
@@ -45,23 +59,46 @@ struct ScorePlan {
 };
 ScorePlan plan_score(int B, int H, int G, int N, int w);
 
+// Stream plus optional profiler, handed to every launcher.
+struct Env {
+    hipStream_t s;
+    Profiler* prof;
+    // Marks the start / end of one kernel launch (no-ops unless profiling is on).
+    void begin(const char* kernel_name) const {
+        if (prof == nullptr || !prof->on || prof->n >= Profiler::kMax) return;
+        int i = prof->n;
+        if (i >= prof->n_events) {
+            if (hipEventCreate(&prof->start[i]) != hipSuccess) return;
+            if (hipEventCreate(&prof->stop[i]) != hipSuccess) return;
+            prof->n_events = i + 1;
+        }
+        prof->name[i] = kernel_name;
+        (void)hipEventRecord(prof->start[i], s);
+    }
+    void end() const {
+        if (prof == nullptr || !prof->on || prof->n >= Profiler::kMax || prof->n >= prof->n_events) return;
+        (void)hipEventRecord(prof->stop[prof->n], s);
+        prof->n += 1;
+    }
+};
+
 // ---- launchers (each returns the hipError_t of its launches) ---------------------------
 hipError_t launch_gram(const void* X, uncomp_dtype dt, int n_mat, int N, int64_t mat_stride,
-                       int64_t ldx, const EntropyPlan& p, char* ws, hipStream_t s);
+                       int64_t ldx, const EntropyPlan& p, char* ws, const Env& env);
 hipError_t launch_jacobi_entropy(int n_mat, int N, int k_trunc, unsigned flags,
                                  const EntropyPlan& p, char* ws, float* entropy_out,
-                                 float* eig_out, hipStream_t s);
+                                 float* eig_out, const Env& env);
 hipError_t launch_budgets(const float* entropy, int L, int B, int H, int M, int n_max, int step,
                           int N, int w, float eps, int delta_n, unsigned flags,
                           int32_t* head_budget, int32_t* head_group, int32_t* layer_group,
-                          int32_t* layer_tokens, char* ws, hipStream_t s);
+                          int32_t* layer_tokens, char* ws, const Env& env);
 hipError_t launch_window_score(const void* Q, const void* K, uncomp_dtype dt, int B, int H, int G,
                                int N, int w, int pool, const int64_t ks[3], const ScorePlan& p,
-                               char* ws, float* score_out, hipStream_t s);
+                               char* ws, float* score_out, const Env& env);
 hipError_t launch_select_gather(const float* score, const int32_t* budget, const void* K,
                                 const void* V, uncomp_dtype dt, int B, int H, int N, int w,
                                 const int64_t ks[3], int cap, void* K_out, void* V_out,
-                                int32_t* idx_out, int32_t* len_out, hipStream_t s);
+                                int32_t* idx_out, int32_t* len_out, const Env& env);
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 

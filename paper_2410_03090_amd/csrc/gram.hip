@@ -100,10 +100,12 @@ EntropyPlan plan_entropy(int n_mat, int N) {
 }
 
 hipError_t launch_gram(const void* X, uncomp_dtype dt, int n_mat, int N, int64_t mat_stride,
-                       int64_t ldx, const EntropyPlan& p, char* ws, hipStream_t s) {
+                       int64_t ldx, const EntropyPlan& p, char* ws, const Env& env) {
+    hipStream_t s = env.s;
     float* gram = reinterpret_cast<float*>(ws + p.gram_off);
     float* sums = reinterpret_cast<float*>(ws + p.sum_off);
     dim3 grid((unsigned)(p.n_chunks * n_mat)), block(256);
+    env.begin("gram_alu");
     if (dt == UNCOMP_BF16) {
         gram_alu_kernel<bf16_bits><<<grid, block, 0, s>>>(
             static_cast<const bf16_bits*>(X), N, mat_stride, ldx, p.n_chunks, p.chunk, gram, sums);
@@ -111,6 +113,7 @@ hipError_t launch_gram(const void* X, uncomp_dtype dt, int n_mat, int N, int64_t
         gram_alu_kernel<float><<<grid, block, 0, s>>>(
             static_cast<const float*>(X), N, mat_stride, ldx, p.n_chunks, p.chunk, gram, sums);
     }
+    env.end();
     return hipGetLastError();
 }
 

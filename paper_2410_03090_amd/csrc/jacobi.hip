@@ -194,15 +194,18 @@ __global__ __launch_bounds__(kThreads) void jacobi_entropy_kernel(
 
 hipError_t launch_jacobi_entropy(int n_mat, int N, int k_trunc, unsigned flags,
                                  const EntropyPlan& p, char* ws, float* entropy_out,
-                                 float* eig_out, hipStream_t s) {
+                                 float* eig_out, const Env& env) {
+    hipStream_t s = env.s;
     static_assert(sizeof(Smem) <= 160 * 1024, "LDS budget");
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(jacobi_entropy_kernel),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)sizeof(Smem));
     if (e != hipSuccess) return e;
     const float* gram = reinterpret_cast<const float*>(ws + p.gram_off);
     const float* sums = reinterpret_cast<const float*>(ws + p.sum_off);
+    env.begin("jacobi_entropy");
     jacobi_entropy_kernel<<<dim3(n_mat), dim3(kThreads), sizeof(Smem), s>>>(
         gram, sums, p.n_chunks, N, k_trunc, flags, entropy_out, eig_out);
+    env.end();
     return hipGetLastError();
 }
 

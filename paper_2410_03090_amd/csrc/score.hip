@@ -197,32 +197,41 @@ ScorePlan plan_score(int B, int H, int G, int N, int w) {
 template <typename T>
 static hipError_t run_score(const T* Q, const T* K, int B, int H, int G, int N, int w, int pool,
                             const int64_t ks[3], const ScorePlan& p, char* ws, float* score_out,
-                            hipStream_t s) {
+                            const Env& env) {
+    hipStream_t s = env.s;
     const int BH = B * H, P = N - w;
     float2* stats = reinterpret_cast<float2*>(ws + p.stats_off);
     float* lse = reinterpret_cast<float*>(ws + p.lse_off);
     float* vote = reinterpret_cast<float*>(ws + p.vote_off);
     const int threads1 = (p.R + 63) / 64 * 64;
+    env.begin("score_stats_alu");
     score_stats_alu_kernel<T><<<dim3((unsigned)(BH * p.n_chunks)), dim3(threads1), 0, s>>>(
         Q, K, H, G, N, w, ks[0], ks[1], ks[2], p.n_chunks, p.chunk, stats);
+    env.end();
     const int rows = BH * p.R;
+    env.begin("score_lse");
     score_lse_kernel<<<dim3((rows + 255) / 256), dim3(256), 0, s>>>(stats, rows, p.R, p.n_chunks, lse);
+    env.end();
     const int n_tiles = (P + 255) / 256;
+    env.begin("score_vote_alu");
     score_vote_alu_kernel<T><<<dim3((unsigned)(BH * n_tiles)), dim3(256), 0, s>>>(
         Q, K, lse, H, G, N, w, ks[0], ks[1], ks[2], n_tiles, vote);
+    env.end();
+    env.begin("score_pool");
     score_pool_kernel<<<dim3((unsigned)(BH * n_tiles)), dim3(256), 0, s>>>(vote, G, P, pool / 2, n_tiles,
                                                                           score_out);
+    env.end();
     return hipGetLastError();
 }
 
 hipError_t launch_window_score(const void* Q, const void* K, uncomp_dtype dt, int B, int H, int G,
                                int N, int w, int pool, const int64_t ks[3], const ScorePlan& p,
-                               char* ws, float* score_out, hipStream_t s) {
+                               char* ws, float* score_out, const Env& env) {
     if (dt == UNCOMP_BF16)
         return run_score<bf16_bits>(static_cast<const bf16_bits*>(Q), static_cast<const bf16_bits*>(K), B, H,
-                                    G, N, w, pool, ks, p, ws, score_out, s);
+                                    G, N, w, pool, ks, p, ws, score_out, env);
     return run_score<float>(static_cast<const float*>(Q), static_cast<const float*>(K), B, H, G, N, w,
-                            pool, ks, p, ws, score_out, s);
+                            pool, ks, p, ws, score_out, env);
 }
 
 }  // namespace uncomp

@@ -183,9 +183,12 @@ __global__ __launch_bounds__(256) void gather_kernel(const uint4* __restrict__ K
 hipError_t launch_select_gather(const float* score, const int32_t* budget, const void* K,
                                 const void* V, uncomp_dtype dt, int B, int H, int N, int w,
                                 const int64_t ks[3], int cap, void* K_out, void* V_out,
-                                int32_t* idx_out, int32_t* len_out, hipStream_t s) {
+                                int32_t* idx_out, int32_t* len_out, const Env& env) {
+    hipStream_t s = env.s;
     const int BH = B * H;
+    env.begin("select");
     select_kernel<<<dim3(BH), dim3(kSelThreads), 0, s>>>(score, budget, N, w, cap, idx_out, len_out);
+    env.end();
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || K == nullptr) return e;
     const int esz = dt == UNCOMP_BF16 ? 2 : 4;
@@ -193,10 +196,12 @@ hipError_t launch_select_gather(const float* score, const int32_t* budget, const
     const int lanes = kD / per16;                     // 16 (bf16) or 32 (fp32)
     const int rows_per_block = 256 / lanes;
     const int n_row_tiles = (cap + rows_per_block - 1) / rows_per_block;
+    env.begin("gather");
     gather_kernel<<<dim3((unsigned)(BH * n_row_tiles)), dim3(256), 0, s>>>(
         static_cast<const uint4*>(K), static_cast<const uint4*>(V), idx_out, len_out, H, cap, lanes,
         ks[0] / per16, ks[1] / per16, ks[2] / per16, n_row_tiles, static_cast<uint4*>(K_out),
         static_cast<uint4*>(V_out));
+    env.end();
     return hipGetLastError();
 }
 
