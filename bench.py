@@ -162,7 +162,7 @@ def cpu_baseline(cfg, K, V, Q, args):
     L, B, H, N, D, G, w = cfg.L, cfg.B, cfg.H, cfg.N, cfg.D, cfg.G, cfg.w
     units = L * B * H
     # one head of the 128K config costs the oracle a few seconds: take enough heads for ~20 s
-    est = 2.3 * (N / 131072.0) * (G * w / 256.0)             # seconds per unit, measured once on 8 cores
+    est = 0.65 * (N / 131072.0) * (G * w / 256.0)             # seconds per unit, measured once on a 16-core box
     n_heads = args.cpu_heads or int(max(1, min(units, 64, round(20.0 / est))))
     f64 = lambda t: t.detach().cpu().to(torch.float64).numpy()
     bits = lambda t: t.detach().cpu().contiguous().view(torch.int16 if t.dtype == torch.bfloat16 else torch.int32).numpy()

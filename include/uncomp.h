@@ -85,6 +85,10 @@ const char* uncomp_last_error(const uncomp_ctx* ctx);
 uncomp_status uncomp_profile(uncomp_ctx* ctx, int on);
 int uncomp_profile_read(uncomp_ctx* ctx, int max_records, const char** names, float* ms);
 
+/* Kernel selection for testing: plain_alu != 0 makes the bf16 calls use the plain-ALU
+ * kernels (the ones fp32 inputs always use) instead of the MFMA kernels.  Default 0. */
+uncomp_status uncomp_set_kernel_path(uncomp_ctx* ctx, int plain_alu);
+
 /*
  * Truncated matrix entropy (Sec. 3.1 Eq. 1 and Lemma 2; Sec. 3.2 Eq. 5-6; unit trace as
  * in the proof of Lemma 4).

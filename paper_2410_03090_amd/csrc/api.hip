@@ -99,6 +99,12 @@ uncomp_status uncomp_profile(uncomp_ctx* ctx, int on) {
     return UNCOMP_OK;
 }
 
+uncomp_status uncomp_set_kernel_path(uncomp_ctx* ctx, int plain_alu) {
+    if (ctx == nullptr) return UNCOMP_ERR_INVALID_ARG;
+    ctx->force_alu = plain_alu != 0;
+    return UNCOMP_OK;
+}
+
 int uncomp_profile_read(uncomp_ctx* ctx, int max_records, const char** names, float* ms) {
     if (ctx == nullptr || max_records < 0) return UNCOMP_ERR_INVALID_ARG;
     int n = ctx->prof.n < max_records ? ctx->prof.n : max_records;
@@ -132,7 +138,7 @@ uncomp_status uncomp_head_entropy(uncomp_ctx* ctx, const void* X, uncomp_dtype d
     EntropyPlan p = plan_entropy(n_mat, N);
     if (p.bytes > ctx->ws_bytes)
         return fail(ctx, UNCOMP_ERR_WORKSPACE, "head_entropy: needs %zu workspace bytes, context has %zu", p.bytes, ctx->ws_bytes);
-    Env env{static_cast<hipStream_t>(stream), &ctx->prof};
+    Env env{static_cast<hipStream_t>(stream), &ctx->prof, ctx->force_alu};
     hipError_t e = launch_gram(X, dtype, n_mat, N, mat_stride, ldx, p, ctx->ws, env);
     if (e != hipSuccess) return hip_fail(ctx, e, "head_entropy: gram launch");
     e = launch_jacobi_entropy(n_mat, N, k_trunc, flags, p, ctx->ws, entropy_out, eig_out, env);
@@ -161,7 +167,7 @@ uncomp_status uncomp_assign_budgets(uncomp_ctx* ctx, const float* entropy, int n
     if (!(eps == eps)) return fail(ctx, UNCOMP_ERR_INVALID_ARG, "assign_budgets: eps is NaN");
     hipError_t e = launch_budgets(entropy, n_layer, n_batch, H, M, n_max, step, N, w, eps, delta_n, flags,
                                   head_budget, head_group, layer_group, layer_tokens, ctx->ws,
-                                  Env{static_cast<hipStream_t>(stream), &ctx->prof});
+                                  Env{static_cast<hipStream_t>(stream), &ctx->prof, ctx->force_alu});
     if (e != hipSuccess) return hip_fail(ctx, e, "assign_budgets: launch");
     return UNCOMP_OK;
 }
@@ -186,7 +192,7 @@ uncomp_status uncomp_window_score(uncomp_ctx* ctx, const void* Qwin, const void*
     if (p.bytes > ctx->ws_bytes)
         return fail(ctx, UNCOMP_ERR_WORKSPACE, "window_score: needs %zu workspace bytes, context has %zu", p.bytes, ctx->ws_bytes);
     hipError_t e = launch_window_score(Qwin, K, dtype, B, H, G, N, w, pool, k_strides, p, ctx->ws, score_out,
-                                       Env{static_cast<hipStream_t>(stream), &ctx->prof});
+                                       Env{static_cast<hipStream_t>(stream), &ctx->prof, ctx->force_alu});
     if (e != hipSuccess) return hip_fail(ctx, e, "window_score: launch");
     return UNCOMP_OK;
 }
@@ -217,7 +223,7 @@ uncomp_status uncomp_select_gather(uncomp_ctx* ctx, const float* score, const in
     static const int64_t zero_strides[3] = {0, 0, 0};
     hipError_t e = launch_select_gather(score, budget, all_kv ? K : nullptr, V, dtype, B, H, N, w,
                                         all_kv ? kv_strides : zero_strides, cap, K_out, V_out, idx_out, len_out,
-                                        Env{static_cast<hipStream_t>(stream), &ctx->prof});
+                                        Env{static_cast<hipStream_t>(stream), &ctx->prof, ctx->force_alu});
     if (e != hipSuccess) return hip_fail(ctx, e, "select_gather: launch");
     return UNCOMP_OK;
 }

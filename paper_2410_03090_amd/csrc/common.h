@@ -29,6 +29,7 @@ struct uncomp_ctx {
     size_t ws_bytes;
     char err[256];
     uncomp::Profiler prof;
+    bool force_alu = false;
 };
 
 namespace uncomp {
@@ -63,6 +64,7 @@ ScorePlan plan_score(int B, int H, int G, int N, int w);
 struct Env {
     hipStream_t s;
     Profiler* prof;
+    bool force_alu = false;          // use the plain-ALU kernels even where an MFMA kernel exists
     // Marks the start / end of one kernel launch (no-ops unless profiling is on).
     void begin(const char* kernel_name) const {
         if (prof == nullptr || !prof->on || prof->n >= Profiler::kMax) return;

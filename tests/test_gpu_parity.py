@@ -78,7 +78,7 @@ def test_entropy_special_cases(ctx):
     A = torch.randn(512, D + 1, generator=g, dtype=torch.float64)
     A[:, 0] = 1.0
     Qm, _ = torch.linalg.qr(A)
-    Xi = (Qm[:, 1:] * 3.0).to(torch.float32)[None]
+    Xi = (Qm[:, 1:] * 3.0).to(torch.float32).contiguous()[None]
     for k in (8, 32):
         Hi = ctx.head_entropy(Xi.to(DEV), k_trunc=k).cpu().numpy()
         assert Hi[0] == pytest.approx(math.log(k), rel=1e-5)
@@ -105,6 +105,19 @@ def test_entropy_large_mean(ctx):
     H = ctx.head_entropy(X.to(DEV)).cpu().numpy()
     Href, _ = O.head_entropy(to_f64(X))
     np.testing.assert_allclose(H, Href, rtol=1e-4)
+
+
+def test_entropy_mfma_and_alu_paths_agree(ctx):
+    # bf16 inputs: the MFMA Gram kernel and the plain-ALU one see the same exact products
+    X = _rand_lowrank(6, 20000, 128, 40, torch.bfloat16, seed=3).to(DEV)
+    a, ea = ctx.head_entropy(X, want_eig=True)
+    ctx.set_kernel_path(plain_alu=True)
+    b, eb = ctx.head_entropy(X, want_eig=True)
+    ctx.set_kernel_path(plain_alu=False)
+    np.testing.assert_allclose(a.cpu().numpy(), b.cpu().numpy(), rtol=2e-6)
+    np.testing.assert_allclose(ea.cpu().numpy(), eb.cpu().numpy(), atol=1e-6)
+    Href, _ = O.head_entropy(to_f64(X))
+    np.testing.assert_allclose(a.cpu().numpy(), Href, rtol=1e-5)
 
 
 # ------------------------------------------------------------------------- budgets
