@@ -87,6 +87,265 @@ __global__ __launch_bounds__(512) void score_stats_alu_kernel(
     if (live) stats[((int64_t)bh * n_chunks + c) * R + row] = make_float2(mx, sum);
 }
 
+// ---------------------------------------------------------------------------------------
+// bf16 MFMA kernels.  Logits S = Q K^T contract over the 128 features, which are contiguous
+// in memory, so both operands of v_mfma_f32_16x16x32_bf16 load straight from rows: query
+// rows are the A operand (held in registers for the whole kernel), a 64-token key tile is
+// the B operand, staged once per workgroup in LDS (rows padded by 16 bytes so that eight
+// consecutive lanes of a 128-bit read hit distinct banks) and read by all four waves.
+// Wave v owns query rows [16*RB*v, 16*RB*(v+1)) of the KV head (RB = 2 or 4 blocks of 16
+// rows, i.e. up to 128 or 256 rows per head).  An accumulator lane holds one token
+// (lane%16) and four rows (4*(lane/16) + 0..3) of each 16x16 block.
+// ---------------------------------------------------------------------------------------
+namespace {
+
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+
+constexpr int kTile = 64;                 // tokens per LDS tile
+constexpr int kRowBytes = 2 * kD + 16;    // padded LDS row
+constexpr int kTileBytes = kTile * kRowBytes;
+constexpr float kRescaleGap = 8.f;        // running reference may lag the true max by 2^8
+
+struct KTileRegs { uint4 v[4]; };
+
+// 64 tokens x 256 B = 1024 16-byte pieces, four per thread; tokens >= t_end read as zero
+__device__ __forceinline__ void ktile_load(KTileRegs& r, const bf16_bits* Kh, int64_t ks_t, int t0, int t_end,
+                                           int tid) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int idx = tid + 256 * i;
+        const int tok = t0 + (idx >> 4);
+        if (tok < t_end) {
+            r.v[i] = *reinterpret_cast<const uint4*>(Kh + (int64_t)tok * ks_t + (idx & 15) * 8);
+        } else {
+            r.v[i] = make_uint4(0u, 0u, 0u, 0u);
+        }
+    }
+}
+__device__ __forceinline__ void ktile_store(const KTileRegs& r, unsigned char* lds, int tid) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int idx = tid + 256 * i;
+        *reinterpret_cast<uint4*>(lds + (idx >> 4) * kRowBytes + (idx & 15) * 16) = r.v[i];
+    }
+}
+
+// query rows of this wave as A operands: qa[rb][ks] = row 16*rb + lane%16, features 32ks + 8*(lane/16) ..
+template <int RB>
+__device__ __forceinline__ void load_q(bf16x8_t qa[RB][4], const bf16_bits* Qh, int row0, int R, int lane) {
+    const int m = lane & 15, g = lane >> 4;
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+        const int row = row0 + 16 * rb + m;
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            uint4 raw = make_uint4(0u, 0u, 0u, 0u);
+            if (row < R) raw = *reinterpret_cast<const uint4*>(Qh + (int64_t)row * kD + 32 * ks + 8 * g);
+            qa[rb][ks] = __builtin_bit_cast(bf16x8_t, raw);
+        }
+    }
+}
+
+// S tile of this wave: acc[st][rb] = rows 16*rb.. x tokens 16*st.. of the LDS tile
+template <int RB>
+__device__ __forceinline__ void tile_logits(f32x4_t acc[4][RB], const bf16x8_t qa[RB][4],
+                                            const unsigned char* lds, int lane) {
+    const int m = lane & 15, g = lane >> 4;
+#pragma unroll
+    for (int st = 0; st < 4; ++st) {
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb) acc[st][rb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            uint4 raw = *reinterpret_cast<const uint4*>(lds + (16 * st + m) * kRowBytes + 64 * ks + 16 * g);
+            bf16x8_t b = __builtin_bit_cast(bf16x8_t, raw);
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb)
+                acc[st][rb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qa[rb][ks], b, acc[st][rb], 0, 0, 0);
+        }
+    }
+}
+
+}  // namespace
+
+// pass 1: running (reference, sum of exp2) per query row over one token chunk
+template <int RB>
+__global__ __launch_bounds__(256) void score_stats_mfma_kernel(
+    const bf16_bits* __restrict__ Q, const bf16_bits* __restrict__ K, int H, int R, int N, int w,
+    int64_t ks_b, int64_t ks_h, int64_t ks_t, int n_chunks, int chunk, float2* __restrict__ stats) {
+    __shared__ __align__(16) unsigned char lds[2][kTileBytes];
+    const int bh = blockIdx.x / n_chunks, c = blockIdx.x % n_chunks;
+    const int b = bh / H, h = bh % H;
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int m = lane & 15, g = lane >> 4;
+    const int P = N - w;
+    const bf16_bits* Kh = K + b * ks_b + h * ks_h;
+    const int row0 = wv * 16 * RB;
+    const float scale2 = kLog2e * rsqrtf((float)kD);
+
+    bf16x8_t qa[RB][4];
+    load_q<RB>(qa, Q + (int64_t)bh * R * kD, row0, R, lane);
+
+    float ref[RB][4], sum[RB][4];
+    int last[RB][4];                       // last token each of this lane's rows may see
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            ref[rb][v] = -INFINITY;
+            sum[rb][v] = 0.f;
+            const int row = row0 + 16 * rb + 4 * g + v;
+            last[rb][v] = row < R ? P + row % w : -1;
+        }
+
+    const int t_begin = c * chunk, t_end = min(N, t_begin + chunk);
+    const int n_tiles = (t_end - t_begin + kTile - 1) / kTile;
+    KTileRegs regs;
+    ktile_load(regs, Kh, ks_t, t_begin, t_end, tid);
+    ktile_store(regs, lds[0], tid);
+    __syncthreads();
+    for (int it = 0; it < n_tiles; ++it) {
+        const int t0 = t_begin + it * kTile;
+        if (it + 1 < n_tiles) ktile_load(regs, Kh, ks_t, t0 + kTile, t_end, tid);
+        f32x4_t acc[4][RB];
+        tile_logits<RB>(acc, qa, lds[it & 1], lane);
+        const bool edge = t0 + kTile > P || t0 + kTile > t_end;   // causal window or ragged end inside
+        // 1. does any row need a new reference?
+        bool need = false;
+        float tmax[RB][4];
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                float mx = -INFINITY;
+#pragma unroll
+                for (int st = 0; st < 4; ++st) {
+                    float sv = acc[st][rb][v] * scale2;
+                    if (edge) {
+                        const int j = t0 + 16 * st + m;
+                        if (j >= t_end || j > last[rb][v]) sv = -INFINITY;
+                    }
+                    acc[st][rb][v] = sv;
+                    mx = fmaxf(mx, sv);
+                }
+                tmax[rb][v] = mx;
+                need |= mx > ref[rb][v] + kRescaleGap;
+            }
+        if (__builtin_amdgcn_ballot_w64(need) != 0ull) {
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+                for (int v = 0; v < 4; ++v)
+                    if (tmax[rb][v] > ref[rb][v]) {
+                        sum[rb][v] *= exp2f(ref[rb][v] - tmax[rb][v]);     // exp2(-inf) = 0 on first use
+                        ref[rb][v] = tmax[rb][v];
+                    }
+        }
+        // 2. accumulate
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const float r = ref[rb][v];
+#pragma unroll
+                for (int st = 0; st < 4; ++st) {
+                    const float sv = acc[st][rb][v];
+                    float e = __builtin_amdgcn_exp2f(sv - r);
+                    if (edge) e = sv == -INFINITY ? 0.f : e;
+                    sum[rb][v] += e;
+                }
+            }
+        if (it + 1 < n_tiles) ktile_store(regs, lds[(it + 1) & 1], tid);
+        __syncthreads();
+    }
+
+    // combine the 16 token slots (lanes with equal lane/16) of every row
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            float r = ref[rb][v], sm = sum[rb][v];
+#pragma unroll
+            for (int o = 1; o < 16; o <<= 1) {
+                const float r2 = __shfl_xor(r, o, 64), s2 = __shfl_xor(sm, o, 64);
+                const float nr = fmaxf(r, r2);
+                const float a = sm > 0.f ? sm * exp2f(r - nr) : 0.f;
+                const float bb = s2 > 0.f ? s2 * exp2f(r2 - nr) : 0.f;
+                r = nr;
+                sm = a + bb;
+            }
+            const int row = row0 + 16 * rb + 4 * g + v;
+            if (m == 0 && row < R) stats[((int64_t)bh * n_chunks + c) * R + row] = make_float2(r, sm);
+        }
+}
+
+// pass 2: vote[g][j] = sum over the w rows of query head g of exp2(logit - lse)
+template <int RB>
+__global__ __launch_bounds__(256) void score_vote_mfma_kernel(
+    const bf16_bits* __restrict__ Q, const bf16_bits* __restrict__ K, const float* __restrict__ lse, int H,
+    int G, int N, int w, int64_t ks_b, int64_t ks_h, int64_t ks_t, int n_chunks, int chunk,
+    float* __restrict__ vote) {
+    __shared__ __align__(16) unsigned char lds[2][kTileBytes];
+    __shared__ float part[2][4 * RB][kTile];      // per 16-row block, per token of the tile
+    const int bh = blockIdx.x / n_chunks, c = blockIdx.x % n_chunks;
+    const int b = bh / H, h = bh % H;
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int m = lane & 15, g = lane >> 4;
+    const int R = G * w, P = N - w;
+    const bf16_bits* Kh = K + b * ks_b + h * ks_h;
+    const int row0 = wv * 16 * RB;
+    const float scale2 = kLog2e * rsqrtf((float)kD);
+    const int blocks_per_head = w >> 4;             // 16-row blocks per query head
+
+    bf16x8_t qa[RB][4];
+    load_q<RB>(qa, Q + (int64_t)bh * R * kD, row0, R, lane);
+    float nl[RB][4];                                // minus log-sum-exp (base 2) of this lane's rows
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const int row = row0 + 16 * rb + 4 * g + v;
+            nl[rb][v] = row < R ? -lse[(int64_t)bh * R + row] : 0.f;
+        }
+
+    const int t_begin = c * chunk, t_end = min(P, t_begin + chunk);
+    const int n_tiles = (t_end - t_begin + kTile - 1) / kTile;
+    float* vote_h = vote + (int64_t)bh * G * P;
+    KTileRegs regs;
+    ktile_load(regs, Kh, ks_t, t_begin, t_end, tid);
+    ktile_store(regs, lds[0], tid);
+    __syncthreads();
+    for (int it = 0; it < n_tiles; ++it) {
+        const int t0 = t_begin + it * kTile;
+        if (it + 1 < n_tiles) ktile_load(regs, Kh, ks_t, t0 + kTile, t_end, tid);
+        f32x4_t acc[4][RB];
+        tile_logits<RB>(acc, qa, lds[it & 1], lane);
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+            for (int st = 0; st < 4; ++st) {
+                float p = 0.f;
+#pragma unroll
+                for (int v = 0; v < 4; ++v) p += __builtin_amdgcn_exp2f(fmaf(acc[st][rb][v], scale2, nl[rb][v]));
+                p += __shfl_xor(p, 16, 64);
+                p += __shfl_xor(p, 32, 64);
+                if (g == 0) part[it & 1][wv * RB + rb][16 * st + m] = p;
+            }
+        if (it + 1 < n_tiles) ktile_store(regs, lds[(it + 1) & 1], tid);
+        __syncthreads();
+        // sum the blocks of each query head and store (part[it&1] is rewritten two tiles later)
+        for (int o = tid; o < G * kTile; o += 256) {
+            const int qh = o / kTile, t = o % kTile;
+            if (t0 + t < t_end) {
+                float v = 0.f;
+                for (int bl = 0; bl < blocks_per_head; ++bl) v += part[it & 1][qh * blocks_per_head + bl][t];
+                vote_h[(int64_t)qh * P + t0 + t] = v;
+            }
+        }
+    }
+}
+
 // merge: one thread per (head, row)
 __global__ __launch_bounds__(256) void score_lse_kernel(const float2* __restrict__ stats, int n_rows_total,
                                                         int R, int n_chunks, float* __restrict__ lse) {
@@ -182,7 +441,7 @@ ScorePlan plan_score(int B, int H, int G, int N, int w) {
     int nc = want < 1 ? 1 : want;
     if (nc > max_chunks) nc = max_chunks;
     int chunk = (N + nc - 1) / nc;
-    chunk = (chunk + 255) / 256 * 256;
+    chunk = (chunk + 255) / 256 * 256;             // whole 64-token tiles
     nc = (N + chunk - 1) / chunk;
     p.n_chunks = nc;
     p.chunk = chunk;
@@ -197,26 +456,55 @@ ScorePlan plan_score(int B, int H, int G, int N, int w) {
 template <typename T>
 static hipError_t run_score(const T* Q, const T* K, int B, int H, int G, int N, int w, int pool,
                             const int64_t ks[3], const ScorePlan& p, char* ws, float* score_out,
-                            const Env& env) {
+                            const Env& env, bool mfma) {
     hipStream_t s = env.s;
     const int BH = B * H, P = N - w;
     float2* stats = reinterpret_cast<float2*>(ws + p.stats_off);
     float* lse = reinterpret_cast<float*>(ws + p.lse_off);
     float* vote = reinterpret_cast<float*>(ws + p.vote_off);
-    const int threads1 = (p.R + 63) / 64 * 64;
-    env.begin("score_stats_alu");
-    score_stats_alu_kernel<T><<<dim3((unsigned)(BH * p.n_chunks)), dim3(threads1), 0, s>>>(
-        Q, K, H, G, N, w, ks[0], ks[1], ks[2], p.n_chunks, p.chunk, stats);
-    env.end();
+    const dim3 grid1((unsigned)(BH * p.n_chunks));
+    if constexpr (sizeof(T) == 2) {
+        if (mfma) {
+            env.begin("score_stats_mfma");
+            if (p.R <= 128)
+                score_stats_mfma_kernel<2><<<grid1, dim3(256), 0, s>>>(Q, K, H, p.R, N, w, ks[0], ks[1], ks[2],
+                                                                        p.n_chunks, p.chunk, stats);
+            else
+                score_stats_mfma_kernel<4><<<grid1, dim3(256), 0, s>>>(Q, K, H, p.R, N, w, ks[0], ks[1], ks[2],
+                                                                        p.n_chunks, p.chunk, stats);
+            env.end();
+        }
+    }
+    if (!mfma) {
+        const int threads1 = (p.R + 63) / 64 * 64;
+        env.begin("score_stats_alu");
+        score_stats_alu_kernel<T><<<grid1, dim3(threads1), 0, s>>>(Q, K, H, G, N, w, ks[0], ks[1], ks[2],
+                                                                   p.n_chunks, p.chunk, stats);
+        env.end();
+    }
     const int rows = BH * p.R;
     env.begin("score_lse");
     score_lse_kernel<<<dim3((rows + 255) / 256), dim3(256), 0, s>>>(stats, rows, p.R, p.n_chunks, lse);
     env.end();
     const int n_tiles = (P + 255) / 256;
-    env.begin("score_vote_alu");
-    score_vote_alu_kernel<T><<<dim3((unsigned)(BH * n_tiles)), dim3(256), 0, s>>>(
-        Q, K, lse, H, G, N, w, ks[0], ks[1], ks[2], n_tiles, vote);
-    env.end();
+    if constexpr (sizeof(T) == 2) {
+        if (mfma) {
+            env.begin("score_vote_mfma");
+            if (p.R <= 128)
+                score_vote_mfma_kernel<2><<<grid1, dim3(256), 0, s>>>(Q, K, lse, H, G, N, w, ks[0], ks[1], ks[2],
+                                                                       p.n_chunks, p.chunk, vote);
+            else
+                score_vote_mfma_kernel<4><<<grid1, dim3(256), 0, s>>>(Q, K, lse, H, G, N, w, ks[0], ks[1], ks[2],
+                                                                       p.n_chunks, p.chunk, vote);
+            env.end();
+        }
+    }
+    if (!mfma) {
+        env.begin("score_vote_alu");
+        score_vote_alu_kernel<T><<<dim3((unsigned)(BH * n_tiles)), dim3(256), 0, s>>>(
+            Q, K, lse, H, G, N, w, ks[0], ks[1], ks[2], n_tiles, vote);
+        env.end();
+    }
     env.begin("score_pool");
     score_pool_kernel<<<dim3((unsigned)(BH * n_tiles)), dim3(256), 0, s>>>(vote, G, P, pool / 2, n_tiles,
                                                                           score_out);
@@ -227,11 +515,14 @@ static hipError_t run_score(const T* Q, const T* K, int B, int H, int G, int N, 
 hipError_t launch_window_score(const void* Q, const void* K, uncomp_dtype dt, int B, int H, int G,
                                int N, int w, int pool, const int64_t ks[3], const ScorePlan& p,
                                char* ws, float* score_out, const Env& env) {
-    if (dt == UNCOMP_BF16)
+    if (dt == UNCOMP_BF16) {
+        // the MFMA kernels need whole 16-row blocks per query head and at most 256 rows per KV head
+        const bool mfma = !env.force_alu && (w % 16 == 0) && p.R <= 256;
         return run_score<bf16_bits>(static_cast<const bf16_bits*>(Q), static_cast<const bf16_bits*>(K), B, H,
-                                    G, N, w, pool, ks, p, ws, score_out, env);
+                                    G, N, w, pool, ks, p, ws, score_out, env, mfma);
+    }
     return run_score<float>(static_cast<const float*>(Q), static_cast<const float*>(K), B, H, G, N, w,
-                            pool, ks, p, ws, score_out, env);
+                            pool, ks, p, ws, score_out, env, false);
 }
 
 }  // namespace uncomp

@@ -153,6 +153,19 @@ def test_score_matches_oracle(ctx, dtype, B, H, G, N, w, pool):
     np.testing.assert_allclose(s.cpu().numpy(), ref, rtol=2e-5, atol=1e-12)
 
 
+@pytest.mark.parametrize("G,N,w", [(4, 5000, 32), (4, 9000, 64), (8, 4097, 32), (2, 3000, 16), (1, 700, 48)])
+def test_score_mfma_and_alu_paths_agree(ctx, G, N, w):
+    cfg = synth.tiny_config(dtype="bf16", B=1, H=2, G=G, N=N, w=w, rank_lo=2, rank_hi=64)
+    K, V, Q = synth.gen_all(cfg, seed0=G * N)
+    a = ctx.window_score(Q[0].to(DEV), K[0].to(DEV), G=G, pool=7)
+    ctx.set_kernel_path(plain_alu=True)
+    b = ctx.window_score(Q[0].to(DEV), K[0].to(DEV), G=G, pool=7)
+    ctx.set_kernel_path(plain_alu=False)
+    np.testing.assert_allclose(a.cpu().numpy(), b.cpu().numpy(), rtol=5e-6)
+    ref = O.window_score(to_f64(Q[0]), to_f64(K[0]), G=G, pool=7)
+    np.testing.assert_allclose(a.cpu().numpy(), ref, rtol=2e-5)
+
+
 def test_score_strided_keys(ctx):
     cfg = synth.tiny_config(dtype="bf16", B=2, H=2, G=2, N=200, w=8)
     K, V, Q = synth.gen_all(cfg, seed0=3)
