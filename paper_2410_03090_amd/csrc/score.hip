@@ -105,7 +105,6 @@ typedef float f32x4_t __attribute__((ext_vector_type(4)));
 constexpr int kTile = 64;                 // tokens per LDS tile
 constexpr int kRowBytes = 2 * kD + 16;    // padded LDS row
 constexpr int kTileBytes = kTile * kRowBytes;
-constexpr float kRescaleGap = 8.f;        // running reference may lag the true max by 2^8
 
 struct KTileRegs { uint4 v[4]; };
 
@@ -167,11 +166,24 @@ __device__ __forceinline__ void tile_logits(f32x4_t acc[4][RB], const bf16x8_t q
     }
 }
 
+// Lane layout: four rows of 16 lanes.  For four registers X, Y, Z, W returns, in lane row
+// 0 / 1 / 2 / 3, the sum over all four rows of X / Z / Y / W (per lane%16).
+// v_permlane32_swap(a,b) -> ([a.lo32, b.lo32], [a.hi32, b.hi32]);
+// v_permlane16_swap(a,b) -> ([a.r0, b.r0, a.r2, b.r2], [a.r1, b.r1, a.r3, b.r3]).
+__device__ __forceinline__ float reduce4_over_rows(float x, float y, float z, float w) {
+    auto s1 = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(y), false, false);
+    auto s2 = __builtin_amdgcn_permlane32_swap(__float_as_uint(z), __float_as_uint(w), false, false);
+    const float t1 = __uint_as_float(s1[0]) + __uint_as_float(s1[1]);
+    const float t2 = __uint_as_float(s2[0]) + __uint_as_float(s2[1]);
+    auto s3 = __builtin_amdgcn_permlane16_swap(__float_as_uint(t1), __float_as_uint(t2), false, false);
+    return __uint_as_float(s3[0]) + __uint_as_float(s3[1]);
+}
+
 }  // namespace
 
 // pass 1: running (reference, sum of exp2) per query row over one token chunk
 template <int RB>
-__global__ __launch_bounds__(256) void score_stats_mfma_kernel(
+__global__ __launch_bounds__(256, 2) void score_stats_mfma_kernel(
     const bf16_bits* __restrict__ Q, const bf16_bits* __restrict__ K, int H, int R, int N, int w,
     int64_t ks_b, int64_t ks_h, int64_t ks_t, int n_chunks, int chunk, float2* __restrict__ stats) {
     __shared__ __align__(16) unsigned char lds[2][kTileBytes];
@@ -187,16 +199,13 @@ __global__ __launch_bounds__(256) void score_stats_mfma_kernel(
     bf16x8_t qa[RB][4];
     load_q<RB>(qa, Q + (int64_t)bh * R * kD, row0, R, lane);
 
-    float ref[RB][4], sum[RB][4];
-    int last[RB][4];                       // last token each of this lane's rows may see
+    float nref[RB][4], sum[RB][4];         // minus the running reference, sum of exp2(logit - reference)
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
-            ref[rb][v] = -INFINITY;
+            nref[rb][v] = INFINITY;
             sum[rb][v] = 0.f;
-            const int row = row0 + 16 * rb + 4 * g + v;
-            last[rb][v] = row < R ? P + row % w : -1;
         }
 
     const int t_begin = c * chunk, t_end = min(N, t_begin + chunk);
@@ -211,51 +220,54 @@ __global__ __launch_bounds__(256) void score_stats_mfma_kernel(
         f32x4_t acc[4][RB];
         tile_logits<RB>(acc, qa, lds[it & 1], lane);
         const bool edge = t0 + kTile > P || t0 + kTile > t_end;   // causal window or ragged end inside
-        // 1. does any row need a new reference?
-        bool need = false;
-        float tmax[RB][4];
-#pragma unroll
-        for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                float mx = -INFINITY;
-#pragma unroll
-                for (int st = 0; st < 4; ++st) {
-                    float sv = acc[st][rb][v] * scale2;
-                    if (edge) {
-                        const int j = t0 + 16 * st + m;
-                        if (j >= t_end || j > last[rb][v]) sv = -INFINITY;
-                    }
-                    acc[st][rb][v] = sv;
-                    mx = fmaxf(mx, sv);
-                }
-                tmax[rb][v] = mx;
-                need |= mx > ref[rb][v] + kRescaleGap;
-            }
-        if (__builtin_amdgcn_ballot_w64(need) != 0ull) {
+        // Fast path: exponentials against the current reference; a row whose tile sum leaves
+        // [0, 2^10] (a logit far above the reference, or no reference yet) sends the wave to
+        // the slow path, which picks new references from the tile's maxima and redoes the tile.
+        bool redo = edge;
+        float ts[RB][4];
+        if (!edge) {
 #pragma unroll
             for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
-                for (int v = 0; v < 4; ++v)
-                    if (tmax[rb][v] > ref[rb][v]) {
-                        sum[rb][v] *= exp2f(ref[rb][v] - tmax[rb][v]);     // exp2(-inf) = 0 on first use
-                        ref[rb][v] = tmax[rb][v];
-                    }
-        }
-        // 2. accumulate
+                for (int v = 0; v < 4; ++v) {
+                    float t = 0.f;
 #pragma unroll
-        for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                const float r = ref[rb][v];
-#pragma unroll
-                for (int st = 0; st < 4; ++st) {
-                    const float sv = acc[st][rb][v];
-                    float e = __builtin_amdgcn_exp2f(sv - r);
-                    if (edge) e = sv == -INFINITY ? 0.f : e;
-                    sum[rb][v] += e;
+                    for (int st = 0; st < 4; ++st)
+                        t += __builtin_amdgcn_exp2f(fmaf(acc[st][rb][v], scale2, nref[rb][v]));
+                    ts[rb][v] = t;
+                    redo |= !(t <= 1024.f);
                 }
-            }
+        }
+        if (__builtin_amdgcn_ballot_w64(redo) == 0ull) {
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) sum[rb][v] += ts[rb][v];
+        } else {
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const int row = row0 + 16 * rb + 4 * g + v;
+                    const int last = row < R ? P + row % w : -1;     // last token this row may see
+                    float sv[4], mx = -INFINITY;
+#pragma unroll
+                    for (int st = 0; st < 4; ++st) {
+                        const int j = t0 + 16 * st + m;
+                        sv[st] = (j < t_end && j <= last) ? acc[st][rb][v] * scale2 : -INFINITY;
+                        mx = fmaxf(mx, sv[st]);
+                    }
+                    float r = -nref[rb][v];                            // current reference (-inf before the first token)
+                    if (mx > r) {
+                        sum[rb][v] *= exp2f(r - mx);                   // exp2(-inf) = 0 on first use
+                        r = mx;
+                        nref[rb][v] = -mx;
+                    }
+#pragma unroll
+                    for (int st = 0; st < 4; ++st)
+                        if (sv[st] != -INFINITY) sum[rb][v] += exp2f(sv[st] - r);
+                }
+        }
         if (it + 1 < n_tiles) ktile_store(regs, lds[(it + 1) & 1], tid);
         __syncthreads();
     }
@@ -265,7 +277,7 @@ __global__ __launch_bounds__(256) void score_stats_mfma_kernel(
     for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
-            float r = ref[rb][v], sm = sum[rb][v];
+            float r = -nref[rb][v], sm = sum[rb][v];
 #pragma unroll
             for (int o = 1; o < 16; o <<= 1) {
                 const float r2 = __shfl_xor(r, o, 64), s2 = __shfl_xor(sm, o, 64);
@@ -322,16 +334,20 @@ __global__ __launch_bounds__(256) void score_vote_mfma_kernel(
         f32x4_t acc[4][RB];
         tile_logits<RB>(acc, qa, lds[it & 1], lane);
 #pragma unroll
-        for (int rb = 0; rb < RB; ++rb)
+        for (int rb = 0; rb < RB; ++rb) {
+            float p[4];
 #pragma unroll
             for (int st = 0; st < 4; ++st) {
-                float p = 0.f;
+                p[st] = 0.f;
 #pragma unroll
-                for (int v = 0; v < 4; ++v) p += __builtin_amdgcn_exp2f(fmaf(acc[st][rb][v], scale2, nl[rb][v]));
-                p += __shfl_xor(p, 16, 64);
-                p += __shfl_xor(p, 32, 64);
-                if (g == 0) part[it & 1][wv * RB + rb][16 * st + m] = p;
+                for (int v = 0; v < 4; ++v) p[st] += __builtin_amdgcn_exp2f(fmaf(acc[st][rb][v], scale2, nl[rb][v]));
             }
+            // sum over the four lane groups (rows 4g..4g+3 of the block) with three register
+            // swaps; lane group g then holds the block total of sub-tile {0,2,1,3}[g]
+            const float tot = reduce4_over_rows(p[0], p[1], p[2], p[3]);
+            const int st_mine = ((g & 1) << 1) | (g >> 1);
+            part[it & 1][wv * RB + rb][16 * st_mine + m] = tot;
+        }
         if (it + 1 < n_tiles) ktile_store(regs, lds[(it + 1) & 1], tid);
         __syncthreads();
         // sum the blocks of each query head and store (part[it&1] is rewritten two tiles later)
