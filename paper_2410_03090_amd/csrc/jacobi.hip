@@ -7,9 +7,13 @@
 //      by the trace and keep the 128x128 result as fp32 columns in LDS;
 //   2. one-sided (Hestenes) Jacobi: plane rotations make the columns mutually orthogonal;
 //      for a symmetric positive semi-definite matrix the column norms then equal the
-//      eigenvalues.  Round-robin ordering gives 64 independent column pairs per round,
-//      each handled by four adjacent lanes (32 rows each) that combine their partial dot
-//      products by lane shuffles;
+//      eigenvalues.  Each pair of columns is handled by four adjacent lanes (32 rows each)
+//      that combine their partial dot products with DPP quad permutes, 16 pairs per wave
+//      per round.  The sweep is ordered in two levels so that waves rarely have to meet:
+//      the 128 columns form 8 half-blocks of 16; a sweep is 7 block rounds (round-robin
+//      over the half-blocks, each wave owning one pair of half-blocks and running its 16
+//      cross rounds on its own) plus one phase of pairs inside the half-blocks.  That is
+//      8 workgroup barriers per sweep for the same 127 rounds / 8128 rotations;
 //   3. column norms -> descending order by rank counting -> truncated entropy in fp64.
 #include "common.h"
 #include "device_utils.h"
@@ -22,7 +26,7 @@ constexpr int kThreads = 256;
 constexpr int kLd = kJacobiLd;
 // A sweep whose largest |cos| between paired columns stayed below this leaves, after its
 // own rotations, angles of the order of the square of it: eigenvalue errors at fp32 rounding.
-constexpr float kStopCos2 = 5e-3f * 5e-3f;
+constexpr float kStopCos2 = 1e-2f * 1e-2f;
 
 struct Smem {
     float A[kD * kLd];       // column j at A + j*kLd
@@ -41,9 +45,11 @@ __device__ __forceinline__ double block_sum(double v, double* red, int tid) {
     return red[0] + red[1] + red[2] + red[3];
 }
 
+// Sum over the four lanes of a quad (all four get the same bits): DPP quad_perm [1,0,3,2]
+// then [2,3,0,1].
 __device__ __forceinline__ float quad_sum(float v) {
-    v += __shfl_xor(v, 1, 64);
-    v += __shfl_xor(v, 2, 64);
+    v += __uint_as_float(__builtin_amdgcn_mov_dpp(__float_as_uint(v), 0xB1, 0xF, 0xF, true));
+    v += __uint_as_float(__builtin_amdgcn_mov_dpp(__float_as_uint(v), 0x4E, 0xF, 0xF, true));
     return v;
 }
 
@@ -98,62 +104,96 @@ __global__ __launch_bounds__(kThreads) void jacobi_entropy_kernel(
     __syncthreads();
 
     // ---- 2. one-sided Jacobi ---------------------------------------------------------------
-    const int slot = tid >> 2;     // which of the 64 pairs of a round
-    const int sub = tid & 3;       // which quarter of the rows (interleaved float4 groups)
-    for (int sweep = 0; sweep < kMaxSweeps; ++sweep) {
-        float max_cos2 = 0.f;
-        for (int r = 0; r < kD - 1; ++r) {
-            int p, q;
-            if (slot == 0) {
-                p = kD - 1;
-                q = r;
-            } else {
-                p = r + slot;
-                if (p >= kD - 1) p -= kD - 1;
-                q = r - slot;
-                if (q < 0) q += kD - 1;
-            }
-            float4* cp = reinterpret_cast<float4*>(sm.A + p * kLd);
-            float4* cq = reinterpret_cast<float4*>(sm.A + q * kLd);
-            float4 ap[8], aq[8];
-            float alpha = 0.f, beta = 0.f, gamma = 0.f;
+    const int wv = tid >> 6;
+    const int slot = (tid >> 2) & 15;   // which of the wave's 16 pairs
+    const int sub = tid & 3;            // which quarter of the rows (interleaved float4 groups)
+    float max_cos2 = 0.f;
+    auto rotate_pair = [&](int p, int q) {
+        float4* cp = reinterpret_cast<float4*>(sm.A + p * kLd);
+        float4* cq = reinterpret_cast<float4*>(sm.A + q * kLd);
+        float4 ap[8], aq[8];
+        float al[2] = {0.f, 0.f}, be[2] = {0.f, 0.f}, ga[2] = {0.f, 0.f};
+#pragma unroll
+        for (int v = 0; v < 8; ++v) {
+            ap[v] = cp[4 * v + sub];
+            aq[v] = cq[4 * v + sub];
+        }
+#pragma unroll
+        for (int v = 0; v < 8; ++v) {
+            al[v & 1] += ap[v].x * ap[v].x + ap[v].y * ap[v].y + ap[v].z * ap[v].z + ap[v].w * ap[v].w;
+            be[v & 1] += aq[v].x * aq[v].x + aq[v].y * aq[v].y + aq[v].z * aq[v].z + aq[v].w * aq[v].w;
+            ga[v & 1] += ap[v].x * aq[v].x + ap[v].y * aq[v].y + ap[v].z * aq[v].z + ap[v].w * aq[v].w;
+        }
+        const float alpha = quad_sum(al[0] + al[1]);
+        const float beta = quad_sum(be[0] + be[1]);
+        const float gamma = quad_sum(ga[0] + ga[1]);
+        const float ab = alpha * beta;
+        const float g2 = gamma * gamma;
+        if (ab > 0.f && g2 > 1e-14f * ab) {            // same decision in all four lanes
+            max_cos2 = fmaxf(max_cos2, g2 * __builtin_amdgcn_rcpf(ab));
+            // tan of the rotation angle: smaller root of t^2 + 2 zeta t - 1 = 0
+            const float zeta = (beta - alpha) * __builtin_amdgcn_rcpf(2.f * gamma);
+            const float t = copysignf(1.f, zeta) *
+                            __builtin_amdgcn_rcpf(fabsf(zeta) + __builtin_amdgcn_sqrtf(fmaf(zeta, zeta, 1.f)));
+            const float c = __builtin_amdgcn_rsqf(fmaf(t, t, 1.f));
+            const float sn = c * t;
 #pragma unroll
             for (int v = 0; v < 8; ++v) {
-                ap[v] = cp[4 * v + sub];
-                aq[v] = cq[4 * v + sub];
-                alpha += ap[v].x * ap[v].x + ap[v].y * ap[v].y + ap[v].z * ap[v].z + ap[v].w * ap[v].w;
-                beta += aq[v].x * aq[v].x + aq[v].y * aq[v].y + aq[v].z * aq[v].z + aq[v].w * aq[v].w;
-                gamma += ap[v].x * aq[v].x + ap[v].y * aq[v].y + ap[v].z * aq[v].z + ap[v].w * aq[v].w;
+                float4 np, nq;
+                np.x = c * ap[v].x - sn * aq[v].x;  nq.x = sn * ap[v].x + c * aq[v].x;
+                np.y = c * ap[v].y - sn * aq[v].y;  nq.y = sn * ap[v].y + c * aq[v].y;
+                np.z = c * ap[v].z - sn * aq[v].z;  nq.z = sn * ap[v].z + c * aq[v].z;
+                np.w = c * ap[v].w - sn * aq[v].w;  nq.w = sn * ap[v].w + c * aq[v].w;
+                cp[4 * v + sub] = np;
+                cq[4 * v + sub] = nq;
             }
-            alpha = quad_sum(alpha);
-            beta = quad_sum(beta);
-            gamma = quad_sum(gamma);
-            const float ab = alpha * beta;
-            const float g2 = gamma * gamma;
-            if (ab > 0.f && g2 > 1e-14f * ab) {        // same decision in all four lanes
-                max_cos2 = fmaxf(max_cos2, g2 / ab);
-                float zeta = (beta - alpha) / (2.f * gamma);
-                float t = copysignf(1.f, zeta) / (fabsf(zeta) + sqrtf(1.f + zeta * zeta));
-                float c = rsqrtf(1.f + t * t);
-                float s = c * t;
-#pragma unroll
-                for (int v = 0; v < 8; ++v) {
-                    float4 np, nq;
-                    np.x = c * ap[v].x - s * aq[v].x;  nq.x = s * ap[v].x + c * aq[v].x;
-                    np.y = c * ap[v].y - s * aq[v].y;  nq.y = s * ap[v].y + c * aq[v].y;
-                    np.z = c * ap[v].z - s * aq[v].z;  nq.z = s * ap[v].z + c * aq[v].z;
-                    np.w = c * ap[v].w - s * aq[v].w;  nq.w = s * ap[v].w + c * aq[v].w;
-                    cp[4 * v + sub] = np;
-                    cq[4 * v + sub] = nq;
+        }
+        // the wave's own LDS traffic is ordered; keep the compiler from moving it
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    };
+
+    for (int sweep = 0; sweep < kMaxSweeps; ++sweep) {
+        max_cos2 = 0.f;
+        // pairs inside half-blocks 2wv and 2wv+1: round-robin over 16 columns, 8 pairs each
+        {
+            const int hb = 2 * wv + (slot >> 3), k = slot & 7;
+            for (int t = 0; t < 15; ++t) {
+                int i, j;
+                if (k == 0) {
+                    i = 15;
+                    j = t;
+                } else {
+                    i = t + k;
+                    if (i >= 15) i -= 15;
+                    j = t - k;
+                    if (j < 0) j += 15;
                 }
+                rotate_pair(16 * hb + i, 16 * hb + j);
             }
+        }
+        __syncthreads();
+        // cross pairs: round-robin over the 8 half-blocks, one pair of half-blocks per wave
+        for (int br = 0; br < 7; ++br) {
+            int X, Y;
+            if (wv == 0) {
+                X = 7;
+                Y = br;
+            } else {
+                X = br + wv;
+                if (X >= 7) X -= 7;
+                Y = br - wv;
+                if (Y < 0) Y += 7;
+            }
+            for (int t = 0; t < 16; ++t) rotate_pair(16 * X + slot, 16 * Y + ((slot + t) & 15));
             __syncthreads();
         }
         // every thread learns the sweep's largest cos^2
         max_cos2 = wave_max(max_cos2);
         if ((tid & 63) == 0) sm.flag[tid >> 6] = max_cos2;
         __syncthreads();
-        float mc = fmaxf(fmaxf(sm.flag[0], sm.flag[1]), fmaxf(sm.flag[2], sm.flag[3]));
+        const float mc = fmaxf(fmaxf(sm.flag[0], sm.flag[1]), fmaxf(sm.flag[2], sm.flag[3]));
         __syncthreads();
         if (mc < kStopCos2) break;
     }
