@@ -50,6 +50,7 @@ def main():
     ap.add_argument("--config", type=int, default=3, help="index into BASELINE.json configs (default: the 128K prefill)")
     ap.add_argument("--seed", type=int, default=2410)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-overlap", action="store_true", help="keep every kernel on one stream")
     ap.add_argument("--cpu-heads", type=int, default=0, help="heads in the oracle sample (0 = auto)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -74,6 +75,7 @@ def main():
 
     ws = binding.Context.workspace_bytes(LB * H, N, D, LB, H, G, w)
     ctx = binding.Context(0, ws)
+    ctx.set_overlap(not args.no_overlap)
     i32 = dict(dtype=torch.int32, device=dev)
     ent = torch.empty(L, B, H, dtype=torch.float32, device=dev)
     bud = (torch.empty(L, B, H, **i32), torch.empty(L, B, H, **i32), torch.empty(L, **i32), torch.empty(L, **i32))

@@ -85,6 +85,17 @@ const char* uncomp_last_error(const uncomp_ctx* ctx);
 uncomp_status uncomp_profile(uncomp_ctx* ctx, int on);
 int uncomp_profile_read(uncomp_ctx* ctx, int max_records, const char** names, float* ms);
 
+/* Overlap mode (default off).  With on != 0, uncomp_head_entropy runs only its Gram kernel on
+ * the caller's stream and moves the eigen stage to a stream owned by the context (ordered
+ * after the Gram kernel by an event); a following uncomp_assign_budgets goes to that stream
+ * too, so both run beside the uncomp_window_score kernels of the caller's stream.  The next
+ * uncomp_select_gather, or an explicit uncomp_join, makes the caller's stream wait for them.
+ * Until then entropy_out / eig_out / the budget outputs are NOT ordered with the caller's
+ * stream.  The workspace must hold the entropy and scoring regions side by side, which is
+ * what uncomp_workspace_bytes reports. */
+uncomp_status uncomp_set_overlap(uncomp_ctx* ctx, int on);
+uncomp_status uncomp_join(uncomp_ctx* ctx, void* stream);
+
 /* Kernel selection for testing: plain_alu != 0 makes the bf16 calls use the plain-ALU
  * kernels (the ones fp32 inputs always use) instead of the MFMA kernels.  Default 0. */
 uncomp_status uncomp_set_kernel_path(uncomp_ctx* ctx, int plain_alu);

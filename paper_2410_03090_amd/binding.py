@@ -23,7 +23,7 @@ DEFAULT_FLAGS = CENTER | TRUNC_RENORM
 
 EXPORTS = (
     "uncomp_create", "uncomp_destroy", "uncomp_workspace_bytes", "uncomp_last_error",
-    "uncomp_profile", "uncomp_profile_read", "uncomp_set_kernel_path",
+    "uncomp_profile", "uncomp_profile_read", "uncomp_set_kernel_path", "uncomp_set_overlap", "uncomp_join",
     "uncomp_head_entropy", "uncomp_assign_budgets", "uncomp_window_score", "uncomp_select_gather",
 )
 
@@ -58,6 +58,10 @@ def load_library() -> ctypes.CDLL:
     lib.uncomp_last_error.restype = c.c_char_p
     lib.uncomp_profile.argtypes = [vp, i32]
     lib.uncomp_profile.restype = i32
+    lib.uncomp_set_overlap.argtypes = [vp, i32]
+    lib.uncomp_set_overlap.restype = i32
+    lib.uncomp_join.argtypes = [vp, vp]
+    lib.uncomp_join.restype = i32
     lib.uncomp_set_kernel_path.argtypes = [vp, i32]
     lib.uncomp_set_kernel_path.restype = i32
     lib.uncomp_profile_read.argtypes = [vp, i32, c.POINTER(c.c_char_p), c.POINTER(f32)]
@@ -126,6 +130,12 @@ class Context:
 
     def profile(self, on: bool):
         self._check(self.lib.uncomp_profile(self.handle, 1 if on else 0))
+
+    def set_overlap(self, on: bool):
+        self._check(self.lib.uncomp_set_overlap(self.handle, 1 if on else 0))
+
+    def join(self):
+        self._check(self.lib.uncomp_join(self.handle, _stream()))
 
     def set_kernel_path(self, plain_alu: bool):
         self._check(self.lib.uncomp_set_kernel_path(self.handle, 1 if plain_alu else 0))

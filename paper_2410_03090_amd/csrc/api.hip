@@ -57,8 +57,15 @@ uncomp_status uncomp_create(uncomp_ctx** ctx_out, int device, size_t workspace_b
         ctx->num_cu = prop.multiProcessorCount;
         e = hipMalloc(reinterpret_cast<void**>(&ctx->ws), ctx->ws_bytes);
     }
+    if (e == hipSuccess) e = hipStreamCreateWithFlags(&ctx->side, hipStreamNonBlocking);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&ctx->ev_fork, hipEventDisableTiming);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&ctx->ev_join, hipEventDisableTiming);
     (void)hipSetDevice(prev);
     if (e != hipSuccess) {
+        if (ctx->ev_fork) (void)hipEventDestroy(ctx->ev_fork);
+        if (ctx->ev_join) (void)hipEventDestroy(ctx->ev_join);
+        if (ctx->side) (void)hipStreamDestroy(ctx->side);
+        if (ctx->ws) (void)hipFree(ctx->ws);
         delete ctx;
         return UNCOMP_ERR_HIP;
     }
@@ -69,6 +76,12 @@ uncomp_status uncomp_create(uncomp_ctx** ctx_out, int device, size_t workspace_b
 uncomp_status uncomp_destroy(uncomp_ctx* ctx) {
     if (ctx == nullptr) return UNCOMP_ERR_INVALID_ARG;
     hipError_t e = hipSuccess;
+    if (ctx->side != nullptr) {
+        (void)hipStreamSynchronize(ctx->side);
+        (void)hipStreamDestroy(ctx->side);
+    }
+    if (ctx->ev_fork != nullptr) (void)hipEventDestroy(ctx->ev_fork);
+    if (ctx->ev_join != nullptr) (void)hipEventDestroy(ctx->ev_join);
     if (ctx->ws != nullptr) e = hipFree(ctx->ws);
     for (int i = 0; i < ctx->prof.n_events; ++i) {
         (void)hipEventDestroy(ctx->prof.start[i]);
@@ -80,15 +93,10 @@ uncomp_status uncomp_destroy(uncomp_ctx* ctx) {
 
 size_t uncomp_workspace_bytes(int n_mat, int N, int D, int B, int H, int G, int w) {
     (void)D;
+    // three regions that may be live at once in overlap mode: budgets | entropy | score
     size_t need = kBudgetScratch;
-    if (n_mat > 0 && N > 0) {
-        size_t b = plan_entropy(n_mat, N).bytes;
-        if (b > need) need = b;
-    }
-    if (B > 0 && H > 0 && G > 0 && N > 0 && w > 0 && w < N) {
-        size_t b = plan_score(B, H, G, N, w).bytes;
-        if (b > need) need = b;
-    }
+    if (n_mat > 0 && N > 0) need += plan_entropy(n_mat, N).bytes;
+    if (B > 0 && H > 0 && G > 0 && N > 0 && w > 0 && w < N) need += plan_score(B, H, G, N, w).bytes;
     return need;
 }
 
@@ -96,6 +104,22 @@ uncomp_status uncomp_profile(uncomp_ctx* ctx, int on) {
     if (ctx == nullptr) return UNCOMP_ERR_INVALID_ARG;
     ctx->prof.on = on != 0;
     ctx->prof.n = 0;
+    return UNCOMP_OK;
+}
+
+uncomp_status uncomp_set_overlap(uncomp_ctx* ctx, int on) {
+    if (ctx == nullptr) return UNCOMP_ERR_INVALID_ARG;
+    ctx->overlap = on != 0;
+    return UNCOMP_OK;
+}
+
+uncomp_status uncomp_join(uncomp_ctx* ctx, void* stream) {
+    if (ctx == nullptr) return UNCOMP_ERR_INVALID_ARG;
+    if (!ctx->side_pending) return UNCOMP_OK;
+    hipError_t e = hipEventRecord(ctx->ev_join, ctx->side);
+    if (e == hipSuccess) e = hipStreamWaitEvent(static_cast<hipStream_t>(stream), ctx->ev_join, 0);
+    if (e != hipSuccess) return hip_fail(ctx, e, "join");
+    ctx->side_pending = false;
     return UNCOMP_OK;
 }
 
@@ -136,12 +160,23 @@ uncomp_status uncomp_head_entropy(uncomp_ctx* ctx, const void* X, uncomp_dtype d
         return fail(ctx, UNCOMP_ERR_INVALID_ARG, "head_entropy: strides must be multiples of 8 elements, ldx >= D, X 16-byte aligned");
     if ((int64_t)n_mat * 64 > 0x7fffffffLL) return fail(ctx, UNCOMP_ERR_UNSUPPORTED, "head_entropy: too many matrices");
     EntropyPlan p = plan_entropy(n_mat, N);
-    if (p.bytes > ctx->ws_bytes)
-        return fail(ctx, UNCOMP_ERR_WORKSPACE, "head_entropy: needs %zu workspace bytes, context has %zu", p.bytes, ctx->ws_bytes);
+    if (kBudgetScratch + p.bytes > ctx->ws_bytes)
+        return fail(ctx, UNCOMP_ERR_WORKSPACE, "head_entropy: needs %zu workspace bytes, context has %zu",
+                    kBudgetScratch + p.bytes, ctx->ws_bytes);
+    char* ws = ctx->ws + kBudgetScratch;
+    ctx->score_ws_off = kBudgetScratch + p.bytes;
     Env env{static_cast<hipStream_t>(stream), &ctx->prof, ctx->force_alu};
-    hipError_t e = launch_gram(X, dtype, n_mat, N, mat_stride, ldx, p, ctx->ws, env);
+    hipError_t e = launch_gram(X, dtype, n_mat, N, mat_stride, ldx, p, ws, env);
     if (e != hipSuccess) return hip_fail(ctx, e, "head_entropy: gram launch");
-    e = launch_jacobi_entropy(n_mat, N, k_trunc, flags, p, ctx->ws, entropy_out, eig_out, env);
+    if (ctx->overlap) {
+        // the eigen stage moves to the side stream, ordered after the Gram kernel
+        e = hipEventRecord(ctx->ev_fork, env.s);
+        if (e == hipSuccess) e = hipStreamWaitEvent(ctx->side, ctx->ev_fork, 0);
+        if (e != hipSuccess) return hip_fail(ctx, e, "head_entropy: fork");
+        env.s = ctx->side;
+        ctx->side_pending = true;
+    }
+    e = launch_jacobi_entropy(n_mat, N, k_trunc, flags, p, ws, entropy_out, eig_out, env);
     if (e != hipSuccess) return hip_fail(ctx, e, "head_entropy: eigen launch");
     return UNCOMP_OK;
 }
@@ -165,9 +200,11 @@ uncomp_status uncomp_assign_budgets(uncomp_ctx* ctx, const float* entropy, int n
     if (step < 0 || delta_n < 0 || n_max < 0) return fail(ctx, UNCOMP_ERR_INVALID_ARG, "assign_budgets: negative n_max, step or delta_n");
     if ((int64_t)n_layer * n_batch * H > 0x7fffffffLL) return fail(ctx, UNCOMP_ERR_UNSUPPORTED, "assign_budgets: too many heads");
     if (!(eps == eps)) return fail(ctx, UNCOMP_ERR_INVALID_ARG, "assign_budgets: eps is NaN");
+    // in overlap mode the entropies are being produced on the side stream: follow them there
+    hipStream_t bs = (ctx->overlap && ctx->side_pending) ? ctx->side : static_cast<hipStream_t>(stream);
     hipError_t e = launch_budgets(entropy, n_layer, n_batch, H, M, n_max, step, N, w, eps, delta_n, flags,
                                   head_budget, head_group, layer_group, layer_tokens, ctx->ws,
-                                  Env{static_cast<hipStream_t>(stream), &ctx->prof, ctx->force_alu});
+                                  Env{bs, &ctx->prof, ctx->force_alu});
     if (e != hipSuccess) return hip_fail(ctx, e, "assign_budgets: launch");
     return UNCOMP_OK;
 }
@@ -189,9 +226,12 @@ uncomp_status uncomp_window_score(uncomp_ctx* ctx, const void* Qwin, const void*
         return fail(ctx, UNCOMP_ERR_INVALID_ARG, "window_score: strides must be multiples of 8 elements, token stride >= D, 16-byte aligned pointers");
     if ((int64_t)B * H * ((N + 255) / 256) > 0x7fffffffLL) return fail(ctx, UNCOMP_ERR_UNSUPPORTED, "window_score: problem too large");
     ScorePlan p = plan_score(B, H, G, N, w);
-    if (p.bytes > ctx->ws_bytes)
-        return fail(ctx, UNCOMP_ERR_WORKSPACE, "window_score: needs %zu workspace bytes, context has %zu", p.bytes, ctx->ws_bytes);
-    hipError_t e = launch_window_score(Qwin, K, dtype, B, H, G, N, w, pool, k_strides, p, ctx->ws, score_out,
+    // keep clear of the entropy region while side-stream work may still read it
+    const size_t off = ctx->side_pending ? ctx->score_ws_off : kBudgetScratch;
+    if (off + p.bytes > ctx->ws_bytes)
+        return fail(ctx, UNCOMP_ERR_WORKSPACE, "window_score: needs %zu workspace bytes, context has %zu",
+                    off + p.bytes, ctx->ws_bytes);
+    hipError_t e = launch_window_score(Qwin, K, dtype, B, H, G, N, w, pool, k_strides, p, ctx->ws + off, score_out,
                                        Env{static_cast<hipStream_t>(stream), &ctx->prof, ctx->force_alu});
     if (e != hipSuccess) return hip_fail(ctx, e, "window_score: launch");
     return UNCOMP_OK;
@@ -221,6 +261,8 @@ uncomp_status uncomp_select_gather(uncomp_ctx* ctx, const float* score, const in
     }
     if ((int64_t)B * H * ((cap + 7) / 8) > 0x7fffffffLL) return fail(ctx, UNCOMP_ERR_UNSUPPORTED, "select_gather: problem too large");
     static const int64_t zero_strides[3] = {0, 0, 0};
+    uncomp_status js = uncomp_join(ctx, stream);
+    if (js != UNCOMP_OK) return js;
     hipError_t e = launch_select_gather(score, budget, all_kv ? K : nullptr, V, dtype, B, H, N, w,
                                         all_kv ? kv_strides : zero_strides, cap, K_out, V_out, idx_out, len_out,
                                         Env{static_cast<hipStream_t>(stream), &ctx->prof, ctx->force_alu});

@@ -30,6 +30,13 @@ struct uncomp_ctx {
     char err[256];
     uncomp::Profiler prof;
     bool force_alu = false;
+    // overlap mode: the eigen stage and the budget kernels run on `side`, beside the scoring
+    // kernels of the caller's stream, and are joined before the selection kernels
+    bool overlap = false;
+    bool side_pending = false;       // work enqueued on `side` that the caller's stream has not waited for
+    hipStream_t side = nullptr;
+    hipEvent_t ev_fork = nullptr, ev_join = nullptr;
+    size_t score_ws_off = 0;         // where the scoring workspace starts (after the entropy region)
 };
 
 namespace uncomp {

@@ -276,6 +276,28 @@ def test_determinism(ctx):
         assert torch.equal(x, y)
 
 
+def test_overlap_mode_gives_identical_results(ctx):
+    # eigen stage + budgets on the context's side stream, joined before selection
+    from paper_2410_03090_amd import binding
+    cfg = synth.tiny_config(dtype="bf16", L=3, B=2, H=4, G=4, N=5000, w=32, avg_budget=256, M=4, rank_hi=64)
+    K, V, Q = synth.gen_all(cfg, seed0=21)
+    Kd, Vd, Qd = K.to(DEV), V.to(DEV), Q.to(DEV)
+    a = _run_path(ctx, cfg, Kd, Vd, Qd)
+    ws = binding.Context.workspace_bytes(cfg.L * cfg.B * cfg.H, cfg.N, cfg.D, cfg.L * cfg.B, cfg.H, cfg.G, cfg.w)
+    c2 = binding.Context(0, ws)
+    c2.set_overlap(True)
+    for _ in range(3):                      # repeated steps reuse the workspace regions
+        b = _run_path(c2, cfg, Kd, Vd, Qd)
+        for x, y in zip(a, b):
+            assert torch.equal(x, y)
+    # an explicit join orders the entropies with the caller's stream
+    ent = c2.head_entropy(Kd.reshape(-1, cfg.N, cfg.D))
+    c2.join()
+    torch.cuda.synchronize()
+    assert torch.equal(ent.reshape(a[0].shape), a[0])
+    c2.close()
+
+
 # ------------------------------------------------------------------------- error paths
 def test_argument_errors(ctx):
     from paper_2410_03090_amd import binding
