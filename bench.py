@@ -51,6 +51,8 @@ def main():
     ap.add_argument("--seed", type=int, default=2410)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-overlap", action="store_true", help="keep every kernel on one stream")
+    ap.add_argument("--calib-copy-mib", type=int, default=0,
+                    help="also run one plain device copy of this many MiB (reference for HBM byte counters)")
     ap.add_argument("--cpu-heads", type=int, default=0, help="heads in the oracle sample (0 = auto)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -90,6 +92,12 @@ def main():
         ctx.window_score(Qf, Kf, G, cfg.pool, out=score)
         ctx.select_gather(score, bud[0].reshape(LB, H), Kf, Vf, w, cap, out=outs)
 
+    if args.calib_copy_mib:
+        src = torch.empty(args.calib_copy_mib << 20, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
