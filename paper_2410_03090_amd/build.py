@@ -12,6 +12,7 @@ SOURCES = ["api.hip", "gram.hip", "jacobi.hip", "budgets.hip", "score.hip", "sel
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",   # no packed-fp32 VALU forms
+    "-mllvm", "-amdgpu-mfma-vgpr-form=1",                           # MFMA results straight into VGPRs (no AGPR copies)
     "-Wall", "-Wno-unused-function",
 ]
 
