@@ -431,21 +431,50 @@ __global__ __launch_bounds__(256) void score_vote_alu_kernel(
     }
 }
 
-// pool + group sum: one thread per prefix token
+// pool + group sum.  A workgroup takes 1024 consecutive tokens of one KV head; the votes of up
+// to four query heads at a time (plus `half` tokens either side, -inf outside [0, P)) are staged
+// in LDS, each thread forms the running maxima of four consecutive tokens from 4 + 2*half staged
+// values per query head and adds them up.
+constexpr int kPoolTile = 1024;
+constexpr int kPoolMaxHalf = 7;
+
 __global__ __launch_bounds__(256) void score_pool_kernel(const float* __restrict__ vote, int G, int P,
                                                          int half, int n_tiles, float* __restrict__ score) {
+    __shared__ float sh[4][kPoolTile + 2 * kPoolMaxHalf + 2];
     const int bh = blockIdx.x / n_tiles, tile = blockIdx.x % n_tiles;
-    const int j = tile * 256 + threadIdx.x;
-    if (j >= P) return;
-    const int lo = max(0, j - half), hi = min(P - 1, j + half);
-    float total = 0.f;
-    for (int g = 0; g < G; ++g) {
-        const float* vg = vote + ((int64_t)bh * G + g) * P;
-        float mx = vg[lo];
-        for (int jj = lo + 1; jj <= hi; ++jj) mx = fmaxf(mx, vg[jj]);
-        total += mx;
+    const int tile0 = tile * kPoolTile;
+    const int span = kPoolTile + 2 * kPoolMaxHalf;
+    float total[4] = {0.f, 0.f, 0.f, 0.f};
+    for (int g0 = 0; g0 < G; g0 += 4) {
+        const int ng = min(4, G - g0);
+        for (int gi = 0; gi < ng; ++gi) {
+            const float* vg = vote + ((int64_t)bh * G + g0 + gi) * P;
+            for (int idx = threadIdx.x; idx < span; idx += 256) {
+                const int j = tile0 - half + idx;
+                sh[gi][idx] = (j >= 0 && j < P && idx < kPoolTile + 2 * half) ? vg[j] : -INFINITY;
+            }
+        }
+        __syncthreads();
+        for (int gi = 0; gi < ng; ++gi) {
+            float v[4 + 2 * kPoolMaxHalf];
+#pragma unroll
+            for (int k = 0; k < 4 + 2 * kPoolMaxHalf; ++k) v[k] = sh[gi][4 * threadIdx.x + k];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                float mx = v[e];
+#pragma unroll
+                for (int d = 1; d <= 2 * kPoolMaxHalf; ++d)
+                    if (d <= 2 * half) mx = fmaxf(mx, v[e + d]);
+                total[e] += mx;
+            }
+        }
+        __syncthreads();
     }
-    score[(int64_t)bh * P + j] = total;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const int j = tile0 + 4 * threadIdx.x + e;
+        if (j < P) score[(int64_t)bh * P + j] = total[e];
+    }
 }
 
 ScorePlan plan_score(int B, int H, int G, int N, int w) {
@@ -503,6 +532,7 @@ static hipError_t run_score(const T* Q, const T* K, int B, int H, int G, int N, 
     score_lse_kernel<<<dim3((rows + 255) / 256), dim3(256), 0, s>>>(stats, rows, p.R, p.n_chunks, lse);
     env.end();
     const int n_tiles = (P + 255) / 256;
+    const int n_pool_tiles = (P + kPoolTile - 1) / kPoolTile;
     if constexpr (sizeof(T) == 2) {
         if (mfma) {
             env.begin("score_vote_mfma");
@@ -522,8 +552,8 @@ static hipError_t run_score(const T* Q, const T* K, int B, int H, int G, int N, 
         env.end();
     }
     env.begin("score_pool");
-    score_pool_kernel<<<dim3((unsigned)(BH * n_tiles)), dim3(256), 0, s>>>(vote, G, P, pool / 2, n_tiles,
-                                                                          score_out);
+    score_pool_kernel<<<dim3((unsigned)(BH * n_pool_tiles)), dim3(256), 0, s>>>(vote, G, P, pool / 2,
+                                                                               n_pool_tiles, score_out);
     env.end();
     return hipGetLastError();
 }

@@ -3,8 +3,8 @@
 //
 // select_kernel, one workgroup per (batch, head):
 //   - the k-th largest score is found exactly by a most-significant-digit radix select on
-//     an order-preserving 32-bit image of the float (digits of 11, 11 and 10 bits, one
-//     LDS histogram per digit);
+//     an order-preserving 32-bit image of the float: digits of up to 11 bits, starting at the
+//     highest bit in which the head's keys differ, one LDS histogram per digit;
 //   - one more ordered pass writes the kept positions in ascending order: everything above
 //     the threshold, and of the scores equal to it the first (k - #above) by position;
 //   - the w window positions follow.
@@ -82,18 +82,65 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const float* __rest
     uint32_t thr = 0;                         // key of the k-th largest score
     uint32_t need_eq = 0;                     // how many keys equal to thr are kept
     if (k > 0 && k < P) {
-        uint32_t prefix = 0, prefix_mask = 0;
+        // Range of the keys first: the radix digits then start at the highest bit in which
+        // any two keys differ.  Scores of one head usually share their exponent and leading
+        // mantissa bits; digits taken from the very top would put every key in one counter.
+        uint32_t kmin = 0xffffffffu, kmax = 0u;
+        for (int j0 = tid; j0 < P; j0 += 8 * kSelThreads) {
+            float v[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int j = j0 + e * kSelThreads;
+                v[e] = j < P ? sc[j] : sc[tid < P ? tid : 0];
+            }
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const uint32_t key = order_key(v[e]);
+                kmin = key < kmin ? key : kmin;
+                kmax = key > kmax ? key : kmax;
+            }
+        }
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) {
+            const uint32_t a = __shfl_xor(kmin, o, 64), c = __shfl_xor(kmax, o, 64);
+            kmin = a < kmin ? a : kmin;
+            kmax = c > kmax ? c : kmax;
+        }
+        if ((tid & 63) == 0) {
+            sm.wsum[tid >> 6] = kmin;
+            sm.hist[tid >> 6] = kmax;
+        }
+        __syncthreads();
+        for (int i = 0; i < kSelWaves; ++i) {
+            kmin = sm.wsum[i] < kmin ? sm.wsum[i] : kmin;
+            kmax = sm.hist[i] > kmax ? sm.hist[i] : kmax;
+        }
+        __syncthreads();
+
+        int bits_left = kmin == kmax ? 0 : 32 - __builtin_clz(kmin ^ kmax);   // low bits that can differ
+        uint32_t prefix_mask = bits_left >= 32 ? 0u : ~((1u << bits_left) - 1u);
+        uint32_t prefix = kmax & prefix_mask;
         uint32_t remaining = (uint32_t)k;     // rank still to be located among matching keys
-        const int shifts[3] = {21, 10, 0};
-        const int widths[3] = {11, 11, 10};
-        for (int pass = 0; pass < 3; ++pass) {
-            const int shift = shifts[pass];
-            const uint32_t nb = 1u << widths[pass];
+        while (bits_left > 0) {
+            const int width = bits_left < 11 ? bits_left : 11;
+            const int shift = bits_left - width;
+            const uint32_t nb = 1u << width;
             for (int i = tid; i < kBins; i += kSelThreads) sm.hist[i] = 0;
             __syncthreads();
-            for (int j = tid; j < P; j += kSelThreads) {
-                uint32_t key = order_key(sc[j]);
-                if ((key & prefix_mask) == prefix) atomicAdd(&sm.hist[(key >> shift) & (nb - 1)], 1u);
+            // eight independent loads per thread in flight before any of them is consumed
+            for (int j0 = tid; j0 < P; j0 += 8 * kSelThreads) {
+                float v[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const int j = j0 + e * kSelThreads;
+                    v[e] = j < P ? sc[j] : 0.f;
+                }
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const uint32_t key = order_key(v[e]);
+                    if (j0 + e * kSelThreads < P && (key & prefix_mask) == prefix)
+                        atomicAdd(&sm.hist[(key >> shift) & (nb - 1)], 1u);
+                }
             }
             __syncthreads();
             // walk the digits from the top: thread t owns digits nb-1-2t and nb-2-2t
@@ -114,6 +161,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const float* __rest
             prefix |= sm.bcast[0] << shift;
             prefix_mask |= (nb - 1) << shift;
             remaining = sm.bcast[1];
+            bits_left = shift;
             __syncthreads();
         }
         thr = prefix;
@@ -124,14 +172,24 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const float* __rest
     if (k > 0) {
         const bool all = (k >= P);
         uint32_t kept_gt = 0, seen_eq = 0;    // running totals over the positions already passed
+        float nxt[4];                         // scores of the next step, loaded one step ahead
+#pragma unroll
+        for (int e = 0; e < 4; ++e) nxt[e] = tid * 4 + e < P ? sc[tid * 4 + e] : 0.f;
         for (int base = 0; base < P; base += kSelThreads * 4) {
             const int j0 = base + tid * 4;
+            float cur[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                cur[e] = nxt[e];
+                const int jn = j0 + kSelThreads * 4 + e;
+                nxt[e] = jn < P ? sc[jn] : 0.f;
+            }
             uint32_t gt[4], eq[4], ngt = 0, neq = 0;
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 gt[e] = eq[e] = 0;
                 if (j0 + e < P) {
-                    uint32_t key = order_key(sc[j0 + e]);
+                    uint32_t key = order_key(cur[e]);
                     gt[e] = (all || key > thr) ? 1u : 0u;
                     eq[e] = (!all && key == thr) ? 1u : 0u;
                 }
