@@ -108,6 +108,14 @@ constexpr int kTileBytes = kTile * kRowBytes;
 
 struct KTileRegs { uint4 v[4]; };
 
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for every
+// outstanding global load, which would cut the key-tile prefetch short at each tile.
+__device__ __forceinline__ void lds_barrier() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
 // 64 tokens x 256 B = 1024 16-byte pieces, four per thread; tokens >= t_end read as zero
 __device__ __forceinline__ void ktile_load(KTileRegs& r, const bf16_bits* Kh, int64_t ks_t, int t0, int t_end,
                                            int tid) {
@@ -210,13 +218,17 @@ __global__ __launch_bounds__(256, 2) void score_stats_mfma_kernel(
 
     const int t_begin = c * chunk, t_end = min(N, t_begin + chunk);
     const int n_tiles = (t_end - t_begin + kTile - 1) / kTile;
-    KTileRegs regs;
-    ktile_load(regs, Kh, ks_t, t_begin, t_end, tid);
-    ktile_store(regs, lds[0], tid);
-    __syncthreads();
+    // Key tiles travel global -> registers -> LDS two tiles ahead of their use: while tile
+    // `it` is computed from one LDS buffer, tile it+1 waits in registers to be stored into the
+    // other buffer and the loads of tile it+2 are in flight.
+    KTileRegs n1, n2;
+    ktile_load(n1, Kh, ks_t, t_begin, t_end, tid);
+    ktile_store(n1, lds[0], tid);
+    ktile_load(n1, Kh, ks_t, t_begin + kTile, t_end, tid);
+    lds_barrier();
     for (int it = 0; it < n_tiles; ++it) {
         const int t0 = t_begin + it * kTile;
-        if (it + 1 < n_tiles) ktile_load(regs, Kh, ks_t, t0 + kTile, t_end, tid);
+        if (it + 2 < n_tiles) ktile_load(n2, Kh, ks_t, t0 + 2 * kTile, t_end, tid);
         f32x4_t acc[4][RB];
         tile_logits<RB>(acc, qa, lds[it & 1], lane);
         const bool edge = t0 + kTile > P || t0 + kTile > t_end;   // causal window or ragged end inside
@@ -268,8 +280,9 @@ __global__ __launch_bounds__(256, 2) void score_stats_mfma_kernel(
                         if (sv[st] != -INFINITY) sum[rb][v] += exp2f(sv[st] - r);
                 }
         }
-        if (it + 1 < n_tiles) ktile_store(regs, lds[(it + 1) & 1], tid);
-        __syncthreads();
+        if (it + 1 < n_tiles) ktile_store(n1, lds[(it + 1) & 1], tid);
+        lds_barrier();
+        n1 = n2;
     }
 
     // combine the 16 token slots (lanes with equal lane/16) of every row
@@ -324,13 +337,14 @@ __global__ __launch_bounds__(256) void score_vote_mfma_kernel(
     const int t_begin = c * chunk, t_end = min(P, t_begin + chunk);
     const int n_tiles = (t_end - t_begin + kTile - 1) / kTile;
     float* vote_h = vote + (int64_t)bh * G * P;
-    KTileRegs regs;
-    ktile_load(regs, Kh, ks_t, t_begin, t_end, tid);
-    ktile_store(regs, lds[0], tid);
-    __syncthreads();
+    KTileRegs n1, n2;
+    ktile_load(n1, Kh, ks_t, t_begin, t_end, tid);
+    ktile_store(n1, lds[0], tid);
+    ktile_load(n1, Kh, ks_t, t_begin + kTile, t_end, tid);
+    lds_barrier();
     for (int it = 0; it < n_tiles; ++it) {
         const int t0 = t_begin + it * kTile;
-        if (it + 1 < n_tiles) ktile_load(regs, Kh, ks_t, t0 + kTile, t_end, tid);
+        if (it + 2 < n_tiles) ktile_load(n2, Kh, ks_t, t0 + 2 * kTile, t_end, tid);
         f32x4_t acc[4][RB];
         tile_logits<RB>(acc, qa, lds[it & 1], lane);
 #pragma unroll
@@ -348,15 +362,24 @@ __global__ __launch_bounds__(256) void score_vote_mfma_kernel(
             const int st_mine = ((g & 1) << 1) | (g >> 1);
             part[it & 1][wv * RB + rb][16 * st_mine + m] = tot;
         }
-        if (it + 1 < n_tiles) ktile_store(regs, lds[(it + 1) & 1], tid);
-        __syncthreads();
+        if (it + 1 < n_tiles) ktile_store(n1, lds[(it + 1) & 1], tid);
+        lds_barrier();
+        n1 = n2;
         // sum the blocks of each query head and store (part[it&1] is rewritten two tiles later)
         for (int o = tid; o < G * kTile; o += 256) {
             const int qh = o / kTile, t = o % kTile;
             if (t0 + t < t_end) {
-                float v = 0.f;
-                for (int bl = 0; bl < blocks_per_head; ++bl) v += part[it & 1][qh * blocks_per_head + bl][t];
-                vote_h[(int64_t)qh * P + t0 + t] = v;
+                const float* pp = &part[it & 1][qh * blocks_per_head][t];
+                float v0 = 0.f, v1 = 0.f, v2 = 0.f, v3 = 0.f;
+                int bl = 0;
+                for (; bl + 4 <= blocks_per_head; bl += 4) {     // four independent LDS reads at a time
+                    v0 += pp[(bl + 0) * kTile];
+                    v1 += pp[(bl + 1) * kTile];
+                    v2 += pp[(bl + 2) * kTile];
+                    v3 += pp[(bl + 3) * kTile];
+                }
+                for (; bl < blocks_per_head; ++bl) v0 += pp[bl * kTile];
+                vote_h[(int64_t)qh * P + t0 + t] = (v0 + v1) + (v2 + v3);
             }
         }
     }
