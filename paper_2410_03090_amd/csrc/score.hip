@@ -106,7 +106,7 @@ constexpr int kTile = 64;                 // tokens per LDS tile
 constexpr int kRowBytes = 2 * kD + 16;    // padded LDS row
 constexpr int kTileBytes = kTile * kRowBytes;
 
-struct KTileRegs { uint4 v[4]; };
+struct KTileRegs { uint4 a, b, c, d; };   // one thread's share of a key tile on its way to LDS
 
 // Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for every
 // outstanding global load, which would cut the key-tile prefetch short at each tile.
@@ -116,26 +116,26 @@ __device__ __forceinline__ void lds_barrier() {
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
-// 64 tokens x 256 B = 1024 16-byte pieces, four per thread; tokens >= t_end read as zero
+// 64 tokens x 256 B = 1024 16-byte pieces, four per thread.  Token indices are clamped to
+// t_end - 1 rather than predicated: straight-line loads let the compiler keep exact counts of
+// the loads in flight (a predicated load makes it wait for all of them), and whatever a token
+// >= t_end contributes is discarded by the callers.
+__device__ __forceinline__ uint4 ktile_piece(const bf16_bits* Kh, int64_t ks_t, int t0, int t_end, int idx) {
+    const int tok = min(t0 + (idx >> 4), t_end - 1);
+    return *reinterpret_cast<const uint4*>(Kh + (int64_t)tok * ks_t + (idx & 15) * 8);
+}
 __device__ __forceinline__ void ktile_load(KTileRegs& r, const bf16_bits* Kh, int64_t ks_t, int t0, int t_end,
                                            int tid) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int idx = tid + 256 * i;
-        const int tok = t0 + (idx >> 4);
-        if (tok < t_end) {
-            r.v[i] = *reinterpret_cast<const uint4*>(Kh + (int64_t)tok * ks_t + (idx & 15) * 8);
-        } else {
-            r.v[i] = make_uint4(0u, 0u, 0u, 0u);
-        }
-    }
+    r.a = ktile_piece(Kh, ks_t, t0, t_end, tid);
+    r.b = ktile_piece(Kh, ks_t, t0, t_end, tid + 256);
+    r.c = ktile_piece(Kh, ks_t, t0, t_end, tid + 512);
+    r.d = ktile_piece(Kh, ks_t, t0, t_end, tid + 768);
 }
 __device__ __forceinline__ void ktile_store(const KTileRegs& r, unsigned char* lds, int tid) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int idx = tid + 256 * i;
-        *reinterpret_cast<uint4*>(lds + (idx >> 4) * kRowBytes + (idx & 15) * 16) = r.v[i];
-    }
+    *reinterpret_cast<uint4*>(lds + (tid >> 4) * kRowBytes + (tid & 15) * 16) = r.a;
+    *reinterpret_cast<uint4*>(lds + ((tid >> 4) + 16) * kRowBytes + (tid & 15) * 16) = r.b;
+    *reinterpret_cast<uint4*>(lds + ((tid >> 4) + 32) * kRowBytes + (tid & 15) * 16) = r.c;
+    *reinterpret_cast<uint4*>(lds + ((tid >> 4) + 48) * kRowBytes + (tid & 15) * 16) = r.d;
 }
 
 // query rows of this wave as A operands: qa[rb][ks] = row 16*rb + lane%16, features 32ks + 8*(lane/16) ..
@@ -171,6 +171,23 @@ __device__ __forceinline__ void tile_logits(f32x4_t acc[4][RB], const bf16x8_t q
             for (int rb = 0; rb < RB; ++rb)
                 acc[st][rb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qa[rb][ks], b, acc[st][rb], 0, 0, 0);
         }
+    }
+}
+
+// one 16-token sub-tile: acc[rb] = rows 16*rb.. x tokens 16*st..
+template <int RB>
+__device__ __forceinline__ void subtile_logits(f32x4_t acc[RB], const bf16x8_t qa[RB][4],
+                                               const unsigned char* lds, int st, int lane) {
+    const int m = lane & 15, g = lane >> 4;
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) acc[rb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+        uint4 raw = *reinterpret_cast<const uint4*>(lds + (16 * st + m) * kRowBytes + 64 * ks + 16 * g);
+        bf16x8_t b = __builtin_bit_cast(bf16x8_t, raw);
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb)
+            acc[rb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qa[rb][ks], b, acc[rb], 0, 0, 0);
     }
 }
 
@@ -228,27 +245,33 @@ __global__ __launch_bounds__(256, 2) void score_stats_mfma_kernel(
     lds_barrier();
     for (int it = 0; it < n_tiles; ++it) {
         const int t0 = t_begin + it * kTile;
-        if (it + 2 < n_tiles) ktile_load(n2, Kh, ks_t, t0 + 2 * kTile, t_end, tid);
-        f32x4_t acc[4][RB];
-        tile_logits<RB>(acc, qa, lds[it & 1], lane);
+        ktile_load(n2, Kh, ks_t, t0 + 2 * kTile, t_end, tid);      // past the chunk: clamped, unused
+        const unsigned char* tile = lds[it & 1];
         const bool edge = t0 + kTile > P || t0 + kTile > t_end;   // causal window or ragged end inside
-        // Fast path: exponentials against the current reference; a row whose tile sum leaves
-        // [0, 2^10] (a logit far above the reference, or no reference yet) sends the wave to
-        // the slow path, which picks new references from the tile's maxima and redoes the tile.
+        // Fast path: exponentials against the current reference, one 16-token sub-tile at a
+        // time so that the MFMAs of the next sub-tile run under them.  A row whose tile sum
+        // leaves [0, 2^10] (a logit far above the reference, or no reference yet) sends the
+        // wave to the slow path, which picks new references from the tile's maxima.
         bool redo = edge;
         float ts[RB][4];
         if (!edge) {
+            f32x4_t acc[2][RB];
+            subtile_logits<RB>(acc[0], qa, tile, 0, lane);
+#pragma unroll
+            for (int st = 0; st < 4; ++st) {
+                if (st < 3) subtile_logits<RB>(acc[(st + 1) & 1], qa, tile, st + 1, lane);
+#pragma unroll
+                for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        const float e = __builtin_amdgcn_exp2f(fmaf(acc[st & 1][rb][v], scale2, nref[rb][v]));
+                        ts[rb][v] = st == 0 ? e : ts[rb][v] + e;
+                    }
+            }
 #pragma unroll
             for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    float t = 0.f;
-#pragma unroll
-                    for (int st = 0; st < 4; ++st)
-                        t += __builtin_amdgcn_exp2f(fmaf(acc[st][rb][v], scale2, nref[rb][v]));
-                    ts[rb][v] = t;
-                    redo |= !(t <= 1024.f);
-                }
+                for (int v = 0; v < 4; ++v) redo |= !(ts[rb][v] <= 1024.f);
         }
         if (__builtin_amdgcn_ballot_w64(redo) == 0ull) {
 #pragma unroll
@@ -256,29 +279,50 @@ __global__ __launch_bounds__(256, 2) void score_stats_mfma_kernel(
 #pragma unroll
                 for (int v = 0; v < 4; ++v) sum[rb][v] += ts[rb][v];
         } else {
+            // slow path (first tile of a chunk, tiles touching the causal window or the ragged
+            // end, rare large logits): logits are recomputed sub-tile by sub-tile, once for the
+            // row maxima and once for the sums, to stay within the fast path's registers
+            float mx[RB][4];
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) mx[rb][v] = -INFINITY;
+            for (int st = 0; st < 4; ++st) {
+                f32x4_t a1[RB];
+                subtile_logits<RB>(a1, qa, tile, st, lane);
+                const int j = t0 + 16 * st + m;
+#pragma unroll
+                for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        const int row = row0 + 16 * rb + 4 * g + v;
+                        const bool seen = row < R && j < t_end && j <= P + row % w;   // causal: row i sees j <= P+i
+                        if (seen) mx[rb][v] = fmaxf(mx[rb][v], a1[rb][v] * scale2);
+                    }
+            }
 #pragma unroll
             for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {
-                    const int row = row0 + 16 * rb + 4 * g + v;
-                    const int last = row < R ? P + row % w : -1;     // last token this row may see
-                    float sv[4], mx = -INFINITY;
-#pragma unroll
-                    for (int st = 0; st < 4; ++st) {
-                        const int j = t0 + 16 * st + m;
-                        sv[st] = (j < t_end && j <= last) ? acc[st][rb][v] * scale2 : -INFINITY;
-                        mx = fmaxf(mx, sv[st]);
+                    const float r = -nref[rb][v];              // -inf before the first token
+                    if (mx[rb][v] > r) {
+                        sum[rb][v] *= exp2f(r - mx[rb][v]);    // exp2(-inf) = 0 on first use
+                        nref[rb][v] = -mx[rb][v];
                     }
-                    float r = -nref[rb][v];                            // current reference (-inf before the first token)
-                    if (mx > r) {
-                        sum[rb][v] *= exp2f(r - mx);                   // exp2(-inf) = 0 on first use
-                        r = mx;
-                        nref[rb][v] = -mx;
-                    }
-#pragma unroll
-                    for (int st = 0; st < 4; ++st)
-                        if (sv[st] != -INFINITY) sum[rb][v] += exp2f(sv[st] - r);
                 }
+            for (int st = 0; st < 4; ++st) {
+                f32x4_t a1[RB];
+                subtile_logits<RB>(a1, qa, tile, st, lane);
+                const int j = t0 + 16 * st + m;
+#pragma unroll
+                for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        const int row = row0 + 16 * rb + 4 * g + v;
+                        const bool seen = row < R && j < t_end && j <= P + row % w;
+                        if (seen) sum[rb][v] += exp2f(fmaf(a1[rb][v], scale2, nref[rb][v]));
+                    }
+            }
         }
         if (it + 1 < n_tiles) ktile_store(n1, lds[(it + 1) & 1], tid);
         lds_barrier();
@@ -344,7 +388,7 @@ __global__ __launch_bounds__(256) void score_vote_mfma_kernel(
     lds_barrier();
     for (int it = 0; it < n_tiles; ++it) {
         const int t0 = t_begin + it * kTile;
-        if (it + 2 < n_tiles) ktile_load(n2, Kh, ks_t, t0 + 2 * kTile, t_end, tid);
+        ktile_load(n2, Kh, ks_t, t0 + 2 * kTile, t_end, tid);      // past the chunk: clamped, unused
         f32x4_t acc[4][RB];
         tile_logits<RB>(acc, qa, lds[it & 1], lane);
 #pragma unroll
@@ -382,6 +426,113 @@ __global__ __launch_bounds__(256) void score_vote_mfma_kernel(
                 vote_h[(int64_t)qh * P + t0 + t] = (v0 + v1) + (v2 + v3);
             }
         }
+    }
+}
+
+// pass 2, barrier-free variant.  The query rows of the KV head (A operands) and their
+// normalisers sit in LDS for the whole kernel; every wave streams its own 64-token key tiles
+// straight from global memory in B-operand layout (lane = token lane%16 of a sub-tile,
+// features 32ks + 8*(lane/16)..), double-buffered in registers, and walks all 16-row blocks of
+// the head.  Votes of a query head accumulate in-lane over its row blocks, are summed over the
+// four lane groups with three register swaps and stored directly: no barrier, no LDS traffic
+// for keys or partial sums inside the loop.
+template <int NRB>     // LDS is sized for 16*NRB query rows
+__global__ __launch_bounds__(256) void score_vote_wave_kernel(
+    const bf16_bits* __restrict__ Q, const bf16_bits* __restrict__ K, const float* __restrict__ lse, int H,
+    int G, int N, int w, int64_t ks_b, int64_t ks_h, int64_t ks_t, int n_chunks, int chunk,
+    float* __restrict__ vote) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    unsigned char* qs = smem;                                             // [16*NRB][kRowBytes]
+    float* nls = reinterpret_cast<float*>(smem + 16 * NRB * kRowBytes);   // [16*NRB] minus lse (base 2)
+    const int bh = blockIdx.x / n_chunks, c = blockIdx.x % n_chunks;
+    const int b = bh / H, h = bh % H;
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int m = lane & 15, g = lane >> 4;
+    const int R = G * w, P = N - w;
+    const int n_rb = R >> 4, bph = w >> 4;          // 16-row blocks per KV head / per query head
+    const bf16_bits* Kh = K + b * ks_b + h * ks_h;
+    const float scale2 = kLog2e * rsqrtf((float)kD);
+    const int t_begin = c * chunk, t_end = min(P, t_begin + chunk);
+    if (t_begin >= t_end) return;
+    const int n_tiles = (t_end - t_begin + kTile - 1) / kTile;
+
+    const bf16_bits* Qh = Q + (int64_t)bh * R * kD;
+    for (int idx = tid; idx < 16 * NRB * 16; idx += 256) {
+        const int row = idx >> 4, piece = idx & 15;
+        uint4 v = make_uint4(0u, 0u, 0u, 0u);
+        if (row < R) v = *reinterpret_cast<const uint4*>(Qh + (int64_t)row * kD + piece * 8);
+        *reinterpret_cast<uint4*>(qs + row * kRowBytes + piece * 16) = v;
+    }
+    for (int r = tid; r < 16 * NRB; r += 256) nls[r] = r < R ? -lse[(int64_t)bh * R + r] : 0.f;
+    __syncthreads();
+
+    float* vote_h = vote + (int64_t)bh * G * P;
+    uint4 ka[4][4], kb[4][4];                        // [sub-tile][k-step] B operands of two tiles
+    auto load_tile = [&](uint4 dst[4][4], int tile) {            // clamped, never predicated (see ktile_load)
+        const int t0 = t_begin + tile * kTile;
+#pragma unroll
+        for (int st = 0; st < 4; ++st) {
+            const int tok = min(t0 + 16 * st + m, t_end - 1);
+            const bf16_bits* src = Kh + (int64_t)tok * ks_t + 8 * g;
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) dst[st][ks] = *reinterpret_cast<const uint4*>(src + 32 * ks);
+        }
+    };
+    struct RowBlock { bf16x8_t a[4]; float4 nl; };     // A operands and normalisers of one 16-row block
+    auto read_block = [&](RowBlock& rbk, int rb) {
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks)
+            rbk.a[ks] = __builtin_bit_cast(
+                bf16x8_t, *reinterpret_cast<const uint4*>(qs + (16 * rb + m) * kRowBytes + 64 * ks + 16 * g));
+        rbk.nl = *reinterpret_cast<const float4*>(nls + 16 * rb + 4 * g);
+    };
+    auto process = [&](const uint4 cur[4][4], uint4 nxt[4][4], int tile) {
+        load_tile(nxt, tile + 4);
+        const int t0 = t_begin + tile * kTile;
+        float pq[4] = {0.f, 0.f, 0.f, 0.f};          // per sub-tile: this lane's rows of the current query head
+        int in_head = 0, qh = 0;
+        auto step = [&](const RowBlock& rbk) {
+            f32x4_t acc[4];
+#pragma unroll
+            for (int st = 0; st < 4; ++st) acc[st] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+                for (int st = 0; st < 4; ++st)
+                    acc[st] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                        rbk.a[ks], __builtin_bit_cast(bf16x8_t, cur[st][ks]), acc[st], 0, 0, 0);
+#pragma unroll
+            for (int st = 0; st < 4; ++st)
+                pq[st] += (__builtin_amdgcn_exp2f(fmaf(acc[st][0], scale2, rbk.nl.x)) +
+                           __builtin_amdgcn_exp2f(fmaf(acc[st][1], scale2, rbk.nl.y))) +
+                          (__builtin_amdgcn_exp2f(fmaf(acc[st][2], scale2, rbk.nl.z)) +
+                           __builtin_amdgcn_exp2f(fmaf(acc[st][3], scale2, rbk.nl.w)));
+            if (++in_head == bph) {
+                // lane group g now receives the total of sub-tile {0,2,1,3}[g]
+                const float tot = reduce4_over_rows(pq[0], pq[1], pq[2], pq[3]);
+                const int j = t0 + 16 * (((g & 1) << 1) | (g >> 1)) + m;
+                if (j < t_end) vote_h[(int64_t)qh * P + j] = tot;
+                pq[0] = pq[1] = pq[2] = pq[3] = 0.f;
+                in_head = 0;
+                ++qh;
+            }
+        };
+        // the LDS reads of a row block are issued one block ahead of its MFMAs
+        RowBlock b0, b1;
+        read_block(b0, 0);
+        int rb = 0;
+        for (; rb + 1 < n_rb; rb += 2) {
+            read_block(b1, rb + 1);
+            step(b0);
+            read_block(b0, min(rb + 2, n_rb - 1));
+            step(b1);
+        }
+        if (rb < n_rb) step(b0);
+    };
+    load_tile(ka, wv);
+    for (int tile = wv; tile < n_tiles; tile += 8) {
+        process(ka, kb, tile);
+        if (tile + 4 < n_tiles) process(kb, ka, tile + 4);
     }
 }
 
@@ -558,13 +709,22 @@ static hipError_t run_score(const T* Q, const T* K, int B, int H, int G, int N, 
     const int n_pool_tiles = (P + kPoolTile - 1) / kPoolTile;
     if constexpr (sizeof(T) == 2) {
         if (mfma) {
-            env.begin("score_vote_mfma");
-            if (p.R <= 128)
-                score_vote_mfma_kernel<2><<<grid1, dim3(256), 0, s>>>(Q, K, lse, H, G, N, w, ks[0], ks[1], ks[2],
-                                                                       p.n_chunks, p.chunk, vote);
-            else
-                score_vote_mfma_kernel<4><<<grid1, dim3(256), 0, s>>>(Q, K, lse, H, G, N, w, ks[0], ks[1], ks[2],
-                                                                       p.n_chunks, p.chunk, vote);
+            env.begin("score_vote_wave");
+            if (p.R <= 128) {
+                constexpr int lds_bytes = 16 * 8 * kRowBytes + 16 * 8 * 4;
+                hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(score_vote_wave_kernel<8>),
+                                                   hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+                if (e != hipSuccess) return e;
+                score_vote_wave_kernel<8><<<grid1, dim3(256), lds_bytes, s>>>(Q, K, lse, H, G, N, w, ks[0], ks[1], ks[2],
+                                                                              p.n_chunks, p.chunk, vote);
+            } else {
+                constexpr int lds_bytes = 16 * 16 * kRowBytes + 16 * 16 * 4;
+                hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(score_vote_wave_kernel<16>),
+                                                   hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+                if (e != hipSuccess) return e;
+                score_vote_wave_kernel<16><<<grid1, dim3(256), lds_bytes, s>>>(Q, K, lse, H, G, N, w, ks[0], ks[1], ks[2],
+                                                                               p.n_chunks, p.chunk, vote);
+            }
             env.end();
         }
     }
