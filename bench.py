@@ -18,6 +18,20 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
 
+# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, scaled by what the same
+# counters read for a plain 1 GiB device copy (profiles/hbm_traffic_<workload>.txt has the raw
+# figures and the commands).  Keyed by workload, then kernel.
+MEASURED_TRAFFIC_BYTES = {
+    "llama3-8b-128k": {
+        "gram_mfma": int((8.000 + 0.126) * 2**30),
+        "score_stats_mfma": int((8.131 + 0.010) * 2**30),
+        "score_vote_wave": int((8.123 + 0.500) * 2**30),
+        "score_pool": int((0.625 + 0.125) * 2**30),
+        "select": int((0.500 + 0.002) * 2**30),
+        "gather": int((0.256 + 0.250) * 2**30),
+    },
+}
+
 
 def algorithmic_work(cfg, name):
     """(bytes, flops) one launch of kernel `name` must move / compute, over all L*B*H heads.
@@ -45,7 +59,7 @@ def algorithmic_work(cfg, name):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=3, help="index into BASELINE.json configs (default: the 128K prefill)")
     ap.add_argument("--seed", type=int, default=2410)
@@ -132,7 +146,11 @@ def main():
         if byt:
             ach = byt / avg_ms / 1e6
             roofline = {"kernel": dominant, "bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBS,
-                        "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": None}
+                        "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBS, 4),
+                        "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name, {}).get(dominant),
+                        "algorithmic_bytes": int(byt),
+                        "mfma_TFLOPs": round(flops / avg_ms / 1e9, 1) if flops else None,
+                        "mfma_frac": round(flops / avg_ms / 1e9 / MFMA_BF16_PEAK_TFLOPS, 4) if flops else None}
         else:
             roofline = {"kernel": dominant, "bound": "alu", "achieved": None, "peak": None, "unit": "TFLOP/s",
                         "frac": None, "traffic": None}

@@ -154,26 +154,6 @@ __device__ __forceinline__ void load_q(bf16x8_t qa[RB][4], const bf16_bits* Qh, 
     }
 }
 
-// S tile of this wave: acc[st][rb] = rows 16*rb.. x tokens 16*st.. of the LDS tile
-template <int RB>
-__device__ __forceinline__ void tile_logits(f32x4_t acc[4][RB], const bf16x8_t qa[RB][4],
-                                            const unsigned char* lds, int lane) {
-    const int m = lane & 15, g = lane >> 4;
-#pragma unroll
-    for (int st = 0; st < 4; ++st) {
-#pragma unroll
-        for (int rb = 0; rb < RB; ++rb) acc[st][rb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            uint4 raw = *reinterpret_cast<const uint4*>(lds + (16 * st + m) * kRowBytes + 64 * ks + 16 * g);
-            bf16x8_t b = __builtin_bit_cast(bf16x8_t, raw);
-#pragma unroll
-            for (int rb = 0; rb < RB; ++rb)
-                acc[st][rb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qa[rb][ks], b, acc[st][rb], 0, 0, 0);
-        }
-    }
-}
-
 // one 16-token sub-tile: acc[rb] = rows 16*rb.. x tokens 16*st..
 template <int RB>
 __device__ __forceinline__ void subtile_logits(f32x4_t acc[RB], const bf16x8_t qa[RB][4],
@@ -349,87 +329,8 @@ __global__ __launch_bounds__(256, 2) void score_stats_mfma_kernel(
         }
 }
 
-// pass 2: vote[g][j] = sum over the w rows of query head g of exp2(logit - lse)
-template <int RB>
-__global__ __launch_bounds__(256) void score_vote_mfma_kernel(
-    const bf16_bits* __restrict__ Q, const bf16_bits* __restrict__ K, const float* __restrict__ lse, int H,
-    int G, int N, int w, int64_t ks_b, int64_t ks_h, int64_t ks_t, int n_chunks, int chunk,
-    float* __restrict__ vote) {
-    __shared__ __align__(16) unsigned char lds[2][kTileBytes];
-    __shared__ float part[2][4 * RB][kTile];      // per 16-row block, per token of the tile
-    const int bh = blockIdx.x / n_chunks, c = blockIdx.x % n_chunks;
-    const int b = bh / H, h = bh % H;
-    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-    const int m = lane & 15, g = lane >> 4;
-    const int R = G * w, P = N - w;
-    const bf16_bits* Kh = K + b * ks_b + h * ks_h;
-    const int row0 = wv * 16 * RB;
-    const float scale2 = kLog2e * rsqrtf((float)kD);
-    const int blocks_per_head = w >> 4;             // 16-row blocks per query head
-
-    bf16x8_t qa[RB][4];
-    load_q<RB>(qa, Q + (int64_t)bh * R * kD, row0, R, lane);
-    float nl[RB][4];                                // minus log-sum-exp (base 2) of this lane's rows
-#pragma unroll
-    for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-        for (int v = 0; v < 4; ++v) {
-            const int row = row0 + 16 * rb + 4 * g + v;
-            nl[rb][v] = row < R ? -lse[(int64_t)bh * R + row] : 0.f;
-        }
-
-    const int t_begin = c * chunk, t_end = min(P, t_begin + chunk);
-    const int n_tiles = (t_end - t_begin + kTile - 1) / kTile;
-    float* vote_h = vote + (int64_t)bh * G * P;
-    KTileRegs n1, n2;
-    ktile_load(n1, Kh, ks_t, t_begin, t_end, tid);
-    ktile_store(n1, lds[0], tid);
-    ktile_load(n1, Kh, ks_t, t_begin + kTile, t_end, tid);
-    lds_barrier();
-    for (int it = 0; it < n_tiles; ++it) {
-        const int t0 = t_begin + it * kTile;
-        ktile_load(n2, Kh, ks_t, t0 + 2 * kTile, t_end, tid);      // past the chunk: clamped, unused
-        f32x4_t acc[4][RB];
-        tile_logits<RB>(acc, qa, lds[it & 1], lane);
-#pragma unroll
-        for (int rb = 0; rb < RB; ++rb) {
-            float p[4];
-#pragma unroll
-            for (int st = 0; st < 4; ++st) {
-                p[st] = 0.f;
-#pragma unroll
-                for (int v = 0; v < 4; ++v) p[st] += __builtin_amdgcn_exp2f(fmaf(acc[st][rb][v], scale2, nl[rb][v]));
-            }
-            // sum over the four lane groups (rows 4g..4g+3 of the block) with three register
-            // swaps; lane group g then holds the block total of sub-tile {0,2,1,3}[g]
-            const float tot = reduce4_over_rows(p[0], p[1], p[2], p[3]);
-            const int st_mine = ((g & 1) << 1) | (g >> 1);
-            part[it & 1][wv * RB + rb][16 * st_mine + m] = tot;
-        }
-        if (it + 1 < n_tiles) ktile_store(n1, lds[(it + 1) & 1], tid);
-        lds_barrier();
-        n1 = n2;
-        // sum the blocks of each query head and store (part[it&1] is rewritten two tiles later)
-        for (int o = tid; o < G * kTile; o += 256) {
-            const int qh = o / kTile, t = o % kTile;
-            if (t0 + t < t_end) {
-                const float* pp = &part[it & 1][qh * blocks_per_head][t];
-                float v0 = 0.f, v1 = 0.f, v2 = 0.f, v3 = 0.f;
-                int bl = 0;
-                for (; bl + 4 <= blocks_per_head; bl += 4) {     // four independent LDS reads at a time
-                    v0 += pp[(bl + 0) * kTile];
-                    v1 += pp[(bl + 1) * kTile];
-                    v2 += pp[(bl + 2) * kTile];
-                    v3 += pp[(bl + 3) * kTile];
-                }
-                for (; bl < blocks_per_head; ++bl) v0 += pp[bl * kTile];
-                vote_h[(int64_t)qh * P + t0 + t] = (v0 + v1) + (v2 + v3);
-            }
-        }
-    }
-}
-
-// pass 2, barrier-free variant.  The query rows of the KV head (A operands) and their
+// pass 2: vote[g][j] = sum over the w rows of query head g of exp2(logit - lse), without
+// barriers.  The query rows of the KV head (A operands) and their
 // normalisers sit in LDS for the whole kernel; every wave streams its own 64-token key tiles
 // straight from global memory in B-operand layout (lane = token lane%16 of a sub-tile,
 // features 32ks + 8*(lane/16)..), double-buffered in registers, and walks all 16-row blocks of
