@@ -34,6 +34,8 @@ struct Smem {
     double red[8];
     float lam[kD];
     float sorted[kD];
+    float dsc[kD];           // column j of the matrix is dsc[j] * A[j]
+    float n2[kD];            // running squared norms of the columns
     float flag[4];
 };
 
@@ -104,29 +106,51 @@ __global__ __launch_bounds__(kThreads) void jacobi_entropy_kernel(
     __syncthreads();
 
     // ---- 2. one-sided Jacobi ---------------------------------------------------------------
+    // Rotations are applied in scaled form: column j is kept as dsc[j] * A[j], so that
+    //   a_p' = c (a_p - t a_q),  a_q' = c (a_q + t a_p)
+    // costs one multiply-add per element (A_p -= (t dsc_q/dsc_p) A_q, A_q += (t dsc_p/dsc_q) A_p)
+    // and the common factor c goes into dsc.  Squared column norms are carried along
+    // (|a_p'|^2 = |a_p|^2 - t gamma, |a_q'|^2 = |a_q|^2 + t gamma), leaving one dot product per
+    // pair.  Scales are folded back into the columns at every workgroup barrier and the norms
+    // are recomputed from the columns at the start of every sweep.
     const int wv = tid >> 6;
     const int slot = (tid >> 2) & 15;   // which of the wave's 16 pairs
     const int sub = tid & 3;            // which quarter of the rows (interleaved float4 groups)
     float max_cos2 = 0.f;
+    if (tid < kD) sm.dsc[tid] = 1.f;
+    auto fold_scales = [&](bool with_norms) {       // between two barriers
+        if (tid < kD) {
+            float4* col = reinterpret_cast<float4*>(sm.A + tid * kLd);
+            const float d = sm.dsc[tid];
+            float acc0 = 0.f, acc1 = 0.f;
+#pragma unroll 8
+            for (int i = 0; i < kD / 4; ++i) {
+                float4 v = col[i];
+                v.x *= d; v.y *= d; v.z *= d; v.w *= d;
+                col[i] = v;
+                acc0 += v.x * v.x + v.y * v.y;
+                acc1 += v.z * v.z + v.w * v.w;
+            }
+            sm.dsc[tid] = 1.f;
+            if (with_norms) sm.n2[tid] = acc0 + acc1;
+        }
+    };
     auto rotate_pair = [&](int p, int q) {
         float4* cp = reinterpret_cast<float4*>(sm.A + p * kLd);
         float4* cq = reinterpret_cast<float4*>(sm.A + q * kLd);
         float4 ap[8], aq[8];
-        float al[2] = {0.f, 0.f}, be[2] = {0.f, 0.f}, ga[2] = {0.f, 0.f};
+        float ga[2] = {0.f, 0.f};
 #pragma unroll
         for (int v = 0; v < 8; ++v) {
             ap[v] = cp[4 * v + sub];
             aq[v] = cq[4 * v + sub];
         }
+        const float dp = sm.dsc[p], dq = sm.dsc[q];
+        const float alpha = sm.n2[p], beta = sm.n2[q];
 #pragma unroll
-        for (int v = 0; v < 8; ++v) {
-            al[v & 1] += ap[v].x * ap[v].x + ap[v].y * ap[v].y + ap[v].z * ap[v].z + ap[v].w * ap[v].w;
-            be[v & 1] += aq[v].x * aq[v].x + aq[v].y * aq[v].y + aq[v].z * aq[v].z + aq[v].w * aq[v].w;
+        for (int v = 0; v < 8; ++v)
             ga[v & 1] += ap[v].x * aq[v].x + ap[v].y * aq[v].y + ap[v].z * aq[v].z + ap[v].w * aq[v].w;
-        }
-        const float alpha = quad_sum(al[0] + al[1]);
-        const float beta = quad_sum(be[0] + be[1]);
-        const float gamma = quad_sum(ga[0] + ga[1]);
+        const float gamma = quad_sum(ga[0] + ga[1]) * (dp * dq);
         const float ab = alpha * beta;
         const float g2 = gamma * gamma;
         if (ab > 0.f && g2 > 1e-14f * ab) {            // same decision in all four lanes
@@ -136,16 +160,24 @@ __global__ __launch_bounds__(kThreads) void jacobi_entropy_kernel(
             const float t = copysignf(1.f, zeta) *
                             __builtin_amdgcn_rcpf(fabsf(zeta) + __builtin_amdgcn_sqrtf(fmaf(zeta, zeta, 1.f)));
             const float c = __builtin_amdgcn_rsqf(fmaf(t, t, 1.f));
-            const float sn = c * t;
+            const float ratio = dq * __builtin_amdgcn_rcpf(dp);
+            const float tp = -t * ratio, tq = t * __builtin_amdgcn_rcpf(ratio);
 #pragma unroll
             for (int v = 0; v < 8; ++v) {
                 float4 np, nq;
-                np.x = c * ap[v].x - sn * aq[v].x;  nq.x = sn * ap[v].x + c * aq[v].x;
-                np.y = c * ap[v].y - sn * aq[v].y;  nq.y = sn * ap[v].y + c * aq[v].y;
-                np.z = c * ap[v].z - sn * aq[v].z;  nq.z = sn * ap[v].z + c * aq[v].z;
-                np.w = c * ap[v].w - sn * aq[v].w;  nq.w = sn * ap[v].w + c * aq[v].w;
+                np.x = fmaf(tp, aq[v].x, ap[v].x);  nq.x = fmaf(tq, ap[v].x, aq[v].x);
+                np.y = fmaf(tp, aq[v].y, ap[v].y);  nq.y = fmaf(tq, ap[v].y, aq[v].y);
+                np.z = fmaf(tp, aq[v].z, ap[v].z);  nq.z = fmaf(tq, ap[v].z, aq[v].z);
+                np.w = fmaf(tp, aq[v].w, ap[v].w);  nq.w = fmaf(tq, ap[v].w, aq[v].w);
                 cp[4 * v + sub] = np;
                 cq[4 * v + sub] = nq;
+            }
+            if (sub == 0) {
+                const float tg = t * gamma;
+                sm.dsc[p] = dp * c;
+                sm.dsc[q] = dq * c;
+                sm.n2[p] = fmaxf(alpha - tg, 0.f);
+                sm.n2[q] = beta + tg;
             }
         }
         // the wave's own LDS traffic is ordered; keep the compiler from moving it
@@ -156,6 +188,9 @@ __global__ __launch_bounds__(kThreads) void jacobi_entropy_kernel(
 
     for (int sweep = 0; sweep < kMaxSweeps; ++sweep) {
         max_cos2 = 0.f;
+        __syncthreads();
+        fold_scales(true);
+        __syncthreads();
         // pairs inside half-blocks 2wv and 2wv+1: round-robin over 16 columns, 8 pairs each
         {
             const int hb = 2 * wv + (slot >> 3), k = slot & 7;
@@ -173,9 +208,11 @@ __global__ __launch_bounds__(kThreads) void jacobi_entropy_kernel(
                 rotate_pair(16 * hb + i, 16 * hb + j);
             }
         }
-        __syncthreads();
         // cross pairs: round-robin over the 8 half-blocks, one pair of half-blocks per wave
         for (int br = 0; br < 7; ++br) {
+            __syncthreads();
+            fold_scales(false);
+            __syncthreads();
             int X, Y;
             if (wv == 0) {
                 X = 7;
@@ -187,7 +224,6 @@ __global__ __launch_bounds__(kThreads) void jacobi_entropy_kernel(
                 if (Y < 0) Y += 7;
             }
             for (int t = 0; t < 16; ++t) rotate_pair(16 * X + slot, 16 * Y + ((slot + t) & 15));
-            __syncthreads();
         }
         // every thread learns the sweep's largest cos^2
         max_cos2 = wave_max(max_cos2);
@@ -197,6 +233,8 @@ __global__ __launch_bounds__(kThreads) void jacobi_entropy_kernel(
         __syncthreads();
         if (mc < kStopCos2) break;
     }
+    fold_scales(false);
+    __syncthreads();
 
     // ---- 3. eigenvalues, ordering, entropy -----------------------------------------------
     if (tid < kD) {
