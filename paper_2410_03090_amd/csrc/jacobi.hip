@@ -55,6 +55,21 @@ __device__ __forceinline__ float quad_sum(float v) {
     return v;
 }
 
+// Sum of v over the four lanes {k, k+16, k+32, k+48}, delivered to all four with identical bits.
+// v_permlane32_swap(a,b) -> ([a.lo32, b.lo32], [a.hi32, b.hi32]);
+// v_permlane16_swap(a,b) -> ([a.r0, b.r0, a.r2, b.r2], [a.r1, b.r1, a.r3, b.r3])  (r = row of 16 lanes).
+__device__ __forceinline__ float rows_allreduce(float v) {
+    auto s1 = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    const float h = __uint_as_float(s1[0]) + __uint_as_float(s1[1]);      // rows 0,2: v0+v2; rows 1,3: v1+v3
+    auto s2 = __builtin_amdgcn_permlane16_swap(__float_as_uint(h), __float_as_uint(h), false, false);
+    return __uint_as_float(s2[0]) + __uint_as_float(s2[1]);
+}
+
+// Rotates a register by one lane inside each row of 16 lanes (DPP row_ror:1).
+__device__ __forceinline__ float row_rotate(float v) {
+    return __uint_as_float(__builtin_amdgcn_update_dpp(0u, __float_as_uint(v), 0x121, 0xF, 0xF, false));
+}
+
 }  // namespace
 
 __global__ __launch_bounds__(kThreads) void jacobi_entropy_kernel(
@@ -208,10 +223,15 @@ __global__ __launch_bounds__(kThreads) void jacobi_entropy_kernel(
                 rotate_pair(16 * hb + i, 16 * hb + j);
             }
         }
-        // cross pairs: round-robin over the 8 half-blocks, one pair of half-blocks per wave
+        // cross pairs: round-robin over the 8 half-blocks, one pair of half-blocks (X, Y) per
+        // wave.  The 32 columns stay in registers for the 16 rounds of the block: lane
+        // (k = lane%16, s = lane/16) holds quarter s of column X[k] and of one Y column; after
+        // every round the Y slices (with their scale and norm) move one lane along their row of
+        // 16, so lane k meets every Y column once and after 16 moves each is back where it
+        // started.  No LDS traffic or barrier inside a block.
+        __syncthreads();
+        fold_scales(false);
         for (int br = 0; br < 7; ++br) {
-            __syncthreads();
-            fold_scales(false);
             __syncthreads();
             int X, Y;
             if (wv == 0) {
@@ -223,7 +243,67 @@ __global__ __launch_bounds__(kThreads) void jacobi_entropy_kernel(
                 Y = br - wv;
                 if (Y < 0) Y += 7;
             }
-            for (int t = 0; t < 16; ++t) rotate_pair(16 * X + slot, 16 * Y + ((slot + t) & 15));
+            const int k = tid & 15, s4 = (tid >> 4) & 3;
+            const int px = 16 * X + k, py = 16 * Y + k;
+            float4* cx = reinterpret_cast<float4*>(sm.A + px * kLd);
+            float4* cy = reinterpret_cast<float4*>(sm.A + py * kLd);
+            float4 xa[8], ya[8];
+#pragma unroll
+            for (int v = 0; v < 8; ++v) {
+                xa[v] = cx[4 * v + s4];
+                ya[v] = cy[4 * v + s4];
+            }
+            float nx = sm.n2[px], ny = sm.n2[py], dx = 1.f, dy = 1.f;
+            for (int t = 0; t < 16; ++t) {
+                float ga[2] = {0.f, 0.f};
+#pragma unroll
+                for (int v = 0; v < 8; ++v)
+                    ga[v & 1] += xa[v].x * ya[v].x + xa[v].y * ya[v].y + xa[v].z * ya[v].z + xa[v].w * ya[v].w;
+                const float gamma = rows_allreduce(ga[0] + ga[1]) * (dx * dy);
+                const float ab = nx * ny;
+                const float g2 = gamma * gamma;
+                if (ab > 0.f && g2 > 1e-14f * ab) {        // same decision in the four lanes of a pair
+                    max_cos2 = fmaxf(max_cos2, g2 * __builtin_amdgcn_rcpf(ab));
+                    const float zeta = (ny - nx) * __builtin_amdgcn_rcpf(2.f * gamma);
+                    const float tn = copysignf(1.f, zeta) *
+                                     __builtin_amdgcn_rcpf(fabsf(zeta) + __builtin_amdgcn_sqrtf(fmaf(zeta, zeta, 1.f)));
+                    const float c = __builtin_amdgcn_rsqf(fmaf(tn, tn, 1.f));
+                    const float ratio = dy * __builtin_amdgcn_rcpf(dx);
+                    const float tp = -tn * ratio, tq = tn * __builtin_amdgcn_rcpf(ratio);
+#pragma unroll
+                    for (int v = 0; v < 8; ++v) {
+                        const float4 ox = xa[v], oy = ya[v];
+                        xa[v].x = fmaf(tp, oy.x, ox.x);  ya[v].x = fmaf(tq, ox.x, oy.x);
+                        xa[v].y = fmaf(tp, oy.y, ox.y);  ya[v].y = fmaf(tq, ox.y, oy.y);
+                        xa[v].z = fmaf(tp, oy.z, ox.z);  ya[v].z = fmaf(tq, ox.z, oy.z);
+                        xa[v].w = fmaf(tp, oy.w, ox.w);  ya[v].w = fmaf(tq, ox.w, oy.w);
+                    }
+                    const float tg = tn * gamma;
+                    dx *= c;
+                    dy *= c;
+                    nx = fmaxf(nx - tg, 0.f);
+                    ny += tg;
+                }
+#pragma unroll
+                for (int v = 0; v < 8; ++v) {
+                    ya[v].x = row_rotate(ya[v].x);
+                    ya[v].y = row_rotate(ya[v].y);
+                    ya[v].z = row_rotate(ya[v].z);
+                    ya[v].w = row_rotate(ya[v].w);
+                }
+                dy = row_rotate(dy);
+                ny = row_rotate(ny);
+            }
+            // scales folded in on the way back; every Y slice is home again after 16 moves
+#pragma unroll
+            for (int v = 0; v < 8; ++v) {
+                cx[4 * v + s4] = make_float4(xa[v].x * dx, xa[v].y * dx, xa[v].z * dx, xa[v].w * dx);
+                cy[4 * v + s4] = make_float4(ya[v].x * dy, ya[v].y * dy, ya[v].z * dy, ya[v].w * dy);
+            }
+            if (s4 == 0) {
+                sm.n2[px] = nx;
+                sm.n2[py] = ny;
+            }
         }
         // every thread learns the sweep's largest cos^2
         max_cos2 = wave_max(max_cos2);
