@@ -89,87 +89,23 @@ __global__ __launch_bounds__(512) void score_stats_alu_kernel(
 
 // ---------------------------------------------------------------------------------------
 // bf16 MFMA kernels.  Logits S = Q K^T contract over the 128 features, which are contiguous
-// in memory, so both operands of v_mfma_f32_16x16x32_bf16 load straight from rows: query
-// rows are the A operand (held in registers for the whole kernel), a 64-token key tile is
-// the B operand, staged once per workgroup in LDS (rows padded by 16 bytes so that eight
-// consecutive lanes of a 128-bit read hit distinct banks) and read by all four waves.
-// Wave v owns query rows [16*RB*v, 16*RB*(v+1)) of the KV head (RB = 2 or 4 blocks of 16
-// rows, i.e. up to 128 or 256 rows per head).  An accumulator lane holds one token
-// (lane%16) and four rows (4*(lane/16) + 0..3) of each 16x16 block.
+// in memory, so both operands of v_mfma_f32_16x16x32_bf16 load straight from rows.  Both
+// passes use the same barrier-free streaming scheme: the query rows of the KV head sit in
+// LDS for the whole kernel (rows padded by 16 bytes so that eight consecutive lanes of a
+// 128-bit read hit distinct banks) and are re-read per 64-token tile; every wave streams its
+// own key tiles straight from global memory in operand layout (lane = token lane%16 of a
+// 16-token sub-tile, features 32ks + 8*(lane/16)..), double-buffered in registers.  Key loads
+// are clamped to the last valid token instead of predicated: straight-line loads let the
+// compiler keep exact counts of the loads in flight (a predicated load makes it wait for all
+// of them), and whatever a token past the end contributes is masked or never stored.
 // ---------------------------------------------------------------------------------------
 namespace {
 
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
 
-constexpr int kTile = 64;                 // tokens per LDS tile
-constexpr int kRowBytes = 2 * kD + 16;    // padded LDS row
-constexpr int kTileBytes = kTile * kRowBytes;
-
-struct KTileRegs { uint4 a, b, c, d; };   // one thread's share of a key tile on its way to LDS
-
-// Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for every
-// outstanding global load, which would cut the key-tile prefetch short at each tile.
-__device__ __forceinline__ void lds_barrier() {
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
-    __builtin_amdgcn_s_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
-}
-
-// 64 tokens x 256 B = 1024 16-byte pieces, four per thread.  Token indices are clamped to
-// t_end - 1 rather than predicated: straight-line loads let the compiler keep exact counts of
-// the loads in flight (a predicated load makes it wait for all of them), and whatever a token
-// >= t_end contributes is discarded by the callers.
-__device__ __forceinline__ uint4 ktile_piece(const bf16_bits* Kh, int64_t ks_t, int t0, int t_end, int idx) {
-    const int tok = min(t0 + (idx >> 4), t_end - 1);
-    return *reinterpret_cast<const uint4*>(Kh + (int64_t)tok * ks_t + (idx & 15) * 8);
-}
-__device__ __forceinline__ void ktile_load(KTileRegs& r, const bf16_bits* Kh, int64_t ks_t, int t0, int t_end,
-                                           int tid) {
-    r.a = ktile_piece(Kh, ks_t, t0, t_end, tid);
-    r.b = ktile_piece(Kh, ks_t, t0, t_end, tid + 256);
-    r.c = ktile_piece(Kh, ks_t, t0, t_end, tid + 512);
-    r.d = ktile_piece(Kh, ks_t, t0, t_end, tid + 768);
-}
-__device__ __forceinline__ void ktile_store(const KTileRegs& r, unsigned char* lds, int tid) {
-    *reinterpret_cast<uint4*>(lds + (tid >> 4) * kRowBytes + (tid & 15) * 16) = r.a;
-    *reinterpret_cast<uint4*>(lds + ((tid >> 4) + 16) * kRowBytes + (tid & 15) * 16) = r.b;
-    *reinterpret_cast<uint4*>(lds + ((tid >> 4) + 32) * kRowBytes + (tid & 15) * 16) = r.c;
-    *reinterpret_cast<uint4*>(lds + ((tid >> 4) + 48) * kRowBytes + (tid & 15) * 16) = r.d;
-}
-
-// query rows of this wave as A operands: qa[rb][ks] = row 16*rb + lane%16, features 32ks + 8*(lane/16) ..
-template <int RB>
-__device__ __forceinline__ void load_q(bf16x8_t qa[RB][4], const bf16_bits* Qh, int row0, int R, int lane) {
-    const int m = lane & 15, g = lane >> 4;
-#pragma unroll
-    for (int rb = 0; rb < RB; ++rb) {
-        const int row = row0 + 16 * rb + m;
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            uint4 raw = make_uint4(0u, 0u, 0u, 0u);
-            if (row < R) raw = *reinterpret_cast<const uint4*>(Qh + (int64_t)row * kD + 32 * ks + 8 * g);
-            qa[rb][ks] = __builtin_bit_cast(bf16x8_t, raw);
-        }
-    }
-}
-
-// one 16-token sub-tile: acc[rb] = rows 16*rb.. x tokens 16*st..
-template <int RB>
-__device__ __forceinline__ void subtile_logits(f32x4_t acc[RB], const bf16x8_t qa[RB][4],
-                                               const unsigned char* lds, int st, int lane) {
-    const int m = lane & 15, g = lane >> 4;
-#pragma unroll
-    for (int rb = 0; rb < RB; ++rb) acc[rb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-        uint4 raw = *reinterpret_cast<const uint4*>(lds + (16 * st + m) * kRowBytes + 64 * ks + 16 * g);
-        bf16x8_t b = __builtin_bit_cast(bf16x8_t, raw);
-#pragma unroll
-        for (int rb = 0; rb < RB; ++rb)
-            acc[rb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qa[rb][ks], b, acc[rb], 0, 0, 0);
-    }
-}
+constexpr int kTile = 64;                 // tokens per key tile
+constexpr int kRowBytes = 2 * kD + 16;    // padded LDS row of one query
 
 // Lane layout: four rows of 16 lanes.  For four registers X, Y, Z, W returns, in lane row
 // 0 / 1 / 2 / 3, the sum over all four rows of X / Z / Y / W (per lane%16).
@@ -186,137 +122,144 @@ __device__ __forceinline__ float reduce4_over_rows(float x, float y, float z, fl
 
 }  // namespace
 
-// pass 1: running (reference, sum of exp2) per query row over one token chunk
-template <int RB>
-__global__ __launch_bounds__(256, 2) void score_stats_mfma_kernel(
+// pass 1 without barriers: same streaming scheme as the vote kernel below (queries in LDS, every
+// wave streams its own key tiles), with the MFMA operands swapped so that an accumulator lane
+// holds ONE query row (lane%16 of the block) and 16 tokens of the tile: a row's running
+// (reference, sum of exp2) is then a single pair of registers per block, updated once per tile.
+// Every wave writes its own partial statistics (4 per chunk); the merge kernel combines them.
+template <int NRB>     // 16-row blocks the LDS and the per-lane state are sized for
+__global__ __launch_bounds__(256, 2) void score_stats_wave_kernel(
     const bf16_bits* __restrict__ Q, const bf16_bits* __restrict__ K, int H, int R, int N, int w,
     int64_t ks_b, int64_t ks_h, int64_t ks_t, int n_chunks, int chunk, float2* __restrict__ stats) {
-    __shared__ __align__(16) unsigned char lds[2][kTileBytes];
+    extern __shared__ __align__(16) unsigned char smem[];
+    unsigned char* qs = smem;                                             // [16*NRB][kRowBytes]
     const int bh = blockIdx.x / n_chunks, c = blockIdx.x % n_chunks;
     const int b = bh / H, h = bh % H;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int m = lane & 15, g = lane >> 4;
     const int P = N - w;
+    const int n_rb = R >> 4;
     const bf16_bits* Kh = K + b * ks_b + h * ks_h;
-    const int row0 = wv * 16 * RB;
     const float scale2 = kLog2e * rsqrtf((float)kD);
-
-    bf16x8_t qa[RB][4];
-    load_q<RB>(qa, Q + (int64_t)bh * R * kD, row0, R, lane);
-
-    float nref[RB][4], sum[RB][4];         // minus the running reference, sum of exp2(logit - reference)
-#pragma unroll
-    for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-        for (int v = 0; v < 4; ++v) {
-            nref[rb][v] = INFINITY;
-            sum[rb][v] = 0.f;
-        }
-
     const int t_begin = c * chunk, t_end = min(N, t_begin + chunk);
-    const int n_tiles = (t_end - t_begin + kTile - 1) / kTile;
-    // Key tiles travel global -> registers -> LDS two tiles ahead of their use: while tile
-    // `it` is computed from one LDS buffer, tile it+1 waits in registers to be stored into the
-    // other buffer and the loads of tile it+2 are in flight.
-    KTileRegs n1, n2;
-    ktile_load(n1, Kh, ks_t, t_begin, t_end, tid);
-    ktile_store(n1, lds[0], tid);
-    ktile_load(n1, Kh, ks_t, t_begin + kTile, t_end, tid);
-    lds_barrier();
-    for (int it = 0; it < n_tiles; ++it) {
-        const int t0 = t_begin + it * kTile;
-        ktile_load(n2, Kh, ks_t, t0 + 2 * kTile, t_end, tid);      // past the chunk: clamped, unused
-        const unsigned char* tile = lds[it & 1];
+    const int n_tiles = t_end > t_begin ? (t_end - t_begin + kTile - 1) / kTile : 0;
+
+    const bf16_bits* Qh = Q + (int64_t)bh * R * kD;
+    for (int idx = tid; idx < 16 * NRB * 16; idx += 256) {
+        const int row = idx >> 4, piece = idx & 15;
+        uint4 v = make_uint4(0u, 0u, 0u, 0u);
+        if (row < R) v = *reinterpret_cast<const uint4*>(Qh + (int64_t)row * kD + piece * 8);
+        *reinterpret_cast<uint4*>(qs + row * kRowBytes + piece * 16) = v;
+    }
+    __syncthreads();
+
+    float nref[NRB], sum[NRB];         // of row 16*rb + m: minus the running reference, sum of exp2(logit - reference)
+#pragma unroll
+    for (int rb = 0; rb < NRB; ++rb) {
+        nref[rb] = INFINITY;
+        sum[rb] = 0.f;
+    }
+    uint4 ka[4][4], kb[4][4];          // [sub-tile][k-step] key operands of two tiles
+    auto load_tile = [&](uint4 dst[4][4], int tile) {            // clamped, never predicated (see ktile_load)
+        const int t0 = t_begin + tile * kTile;
+#pragma unroll
+        for (int st = 0; st < 4; ++st) {
+            const int tok = min(t0 + 16 * st + m, t_end - 1);
+            const bf16_bits* src = Kh + (int64_t)tok * ks_t + 8 * g;
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) dst[st][ks] = *reinterpret_cast<const uint4*>(src + 32 * ks);
+        }
+    };
+    auto read_block = [&](bf16x8_t a[4], int rb) {
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks)
+            a[ks] = __builtin_bit_cast(
+                bf16x8_t, *reinterpret_cast<const uint4*>(qs + (16 * rb + m) * kRowBytes + 64 * ks + 16 * g));
+    };
+    auto process = [&](const uint4 cur[4][4], uint4 nxt[4][4], int tile) {
+        load_tile(nxt, tile + 4);
+        const int t0 = t_begin + tile * kTile;
         const bool edge = t0 + kTile > P || t0 + kTile > t_end;   // causal window or ragged end inside
-        // Fast path: exponentials against the current reference, one 16-token sub-tile at a
-        // time so that the MFMAs of the next sub-tile run under them.  A row whose tile sum
-        // leaves [0, 2^10] (a logit far above the reference, or no reference yet) sends the
-        // wave to the slow path, which picks new references from the tile's maxima.
-        bool redo = edge;
-        float ts[RB][4];
-        if (!edge) {
-            f32x4_t acc[2][RB];
-            subtile_logits<RB>(acc[0], qa, tile, 0, lane);
+        // query operands are read one block ahead where registers allow (NRB = 8)
+        constexpr bool kAhead = NRB <= 8;
+        bf16x8_t qa[kAhead ? 2 : 1][4];
+        if (kAhead) read_block(qa[0], 0);
 #pragma unroll
-            for (int st = 0; st < 4; ++st) {
-                if (st < 3) subtile_logits<RB>(acc[(st + 1) & 1], qa, tile, st + 1, lane);
-#pragma unroll
-                for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-                    for (int v = 0; v < 4; ++v) {
-                        const float e = __builtin_amdgcn_exp2f(fmaf(acc[st & 1][rb][v], scale2, nref[rb][v]));
-                        ts[rb][v] = st == 0 ? e : ts[rb][v] + e;
-                    }
-            }
-#pragma unroll
-            for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-                for (int v = 0; v < 4; ++v) redo |= !(ts[rb][v] <= 1024.f);
-        }
-        if (__builtin_amdgcn_ballot_w64(redo) == 0ull) {
-#pragma unroll
-            for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-                for (int v = 0; v < 4; ++v) sum[rb][v] += ts[rb][v];
-        } else {
-            // slow path (first tile of a chunk, tiles touching the causal window or the ragged
-            // end, rare large logits): logits are recomputed sub-tile by sub-tile, once for the
-            // row maxima and once for the sums, to stay within the fast path's registers
-            float mx[RB][4];
-#pragma unroll
-            for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-                for (int v = 0; v < 4; ++v) mx[rb][v] = -INFINITY;
-            for (int st = 0; st < 4; ++st) {
-                f32x4_t a1[RB];
-                subtile_logits<RB>(a1, qa, tile, st, lane);
-                const int j = t0 + 16 * st + m;
-#pragma unroll
-                for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-                    for (int v = 0; v < 4; ++v) {
-                        const int row = row0 + 16 * rb + 4 * g + v;
-                        const bool seen = row < R && j < t_end && j <= P + row % w;   // causal: row i sees j <= P+i
-                        if (seen) mx[rb][v] = fmaxf(mx[rb][v], a1[rb][v] * scale2);
-                    }
-            }
-#pragma unroll
-            for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    const float r = -nref[rb][v];              // -inf before the first token
-                    if (mx[rb][v] > r) {
-                        sum[rb][v] *= exp2f(r - mx[rb][v]);    // exp2(-inf) = 0 on first use
-                        nref[rb][v] = -mx[rb][v];
-                    }
+        for (int rb = 0; rb < NRB; ++rb) {
+            if (rb < n_rb) {
+                if (kAhead) {
+                    if (rb + 1 < NRB) read_block(qa[(rb + 1) & (kAhead ? 1 : 0)], min(rb + 1, n_rb - 1));
+                } else {
+                    read_block(qa[0], rb);
                 }
-            for (int st = 0; st < 4; ++st) {
-                f32x4_t a1[RB];
-                subtile_logits<RB>(a1, qa, tile, st, lane);
-                const int j = t0 + 16 * st + m;
+                // acc[st][v] = logit of token t0 + 16 st + 4 g + v against query row 16 rb + m
+                f32x4_t acc[4];
 #pragma unroll
-                for (int rb = 0; rb < RB; ++rb)
+                for (int st = 0; st < 4; ++st) acc[st] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                    for (int v = 0; v < 4; ++v) {
-                        const int row = row0 + 16 * rb + 4 * g + v;
-                        const bool seen = row < R && j < t_end && j <= P + row % w;
-                        if (seen) sum[rb][v] += exp2f(fmaf(a1[rb][v], scale2, nref[rb][v]));
+                for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+                    for (int st = 0; st < 4; ++st)
+                        acc[st] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                            __builtin_bit_cast(bf16x8_t, cur[st][ks]), qa[kAhead ? (rb & 1) : 0][ks], acc[st], 0, 0, 0);
+                // fast path: all 16 logits against the current reference; a sum outside [0, 2^12]
+                // (a logit far above the reference, or no reference yet) takes the slow path
+                float t = 0.f;
+                bool redo = edge;
+                if (!edge) {
+                    float t4[4];
+#pragma unroll
+                    for (int st = 0; st < 4; ++st)
+                        t4[st] = (__builtin_amdgcn_exp2f(fmaf(acc[st][0], scale2, nref[rb])) +
+                                  __builtin_amdgcn_exp2f(fmaf(acc[st][1], scale2, nref[rb]))) +
+                                 (__builtin_amdgcn_exp2f(fmaf(acc[st][2], scale2, nref[rb])) +
+                                  __builtin_amdgcn_exp2f(fmaf(acc[st][3], scale2, nref[rb])));
+                    t = (t4[0] + t4[1]) + (t4[2] + t4[3]);
+                    redo = !(t <= 4096.f);
+                }
+                if (__builtin_amdgcn_ballot_w64(redo) == 0ull) {
+                    sum[rb] += t;
+                } else {
+                    const int last = P + (16 * rb + m) % w;        // last token this row may see
+                    float mx = -INFINITY;
+#pragma unroll
+                    for (int st = 0; st < 4; ++st)
+#pragma unroll
+                        for (int v = 0; v < 4; ++v) {
+                            const int j = t0 + 16 * st + 4 * g + v;
+                            if (j < t_end && j <= last) mx = fmaxf(mx, acc[st][v] * scale2);
+                        }
+                    const float r = -nref[rb];                     // -inf before the first token
+                    if (mx > r) {
+                        sum[rb] *= exp2f(r - mx);                  // exp2(-inf) = 0 on first use
+                        nref[rb] = -mx;
                     }
+#pragma unroll
+                    for (int st = 0; st < 4; ++st)
+#pragma unroll
+                        for (int v = 0; v < 4; ++v) {
+                            const int j = t0 + 16 * st + 4 * g + v;
+                            if (j < t_end && j <= last) sum[rb] += exp2f(fmaf(acc[st][v], scale2, nref[rb]));
+                        }
+                }
             }
         }
-        if (it + 1 < n_tiles) ktile_store(n1, lds[(it + 1) & 1], tid);
-        lds_barrier();
-        n1 = n2;
+    };
+    if (n_tiles > 0) {
+        load_tile(ka, wv);
+        for (int tile = wv; tile < n_tiles; tile += 8) {
+            process(ka, kb, tile);
+            if (tile + 4 < n_tiles) process(kb, ka, tile + 4);
+        }
     }
 
-    // combine the 16 token slots (lanes with equal lane/16) of every row
+    // the four lane groups saw different tokens of the same rows: combine, then one lane per row writes
 #pragma unroll
-    for (int rb = 0; rb < RB; ++rb)
+    for (int rb = 0; rb < NRB; ++rb) {
+        if (rb < n_rb) {
+            float r = -nref[rb], sm = sum[rb];
 #pragma unroll
-        for (int v = 0; v < 4; ++v) {
-            float r = -nref[rb][v], sm = sum[rb][v];
-#pragma unroll
-            for (int o = 1; o < 16; o <<= 1) {
+            for (int o = 16; o < 64; o <<= 1) {
                 const float r2 = __shfl_xor(r, o, 64), s2 = __shfl_xor(sm, o, 64);
                 const float nr = fmaxf(r, r2);
                 const float a = sm > 0.f ? sm * exp2f(r - nr) : 0.f;
@@ -324,9 +267,10 @@ __global__ __launch_bounds__(256, 2) void score_stats_mfma_kernel(
                 r = nr;
                 sm = a + bb;
             }
-            const int row = row0 + 16 * rb + 4 * g + v;
-            if (m == 0 && row < R) stats[((int64_t)bh * n_chunks + c) * R + row] = make_float2(r, sm);
+            if (g == 0)
+                stats[((int64_t)bh * (n_chunks * 4) + c * 4 + wv) * R + 16 * rb + m] = make_float2(r, sm);
         }
+    }
 }
 
 // pass 2: vote[g][j] = sum over the w rows of query head g of exp2(logit - lse), without
@@ -567,7 +511,7 @@ ScorePlan plan_score(int B, int H, int G, int N, int w) {
     p.chunk = chunk;
     const size_t P = (size_t)(N - w);
     p.stats_off = 0;
-    p.lse_off = align_up((size_t)BH * nc * p.R * sizeof(float2), 256);
+    p.lse_off = align_up((size_t)BH * nc * 4 * p.R * sizeof(float2), 256);   // up to 4 partials per chunk
     p.vote_off = p.lse_off + align_up((size_t)BH * p.R * sizeof(float), 256);
     p.bytes = p.vote_off + align_up((size_t)BH * G * P * sizeof(float), 256);
     return p;
@@ -583,16 +527,27 @@ static hipError_t run_score(const T* Q, const T* K, int B, int H, int G, int N, 
     float* lse = reinterpret_cast<float*>(ws + p.lse_off);
     float* vote = reinterpret_cast<float*>(ws + p.vote_off);
     const dim3 grid1((unsigned)(BH * p.n_chunks));
+    int n_parts = p.n_chunks;            // partial statistics per query row
     if constexpr (sizeof(T) == 2) {
         if (mfma) {
-            env.begin("score_stats_mfma");
-            if (p.R <= 128)
-                score_stats_mfma_kernel<2><<<grid1, dim3(256), 0, s>>>(Q, K, H, p.R, N, w, ks[0], ks[1], ks[2],
-                                                                        p.n_chunks, p.chunk, stats);
-            else
-                score_stats_mfma_kernel<4><<<grid1, dim3(256), 0, s>>>(Q, K, H, p.R, N, w, ks[0], ks[1], ks[2],
-                                                                        p.n_chunks, p.chunk, stats);
+            env.begin("score_stats_wave");
+            if (p.R <= 128) {
+                constexpr int lds_bytes = 16 * 8 * kRowBytes;
+                hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(score_stats_wave_kernel<8>),
+                                                   hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+                if (e != hipSuccess) return e;
+                score_stats_wave_kernel<8><<<grid1, dim3(256), lds_bytes, s>>>(Q, K, H, p.R, N, w, ks[0], ks[1], ks[2],
+                                                                               p.n_chunks, p.chunk, stats);
+            } else {
+                constexpr int lds_bytes = 16 * 16 * kRowBytes;
+                hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(score_stats_wave_kernel<16>),
+                                                   hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+                if (e != hipSuccess) return e;
+                score_stats_wave_kernel<16><<<grid1, dim3(256), lds_bytes, s>>>(Q, K, H, p.R, N, w, ks[0], ks[1], ks[2],
+                                                                                p.n_chunks, p.chunk, stats);
+            }
             env.end();
+            n_parts = p.n_chunks * 4;
         }
     }
     if (!mfma) {
@@ -604,7 +559,7 @@ static hipError_t run_score(const T* Q, const T* K, int B, int H, int G, int N, 
     }
     const int rows = BH * p.R;
     env.begin("score_lse");
-    score_lse_kernel<<<dim3((rows + 255) / 256), dim3(256), 0, s>>>(stats, rows, p.R, p.n_chunks, lse);
+    score_lse_kernel<<<dim3((rows + 255) / 256), dim3(256), 0, s>>>(stats, rows, p.R, n_parts, lse);
     env.end();
     const int n_tiles = (P + 255) / 256;
     const int n_pool_tiles = (P + kPoolTile - 1) / kPoolTile;
