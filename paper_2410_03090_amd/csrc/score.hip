@@ -362,17 +362,16 @@ __global__ __launch_bounds__(256) void score_vote_wave_kernel(
                 ++qh;
             }
         };
-        // the LDS reads of a row block are issued one block ahead of its MFMAs
-        RowBlock b0, b1;
-        read_block(b0, 0);
-        int rb = 0;
-        for (; rb + 1 < n_rb; rb += 2) {
-            read_block(b1, rb + 1);
-            step(b0);
-            read_block(b0, min(rb + 2, n_rb - 1));
-            step(b1);
+        // fully unrolled over the row blocks, so that the scheduler can run the MFMAs of one
+        // block under the exp2 work of the previous one
+        RowBlock blk;
+#pragma unroll
+        for (int rb = 0; rb < NRB; ++rb) {
+            if (rb < n_rb) {
+                read_block(blk, rb);
+                step(blk);
+            }
         }
-        if (rb < n_rb) step(b0);
     };
     load_tile(ka, wv);
     for (int tile = wv; tile < n_tiles; tile += 8) {
