@@ -450,39 +450,52 @@ __global__ __launch_bounds__(256) void score_vote_alu_kernel(
 }
 
 // pool + group sum.  A workgroup takes 1024 consecutive tokens of one KV head; the votes of up
-// to four query heads at a time (plus `half` tokens either side, -inf outside [0, P)) are staged
-// in LDS, each thread forms the running maxima of four consecutive tokens from 4 + 2*half staged
-// values per query head and adds them up.
+// to four query heads at a time (plus HALF tokens either side, -inf outside [0, P)) are staged
+// in LDS (one 16-byte load per thread where the row allows it), each thread forms the running
+// maxima of four consecutive tokens from 4 + 2*HALF staged values per query head and adds them.
 constexpr int kPoolTile = 1024;
-constexpr int kPoolMaxHalf = 7;
 
+template <int HALF>
 __global__ __launch_bounds__(256) void score_pool_kernel(const float* __restrict__ vote, int G, int P,
-                                                         int half, int n_tiles, float* __restrict__ score) {
-    __shared__ float sh[4][kPoolTile + 2 * kPoolMaxHalf + 2];
+                                                         int n_tiles, float* __restrict__ score) {
+    __shared__ float sh[4][kPoolTile + 2 * HALF + 4];
     const int bh = blockIdx.x / n_tiles, tile = blockIdx.x % n_tiles;
     const int tile0 = tile * kPoolTile;
-    const int span = kPoolTile + 2 * kPoolMaxHalf;
+    const int tid = threadIdx.x;
+    const bool vec = (P & 3) == 0;               // rows start 16-byte aligned
     float total[4] = {0.f, 0.f, 0.f, 0.f};
     for (int g0 = 0; g0 < G; g0 += 4) {
         const int ng = min(4, G - g0);
         for (int gi = 0; gi < ng; ++gi) {
             const float* vg = vote + ((int64_t)bh * G + g0 + gi) * P;
-            for (int idx = threadIdx.x; idx < span; idx += 256) {
-                const int j = tile0 - half + idx;
-                sh[gi][idx] = (j >= 0 && j < P && idx < kPoolTile + 2 * half) ? vg[j] : -INFINITY;
+            const int j = tile0 + 4 * tid;
+            float4 v = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
+            if (vec && j + 3 < P) {
+                v = *reinterpret_cast<const float4*>(vg + j);
+            } else {
+                if (j < P) v.x = vg[j];
+                if (j + 1 < P) v.y = vg[j + 1];
+                if (j + 2 < P) v.z = vg[j + 2];
+                if (j + 3 < P) v.w = vg[j + 3];
+            }
+            float* dst = &sh[gi][HALF + 4 * tid];
+            dst[0] = v.x; dst[1] = v.y; dst[2] = v.z; dst[3] = v.w;
+            if (tid < 2 * HALF) {                 // HALF tokens before and after the tile
+                const int idx = tid < HALF ? tid : kPoolTile + tid;
+                const int jh = tile0 - HALF + idx;
+                sh[gi][idx] = (jh >= 0 && jh < P) ? vg[jh] : -INFINITY;
             }
         }
         __syncthreads();
         for (int gi = 0; gi < ng; ++gi) {
-            float v[4 + 2 * kPoolMaxHalf];
+            float v[4 + 2 * HALF];
 #pragma unroll
-            for (int k = 0; k < 4 + 2 * kPoolMaxHalf; ++k) v[k] = sh[gi][4 * threadIdx.x + k];
+            for (int k = 0; k < 4 + 2 * HALF; ++k) v[k] = sh[gi][4 * tid + k];
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 float mx = v[e];
 #pragma unroll
-                for (int d = 1; d <= 2 * kPoolMaxHalf; ++d)
-                    if (d <= 2 * half) mx = fmaxf(mx, v[e + d]);
+                for (int d = 1; d <= 2 * HALF; ++d) mx = fmaxf(mx, v[e + d]);
                 total[e] += mx;
             }
         }
@@ -490,7 +503,7 @@ __global__ __launch_bounds__(256) void score_pool_kernel(const float* __restrict
     }
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-        const int j = tile0 + 4 * threadIdx.x + e;
+        const int j = tile0 + 4 * tid + e;
         if (j < P) score[(int64_t)bh * P + j] = total[e];
     }
 }
@@ -590,8 +603,19 @@ static hipError_t run_score(const T* Q, const T* K, int B, int H, int G, int N, 
         env.end();
     }
     env.begin("score_pool");
-    score_pool_kernel<<<dim3((unsigned)(BH * n_pool_tiles)), dim3(256), 0, s>>>(vote, G, P, pool / 2,
-                                                                               n_pool_tiles, score_out);
+    {
+        const dim3 pg((unsigned)(BH * n_pool_tiles)), pb(256);
+        switch (pool / 2) {
+            case 0: score_pool_kernel<0><<<pg, pb, 0, s>>>(vote, G, P, n_pool_tiles, score_out); break;
+            case 1: score_pool_kernel<1><<<pg, pb, 0, s>>>(vote, G, P, n_pool_tiles, score_out); break;
+            case 2: score_pool_kernel<2><<<pg, pb, 0, s>>>(vote, G, P, n_pool_tiles, score_out); break;
+            case 3: score_pool_kernel<3><<<pg, pb, 0, s>>>(vote, G, P, n_pool_tiles, score_out); break;
+            case 4: score_pool_kernel<4><<<pg, pb, 0, s>>>(vote, G, P, n_pool_tiles, score_out); break;
+            case 5: score_pool_kernel<5><<<pg, pb, 0, s>>>(vote, G, P, n_pool_tiles, score_out); break;
+            case 6: score_pool_kernel<6><<<pg, pb, 0, s>>>(vote, G, P, n_pool_tiles, score_out); break;
+            default: score_pool_kernel<7><<<pg, pb, 0, s>>>(vote, G, P, n_pool_tiles, score_out); break;
+        }
+    }
     env.end();
     return hipGetLastError();
 }
