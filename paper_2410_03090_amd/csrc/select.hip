@@ -86,19 +86,25 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const float* __rest
         // any two keys differ.  Scores of one head usually share their exponent and leading
         // mantissa bits; digits taken from the very top would put every key in one counter.
         uint32_t kmin = 0xffffffffu, kmax = 0u;
-        for (int j0 = tid; j0 < P; j0 += 8 * kSelThreads) {
-            float v[8];
+        // rows of P floats start 16-byte aligned when P is a multiple of 4: 16-byte loads, two
+        // per thread in flight; otherwise (and for the tail) plain 4-byte loads
+        const int P4 = (P & 3) == 0 ? P >> 2 : 0;
+        const float4* sc4 = reinterpret_cast<const float4*>(sc);
+        for (int q0 = tid; q0 < P4; q0 += 2 * kSelThreads) {
+            const float4 a = sc4[q0];
+            const float4 c = q0 + kSelThreads < P4 ? sc4[q0 + kSelThreads] : a;
+            const float vals[8] = {a.x, a.y, a.z, a.w, c.x, c.y, c.z, c.w};
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
-                const int j = j0 + e * kSelThreads;
-                v[e] = j < P ? sc[j] : sc[tid < P ? tid : 0];
-            }
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const uint32_t key = order_key(v[e]);
+                const uint32_t key = order_key(vals[e]);
                 kmin = key < kmin ? key : kmin;
                 kmax = key > kmax ? key : kmax;
             }
+        }
+        for (int j = 4 * P4 + tid; j < P; j += kSelThreads) {
+            const uint32_t key = order_key(sc[j]);
+            kmin = key < kmin ? key : kmin;
+            kmax = key > kmax ? key : kmax;
         }
 #pragma unroll
         for (int o = 32; o > 0; o >>= 1) {
@@ -127,21 +133,18 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const float* __rest
             const uint32_t nb = 1u << width;
             for (int i = tid; i < kBins; i += kSelThreads) sm.hist[i] = 0;
             __syncthreads();
-            // eight independent loads per thread in flight before any of them is consumed
-            for (int j0 = tid; j0 < P; j0 += 8 * kSelThreads) {
-                float v[8];
-#pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const int j = j0 + e * kSelThreads;
-                    v[e] = j < P ? sc[j] : 0.f;
-                }
-#pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const uint32_t key = order_key(v[e]);
-                    if (j0 + e * kSelThreads < P && (key & prefix_mask) == prefix)
-                        atomicAdd(&sm.hist[(key >> shift) & (nb - 1)], 1u);
-                }
+            auto count = [&](float v) {
+                const uint32_t key = order_key(v);
+                if ((key & prefix_mask) == prefix) atomicAdd(&sm.hist[(key >> shift) & (nb - 1)], 1u);
+            };
+            for (int q0 = tid; q0 < P4; q0 += 2 * kSelThreads) {
+                const float4 a = sc4[q0];
+                const bool two = q0 + kSelThreads < P4;
+                const float4 c = two ? sc4[q0 + kSelThreads] : a;
+                count(a.x); count(a.y); count(a.z); count(a.w);
+                if (two) { count(c.x); count(c.y); count(c.z); count(c.w); }
             }
+            for (int j = 4 * P4 + tid; j < P; j += kSelThreads) count(sc[j]);
             __syncthreads();
             // walk the digits from the top: thread t owns digits nb-1-2t and nb-2-2t
             uint32_t c0 = 0, c1 = 0;
