@@ -24,6 +24,13 @@ Parity status of each function (what pins it lives in tests/test_oracle_*.py):
                     conservation, spike -> plateau behaviour of the max-pool.
 * select_gather     pinned: exhaustive subset search on tiny inputs, structural
                     invariants, byte compare of gathered rows.
+* decode_init /     pinned: without eviction the cumulative scores of T decode steps
+  decode_step       equal the unpooled window score of the same T queries (the prefill
+                    function above, itself pinned); equal keys give the uniform closed
+                    form (each entry gains G/n, the output is the mean value row);
+                    probability mass G per step; a dominant key takes the whole step;
+                    the evicted entry checked by exhaustive search on tiny caches;
+                    occupancy and recent-window invariants over long runs.
 """
 from __future__ import annotations
 
@@ -233,3 +240,73 @@ def select_gather(score, budget, K, V, w: int, cap: int):
                 K_out[b, h, r] = K[b, h, sel[r]]
                 V_out[b, h, r] = V[b, h, sel[r]]
     return K_out, V_out, idx, length
+
+
+# --------------------------------------------------------------------------
+# O5  decode-time eviction  (Sec. 3.3.3 "Dynamic KV Cache Eviction", last
+#     sentence; Alg. 2 "Decoding": the new token joins the head's cache, the
+#     query attends to the joined cache, then the cache is updated)
+# --------------------------------------------------------------------------
+def decode_init(score_row: np.ndarray, idx: np.ndarray, N: int, w: int) -> np.ndarray:
+    """Cumulative scores a head's compacted cache starts decoding with: the
+    prefill score of every kept prefix position (position < N-w).  The w window
+    positions carry no prefill score (they were kept unconditionally) and start
+    at zero, like every token that joins later."""
+    P = N - w
+    score_row = np.asarray(score_row, dtype=np.float64)
+    return np.array([score_row[j] if j < P else 0.0 for j in np.asarray(idx)], dtype=np.float64)
+
+
+def decode_step(Kc: np.ndarray, Vc: np.ndarray, idx: np.ndarray, cum: np.ndarray,
+                q: np.ndarray, k_new: np.ndarray, v_new: np.ndarray, pos: int,
+                budget: int, w: int, decide_dtype=np.float32):
+    """One generated token for one KV head.
+
+    Kc, Vc [n, D] are the head's cached rows, idx [n] their original positions
+    (distinct, all < pos), cum [n] their cumulative scores; q [G, D] the new
+    token's G query heads, k_new / v_new [D] its key and value, pos its position.
+
+    1. the new token joins the cache with cumulative score 0;
+    2. every query head attends to the n+1 entries:
+       p_g = softmax_j(q_g . k_j / sqrt(D)), out_g = sum_j p_gj v_j;
+    3. every entry's cumulative score grows by sum_g p_gj;
+    4. if the cache now holds more than ``budget`` entries (a budget below w counts
+       as w, as at prefill), the entry of lowest cumulative score leaves.  The most recent w positions (pos-w+1 .. pos) are
+       exempt, as the observation window is at prefill; equal scores resolve
+       towards the older position.  The comparison is made on scores rounded to
+       ``decide_dtype`` (the precision the compared path keeps them in).
+
+    Returns (Kc, Vc, idx, cum, out [G, D], evicted position or -1), entries in
+    ascending position order."""
+    Kc = np.asarray(Kc, dtype=np.float64)
+    Vc = np.asarray(Vc, dtype=np.float64)
+    q = np.asarray(q, dtype=np.float64)
+    n, D = Kc.shape
+    assert w >= 1
+    budget = max(int(budget), w)
+    keys = np.concatenate([Kc, np.asarray(k_new, dtype=np.float64)[None, :]], axis=0)
+    vals = np.concatenate([Vc, np.asarray(v_new, dtype=np.float64)[None, :]], axis=0)
+    where = np.concatenate([np.asarray(idx, dtype=np.int64), [pos]])
+    total = np.concatenate([np.asarray(cum, dtype=np.float64), [0.0]])
+    G = q.shape[0]
+    out = np.zeros((G, D))
+    for g in range(G):
+        logits = keys @ q[g] / np.sqrt(D)
+        ex = np.exp(logits - logits.max())
+        prob = ex / ex.sum()
+        out[g] = prob @ vals
+        total = total + prob
+    evicted = -1
+    if n + 1 > budget:
+        seen = total.astype(decide_dtype)
+        best = -1
+        for j in range(n + 1):
+            if where[j] > pos - w:
+                continue
+            if best < 0 or seen[j] < seen[best] or (seen[j] == seen[best] and where[j] < where[best]):
+                best = j
+        assert best >= 0
+        evicted = int(where[best])
+        keep = np.arange(n + 1) != best
+        keys, vals, where, total = keys[keep], vals[keep], where[keep], total[keep]
+    return keys, vals, where.astype(np.int32), total, out, evicted
