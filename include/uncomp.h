@@ -8,6 +8,11 @@
  *   uncomp_window_score    observation-window attention score of every prefix token
  *   uncomp_select_gather   per-head top-k of the scores, compaction of K and V
  *
+ * and, for the tokens generated afterwards:
+ *
+ *   uncomp_decode_init     cumulative scores of the compacted cache from the prefill score
+ *   uncomp_decode_step     one token: attention over the cache, score update, eviction
+ *
  * Conventions that hold for every call:
  *   - Pointers named X, K, V, Qwin, *_out, entropy, score, budget are DEVICE pointers
  *     owned by the caller; the library never allocates, frees or keeps them.  The
@@ -178,6 +183,49 @@ uncomp_status uncomp_select_gather(uncomp_ctx* ctx, const float* score, const in
                                    const int64_t kv_strides[3], int cap,
                                    void* K_out, void* V_out, int32_t* idx_out, int32_t* len_out,
                                    void* stream);
+
+/*
+ * Decode-time eviction (Sec. 3.3.3 "Dynamic KV Cache Eviction", last sentence: as tokens
+ * are generated the entry of lowest cumulative attention score leaves; Alg. 2 "Decoding":
+ * the new token joins the head's cache, the query attends to the joined cache, the cache
+ * is updated).  The state of a head is what uncomp_select_gather produced: K_c / V_c
+ * [n_heads][cap][D] rows, idx [n_heads][cap] their original positions, len [n_heads] the
+ * rows in use, plus cum [n_heads][cap] floats, the cumulative score of each row.  All of it
+ * is DEVICE memory owned by the caller and updated in place.
+ *
+ * uncomp_decode_init fills cum from the prefill score: cum[h][r] = score[h][idx[h][r]] for
+ * r < len[h] and idx < N - w; rows of the observation window (idx >= N - w) and rows at
+ * r >= len[h] start at 0.  score is [n_heads][N - w] floats.
+ */
+uncomp_status uncomp_decode_init(uncomp_ctx* ctx, const float* score, const int32_t* idx,
+                                 const int32_t* len, int n_heads, int N, int w, int cap,
+                                 float* cum_out, void* stream);
+
+/*
+ * One generated token for n_heads KV heads (any mix of layers and sequences).  q
+ * [n_heads][G][D], k_new / v_new [n_heads][D] (dense, dtype as the cache), pos [n_heads]
+ * int32 the token's position in its sequence, budget [n_heads] int32.  Per head, with n =
+ * len[h] rows cached:
+ *   1. the new token joins with cumulative score 0 (n + 1 entries);
+ *   2. p_g = softmax over the entries of q_g . k / sqrt(D) in fp32;
+ *      out[h][g][:] = sum_r p_gr v_r  (floats [n_heads][G][D]; out may be NULL);
+ *   3. cum of every entry grows by sum_g p_gr;
+ *   4. b = clamp(budget[h], w, cap).  If n + 1 > b, the entry of lowest cum among those at
+ *      positions <= pos - w (the w most recent positions are exempt) leaves, equal scores
+ *      by lower position, and the new token takes its row; len stays n and evicted[h] is the
+ *      position that left.  Otherwise the new token takes row n, len becomes n + 1 and
+ *      evicted[h] = -1.  (evicted may be NULL.)
+ * Row order inside a head is therefore unspecified after the first eviction; idx tells which
+ * position a row holds.  A malformed state in which the head is over budget but no entry is
+ * old enough to leave appends while n < cap, else drops the token and reports -2.
+ * Requires 1 <= w <= cap, 1 <= G <= 16, D == 128, G*(cap + 1) <= 36864, 16-byte aligned
+ * q / k_new / v_new / K_c / V_c.  Needs no workspace.
+ */
+uncomp_status uncomp_decode_step(uncomp_ctx* ctx, const void* q, const void* k_new,
+                                 const void* v_new, uncomp_dtype dtype, int n_heads, int G, int D,
+                                 const int32_t* pos, const int32_t* budget, int w, int cap,
+                                 void* K_c, void* V_c, int32_t* idx, float* cum, int32_t* len,
+                                 float* out, int32_t* evicted, void* stream);
 
 #ifdef __cplusplus
 }

@@ -25,6 +25,7 @@ EXPORTS = (
     "uncomp_create", "uncomp_destroy", "uncomp_workspace_bytes", "uncomp_last_error",
     "uncomp_profile", "uncomp_profile_read", "uncomp_set_kernel_path", "uncomp_set_overlap", "uncomp_join",
     "uncomp_head_entropy", "uncomp_assign_budgets", "uncomp_window_score", "uncomp_select_gather",
+    "uncomp_decode_init", "uncomp_decode_step",
 )
 
 _lib = None
@@ -77,6 +78,11 @@ def load_library() -> ctypes.CDLL:
     lib.uncomp_select_gather.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32,
                                          c.POINTER(i64), i32, vp, vp, vp, vp, vp]
     lib.uncomp_select_gather.restype = i32
+    lib.uncomp_decode_init.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, vp, vp]
+    lib.uncomp_decode_init.restype = i32
+    lib.uncomp_decode_step.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, vp, vp, i32, i32,
+                                       vp, vp, vp, vp, vp, vp, vp, vp]
+    lib.uncomp_decode_step.restype = i32
     _lib = lib
     return lib
 
@@ -219,3 +225,42 @@ class Context:
             self.handle, score.data_ptr(), budget.data_ptr(), _ptr(K), _ptr(V), code, B, H, N, D, int(w),
             strides, int(cap), _ptr(Ko), _ptr(Vo), idx.data_ptr(), ln.data_ptr(), _stream()))
         return Ko, Vo, idx, ln
+
+    # -- decode-time eviction ------------------------------------------------------------
+    def decode_init(self, score: torch.Tensor, idx: torch.Tensor, length: torch.Tensor, N: int, w: int, out=None):
+        """score [..., N-w] float32, idx [..., cap] int32, length [...] int32 (leading dims = heads).
+        Returns cum [..., cap] float32."""
+        cap = idx.shape[-1]
+        n_heads = length.numel()
+        assert score.is_contiguous() and idx.is_contiguous() and length.is_contiguous()
+        assert score.shape[-1] == N - w and score.numel() == n_heads * (N - w) and idx.numel() == n_heads * cap
+        if out is None:
+            out = torch.empty(idx.shape, dtype=torch.float32, device=idx.device)
+        self._check(self.lib.uncomp_decode_init(
+            self.handle, score.data_ptr(), idx.data_ptr(), length.data_ptr(), n_heads, int(N), int(w), cap,
+            out.data_ptr(), _stream()))
+        return out
+
+    def decode_step(self, q: torch.Tensor, k_new: torch.Tensor, v_new: torch.Tensor, pos: torch.Tensor,
+                    budget: torch.Tensor, w: int, K_c: torch.Tensor, V_c: torch.Tensor, idx: torch.Tensor,
+                    cum: torch.Tensor, length: torch.Tensor, out=None, evicted=None, want_out: bool = True):
+        """q [n_heads, G, D], k_new / v_new [n_heads, D], pos / budget / length [n_heads] int32,
+        K_c / V_c [n_heads, cap, D], idx / cum [n_heads, cap]; the cache tensors are updated in place
+        (leading dims may be split, e.g. [B, H, ...]).  Returns out [n_heads, G, D] float32, evicted [n_heads]."""
+        n_heads = length.numel()
+        G, D = q.shape[-2], q.shape[-1]
+        cap = idx.shape[-1]
+        for t in (q, k_new, v_new, pos, budget, K_c, V_c, idx, cum, length):
+            assert t.is_contiguous()
+        assert q.dtype == K_c.dtype == V_c.dtype == k_new.dtype == v_new.dtype
+        assert pos.dtype == budget.dtype == length.dtype == idx.dtype == torch.int32 and cum.dtype == torch.float32
+        assert q.numel() == n_heads * G * D and K_c.numel() == n_heads * cap * D and k_new.numel() == n_heads * D
+        if out is None and want_out:
+            out = torch.empty(n_heads, G, D, dtype=torch.float32, device=q.device)
+        if evicted is None:
+            evicted = torch.empty(n_heads, dtype=torch.int32, device=q.device)
+        self._check(self.lib.uncomp_decode_step(
+            self.handle, q.data_ptr(), k_new.data_ptr(), v_new.data_ptr(), _dtype_code(K_c), n_heads, G, D,
+            pos.data_ptr(), budget.data_ptr(), int(w), cap, K_c.data_ptr(), V_c.data_ptr(), idx.data_ptr(),
+            cum.data_ptr(), length.data_ptr(), _ptr(out), evicted.data_ptr(), _stream()))
+        return out, evicted

@@ -270,4 +270,48 @@ uncomp_status uncomp_select_gather(uncomp_ctx* ctx, const float* score, const in
     return UNCOMP_OK;
 }
 
+uncomp_status uncomp_decode_init(uncomp_ctx* ctx, const float* score, const int32_t* idx, const int32_t* len,
+                                 int n_heads, int N, int w, int cap, float* cum_out, void* stream) {
+    if (ctx == nullptr) return UNCOMP_ERR_INVALID_ARG;
+    if (score == nullptr || idx == nullptr || len == nullptr || cum_out == nullptr)
+        return fail(ctx, UNCOMP_ERR_INVALID_ARG, "decode_init: null pointer");
+    if (n_heads <= 0 || N <= 0 || cap <= 0) return fail(ctx, UNCOMP_ERR_INVALID_ARG, "decode_init: sizes must be positive");
+    if (w <= 0 || w >= N) return fail(ctx, UNCOMP_ERR_UNSUPPORTED, "decode_init: need 0 < w < N");
+    hipError_t e = launch_decode_init(score, idx, len, n_heads, N, w, cap, cum_out,
+                                      Env{static_cast<hipStream_t>(stream), &ctx->prof, ctx->force_alu});
+    if (e != hipSuccess) return hip_fail(ctx, e, "decode_init: launch");
+    return UNCOMP_OK;
+}
+
+uncomp_status uncomp_decode_step(uncomp_ctx* ctx, const void* q, const void* k_new, const void* v_new,
+                                 uncomp_dtype dtype, int n_heads, int G, int D, const int32_t* pos,
+                                 const int32_t* budget, int w, int cap, void* K_c, void* V_c, int32_t* idx,
+                                 float* cum, int32_t* len, float* out, int32_t* evicted, void* stream) {
+    if (ctx == nullptr) return UNCOMP_ERR_INVALID_ARG;
+    if (q == nullptr || k_new == nullptr || v_new == nullptr || pos == nullptr || budget == nullptr ||
+        K_c == nullptr || V_c == nullptr || idx == nullptr || cum == nullptr || len == nullptr)
+        return fail(ctx, UNCOMP_ERR_INVALID_ARG, "decode_step: null pointer");
+    if (n_heads <= 0 || cap <= 0) return fail(ctx, UNCOMP_ERR_INVALID_ARG, "decode_step: sizes must be positive");
+    if (dtype != UNCOMP_BF16 && dtype != UNCOMP_F32) return fail(ctx, UNCOMP_ERR_UNSUPPORTED, "decode_step: dtype");
+    if (D != kD) return fail(ctx, UNCOMP_ERR_UNSUPPORTED, "decode_step: D must be 128");
+    if (G < 1 || G > 16) return fail(ctx, UNCOMP_ERR_UNSUPPORTED, "decode_step: need 1 <= G <= 16");
+    if (w < 1 || w > cap) return fail(ctx, UNCOMP_ERR_INVALID_ARG, "decode_step: need 1 <= w <= cap");
+    if ((int64_t)G * ((int64_t)cap + 1) > 36864)
+        return fail(ctx, UNCOMP_ERR_UNSUPPORTED, "decode_step: G*(cap+1) must be <= 36864");
+    if (!aligned16(q) || !aligned16(k_new) || !aligned16(v_new) || !aligned16(K_c) || !aligned16(V_c))
+        return fail(ctx, UNCOMP_ERR_INVALID_ARG, "decode_step: 16-byte aligned pointers required");
+    float* out_p = out;
+    if (out_p == nullptr) {
+        // the kernel always forms the output; without a destination it lands in the workspace
+        if ((size_t)n_heads * G * kD * sizeof(float) > ctx->ws_bytes)
+            return fail(ctx, UNCOMP_ERR_WORKSPACE, "decode_step: out == NULL needs %zu workspace bytes",
+                        (size_t)n_heads * G * kD * sizeof(float));
+        out_p = reinterpret_cast<float*>(ctx->ws);
+    }
+    hipError_t e = launch_decode_step(q, k_new, v_new, dtype, n_heads, G, pos, budget, w, cap, K_c, V_c, idx, cum,
+                                      len, out_p, evicted, Env{static_cast<hipStream_t>(stream), &ctx->prof, ctx->force_alu});
+    if (e != hipSuccess) return hip_fail(ctx, e, "decode_step: launch");
+    return UNCOMP_OK;
+}
+
 }  // extern "C"

@@ -108,6 +108,13 @@ hipError_t launch_select_gather(const float* score, const int32_t* budget, const
                                 const void* V, uncomp_dtype dt, int B, int H, int N, int w,
                                 const int64_t ks[3], int cap, void* K_out, void* V_out,
                                 int32_t* idx_out, int32_t* len_out, const Env& env);
+hipError_t launch_decode_init(const float* score, const int32_t* idx, const int32_t* len, int n_heads,
+                              int N, int w, int cap, float* cum, const Env& env);
+size_t decode_step_lds_bytes(int G, int cap);
+hipError_t launch_decode_step(const void* q, const void* k_new, const void* v_new, uncomp_dtype dt,
+                              int n_heads, int G, const int32_t* pos, const int32_t* budget, int w, int cap,
+                              void* Kc, void* Vc, int32_t* idx, float* cum, int32_t* len, float* out,
+                              int32_t* evicted, const Env& env);
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 

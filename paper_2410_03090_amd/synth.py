@@ -10,7 +10,9 @@ KV head) a rank r is drawn uniformly from the config's range, then
     K = s_l * (U V^T + 0.1 E),  U [N,r], V [D,r] ~ N(0,1)/sqrt(r), E ~ N(0,1)
 with s_l a per-layer scale, values V_cache ~ N(0,1), and the observation-window
 queries of each of the G query heads sharing a KV head built the same way with
-the same V:  Q = U' V^T + 0.1 E'.  Everything is generated in fp32 with torch's
+the same V:  Q = U' V^T + 0.1 E'.  Tokens generated after the prompt (decode
+steps) get keys and queries from the same V with fresh coefficients and noise.
+Everything is generated in fp32 with torch's
 generator for the chosen device (seed = seed0 + linear (layer,batch,head) index,
 so a single head can be regenerated alone), then rounded once to the config's
 dtype; every consumer reads those rounded bits.
@@ -110,6 +112,26 @@ def gen_head(cfg: Config, seed0: int, l: int, b: int, h: int, device="cpu", scal
     Q = Uq @ Vf.T + 0.1 * Eq
     dt = cfg.torch_dtype
     return K.to(dt), Vc.to(dt), Q.to(dt)
+
+
+def gen_decode_tokens(cfg: Config, seed0: int, l: int, b: int, h: int, T: int, device="cpu", scale: float = 1.0):
+    """T generated tokens that follow gen_head's prompt for the same (layer, batch, KV
+    head): keys k [T,D], values v [T,D] and queries q [T,G,D] drawn from the same factor
+    matrix V as the prompt (re-drawn here from the head's seed), with their own noise."""
+    r = head_rank(cfg, seed0, l, b, h)
+    head = ((l * cfg.B) + b) * cfg.H + h
+    g = torch.Generator(device=device).manual_seed(seed0 + head)
+    f32 = dict(generator=g, device=device, dtype=torch.float32)
+    inv = 1.0 / math.sqrt(r)
+    torch.randn(cfg.N, r, **f32)                       # the prompt's U: drawn to reach V's place in the stream
+    Vf = torch.randn(cfg.D, r, **f32) * inv
+    g2 = torch.Generator(device=device).manual_seed(seed0 + 0xDEC0DE + 31 * head)
+    f32 = dict(generator=g2, device=device, dtype=torch.float32)
+    k = scale * ((torch.randn(T, r, **f32) * inv) @ Vf.T + 0.1 * torch.randn(T, cfg.D, **f32))
+    v = torch.randn(T, cfg.D, **f32)
+    q = (torch.randn(T, cfg.G, r, **f32) * inv) @ Vf.T + 0.1 * torch.randn(T, cfg.G, cfg.D, **f32)
+    dt = cfg.torch_dtype
+    return k.to(dt), v.to(dt), q.to(dt)
 
 
 def gen_layers(cfg: Config, seed0: int, layers, device="cpu"):
