@@ -68,6 +68,8 @@ def main():
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="also run one plain device copy of this many MiB (reference for HBM byte counters)")
     ap.add_argument("--cpu-heads", type=int, default=0, help="heads in the oracle sample (0 = auto)")
+    ap.add_argument("--decode-steps", type=int, default=64,
+                    help="generated tokens to run through uncomp_decode_step after the timed prefill steps (0 = skip)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU only: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
@@ -90,6 +92,8 @@ def main():
     Kf, Vf, Qf = K.reshape(LB, H, N, D), V.reshape(LB, H, N, D), Q.reshape(LB, H * G, w, D)
 
     ws = binding.Context.workspace_bytes(LB * H, N, D, LB, H, G, w)
+    if args.decode_steps > 0:
+        ws = max(ws, binding.Context.decode_workspace_bytes(LB * H, G, cfg.cap))
     ctx = binding.Context(0, ws)
     ctx.set_overlap(not args.no_overlap)
     i32 = dict(dtype=torch.int32, device=dev)
@@ -155,6 +159,8 @@ def main():
             roofline = {"kernel": dominant, "bound": "alu", "achieved": None, "peak": None, "unit": "TFLOP/s",
                         "frac": None, "traffic": None}
 
+    decode = decode_leg(cfg, ctx, score, bud[0], outs, args) if args.decode_steps > 0 else None
+
     cpu = None
     if not args.no_cpu_baseline:
         cpu = cpu_baseline(cfg, K, V, Q, args)
@@ -169,10 +175,62 @@ def main():
                    "head_dim": D, "window": w, "pool": cfg.pool, "k_trunc": cfg.k_trunc,
                    "avg_budget": cfg.avg_budget, "mean_kept": round(kept, 1), "rho": round(kept / N, 5),
                    "head_tokens_per_s": round(value * L * H, 1)},
-        "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels,
+        "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels, "decode": decode,
         "gen_seconds": round(t_gen, 1),
     }
     print(json.dumps(out))
+
+
+def decode_leg(cfg, ctx, score, head_budget, outs, args):
+    """Not part of `value`: the tokens generated after the prefill.  Every KV head of every
+    layer takes one uncomp_decode_step per token (attention over its compacted cache, score
+    update, eviction), all heads in one launch.  Reports the kernel's time per generated
+    token and its HBM rate on the bytes it has to read (the cached K and V rows once)."""
+    import torch
+
+    from paper_2410_03090_amd import synth
+    dev = score.device
+    L, B, H, N, D, G, w = cfg.L, cfg.B, cfg.H, cfg.N, cfg.D, cfg.G, cfg.w
+    heads, T, cap = L * B * H, args.decode_steps, cfg.cap
+    Kc, Vc, idx, ln = (outs[0].view(heads, cap, D), outs[1].view(heads, cap, D), outs[2].view(heads, cap),
+                       outs[3].view(heads))
+    scales = synth.layer_scales(cfg, args.seed)
+    kn = torch.empty(T, heads, D, dtype=Kc.dtype, device=dev)
+    vn = torch.empty_like(kn)
+    qn = torch.empty(T, heads, G, D, dtype=Kc.dtype, device=dev)
+    for l in range(L):
+        for b in range(B):
+            for h in range(H):
+                u = (l * B + b) * H + h
+                kn[:, u], vn[:, u], qn[:, u] = synth.gen_decode_tokens(cfg, args.seed, l, b, h, T, device=dev,
+                                                                       scale=float(scales[l]))
+    budget = head_budget.reshape(heads).contiguous()
+    cum = ctx.decode_init(score.view(heads, N - w), idx, ln, N, w)
+    out = torch.empty(heads, G, D, dtype=torch.float32, device=dev)
+    ev = torch.empty(heads, dtype=torch.int32, device=dev)
+    pos = [torch.full((heads,), N + t, dtype=torch.int32, device=dev) for t in range(T)]
+    rows = float(ln.float().sum().item()) + heads            # entries read per step (cache is full: stays constant)
+    torch.cuda.synchronize()
+    ctx.profile(True)
+    t0 = time.perf_counter()
+    for t in range(T):
+        ctx.decode_step(qn[t], kn[t], vn[t], pos[t], budget, w, Kc, Vc, idx, cum, ln, out=out, evicted=ev)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    per = {}
+    for name, m in ctx.profile_read():
+        per.setdefault(name, []).append(m)
+    ctx.profile(False)
+    # per kernel: mean over the last three quarters of the steps (first-touch, clocks)
+    kern = {name: sum(v[len(v) // 4:]) / len(v[len(v) // 4:]) for name, v in per.items()}
+    avg = sum(kern.values())
+    e = 2 if cfg.dtype == "bf16" else 4
+    byt = rows * 2 * D * e
+    return {"steps": T, "kv_heads_per_step": heads, "cache_rows": int(rows), "kernel_us_per_token": round(avg * 1e3, 2),
+            "wall_us_per_token": round(wall / T * 1e6, 2), "algorithmic_bytes": int(byt),
+            "GBps": round(byt / avg / 1e6, 1), "hbm_frac": round(byt / avg / 1e6 / HBM_PEAK_GBS, 4),
+            "kernels_us": {k: round(v * 1e3, 2) for k, v in kern.items()},
+            "evicting_heads": int((ev >= 0).sum().item())}
 
 
 def cpu_baseline(cfg, K, V, Q, args):

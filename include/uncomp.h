@@ -218,9 +218,12 @@ uncomp_status uncomp_decode_init(uncomp_ctx* ctx, const float* score, const int3
  * Row order inside a head is therefore unspecified after the first eviction; idx tells which
  * position a row holds.  A malformed state in which the head is over budget but no entry is
  * old enough to leave appends while n < cap, else drops the token and reports -2.
- * Requires 1 <= w <= cap, 1 <= G <= 16, D == 128, G*(cap + 1) <= 36864, 16-byte aligned
- * q / k_new / v_new / K_c / V_c.  Needs no workspace.
+ * Requires 1 <= w <= cap, 1 <= G <= 16, D == 128, 16-byte aligned q / k_new / v_new / K_c /
+ * V_c.  bf16 caches need uncomp_decode_workspace_bytes(n_heads, G, cap) of workspace (partial
+ * results of the two kernels the step is split into); fp32 caches need none but are limited
+ * to G*(cap + 1) <= 36864.  The workspace is shared with the prefill calls of the context.
  */
+size_t uncomp_decode_workspace_bytes(int n_heads, int G, int cap);
 uncomp_status uncomp_decode_step(uncomp_ctx* ctx, const void* q, const void* k_new,
                                  const void* v_new, uncomp_dtype dtype, int n_heads, int G, int D,
                                  const int32_t* pos, const int32_t* budget, int w, int cap,

@@ -25,7 +25,7 @@ EXPORTS = (
     "uncomp_create", "uncomp_destroy", "uncomp_workspace_bytes", "uncomp_last_error",
     "uncomp_profile", "uncomp_profile_read", "uncomp_set_kernel_path", "uncomp_set_overlap", "uncomp_join",
     "uncomp_head_entropy", "uncomp_assign_budgets", "uncomp_window_score", "uncomp_select_gather",
-    "uncomp_decode_init", "uncomp_decode_step",
+    "uncomp_decode_init", "uncomp_decode_step", "uncomp_decode_workspace_bytes",
 )
 
 _lib = None
@@ -83,6 +83,8 @@ def load_library() -> ctypes.CDLL:
     lib.uncomp_decode_step.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, vp, vp, i32, i32,
                                        vp, vp, vp, vp, vp, vp, vp, vp]
     lib.uncomp_decode_step.restype = i32
+    lib.uncomp_decode_workspace_bytes.argtypes = [i32, i32, i32]
+    lib.uncomp_decode_workspace_bytes.restype = c.c_size_t
     _lib = lib
     return lib
 
@@ -118,6 +120,10 @@ class Context:
     @staticmethod
     def workspace_bytes(n_mat: int, N: int, D: int, B: int, H: int, G: int, w: int) -> int:
         return int(load_library().uncomp_workspace_bytes(n_mat, N, D, B, H, G, w))
+
+    @staticmethod
+    def decode_workspace_bytes(n_heads: int, G: int, cap: int) -> int:
+        return int(load_library().uncomp_decode_workspace_bytes(n_heads, G, cap))
 
     def close(self):
         if getattr(self, "handle", None) is not None and self.handle:

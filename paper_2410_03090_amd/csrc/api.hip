@@ -270,6 +270,11 @@ uncomp_status uncomp_select_gather(uncomp_ctx* ctx, const float* score, const in
     return UNCOMP_OK;
 }
 
+size_t uncomp_decode_workspace_bytes(int n_heads, int G, int cap) {
+    if (n_heads <= 0 || G <= 0 || cap <= 0) return 0;
+    return plan_decode(n_heads, G, cap).bytes;
+}
+
 uncomp_status uncomp_decode_init(uncomp_ctx* ctx, const float* score, const int32_t* idx, const int32_t* len,
                                  int n_heads, int N, int w, int cap, float* cum_out, void* stream) {
     if (ctx == nullptr) return UNCOMP_ERR_INVALID_ARG;
@@ -296,20 +301,25 @@ uncomp_status uncomp_decode_step(uncomp_ctx* ctx, const void* q, const void* k_n
     if (D != kD) return fail(ctx, UNCOMP_ERR_UNSUPPORTED, "decode_step: D must be 128");
     if (G < 1 || G > 16) return fail(ctx, UNCOMP_ERR_UNSUPPORTED, "decode_step: need 1 <= G <= 16");
     if (w < 1 || w > cap) return fail(ctx, UNCOMP_ERR_INVALID_ARG, "decode_step: need 1 <= w <= cap");
-    if ((int64_t)G * ((int64_t)cap + 1) > 36864)
-        return fail(ctx, UNCOMP_ERR_UNSUPPORTED, "decode_step: G*(cap+1) must be <= 36864");
     if (!aligned16(q) || !aligned16(k_new) || !aligned16(v_new) || !aligned16(K_c) || !aligned16(V_c))
         return fail(ctx, UNCOMP_ERR_INVALID_ARG, "decode_step: 16-byte aligned pointers required");
-    float* out_p = out;
-    if (out_p == nullptr) {
-        // the kernel always forms the output; without a destination it lands in the workspace
-        if ((size_t)n_heads * G * kD * sizeof(float) > ctx->ws_bytes)
-            return fail(ctx, UNCOMP_ERR_WORKSPACE, "decode_step: out == NULL needs %zu workspace bytes",
-                        (size_t)n_heads * G * kD * sizeof(float));
-        out_p = reinterpret_cast<float*>(ctx->ws);
-    }
-    hipError_t e = launch_decode_step(q, k_new, v_new, dtype, n_heads, G, pos, budget, w, cap, K_c, V_c, idx, cum,
-                                      len, out_p, evicted, Env{static_cast<hipStream_t>(stream), &ctx->prof, ctx->force_alu});
+    if ((int64_t)n_heads * (((int64_t)cap + 128) / 128) > 0x7fffffffLL)
+        return fail(ctx, UNCOMP_ERR_UNSUPPORTED, "decode_step: problem too large");
+    const DecodePlan p = plan_decode(n_heads, G, cap);
+    const bool wave_path = dtype == UNCOMP_BF16 && !ctx->force_alu;
+    if (!wave_path && (int64_t)G * ((int64_t)cap + 1) > 36864)
+        return fail(ctx, UNCOMP_ERR_UNSUPPORTED, "decode_step: fp32 caches need G*(cap+1) <= 36864");
+    const size_t need = wave_path ? p.bytes : (out == nullptr ? p.p_off : 0);
+    if (need > ctx->ws_bytes)
+        return fail(ctx, UNCOMP_ERR_WORKSPACE, "decode_step: needs %zu workspace bytes, context has %zu", need,
+                    ctx->ws_bytes);
+    // the kernels always form the output; without a destination it lands in the workspace
+    float* out_p = out != nullptr ? out : reinterpret_cast<float*>(ctx->ws + p.out_off);
+    const Env env{static_cast<hipStream_t>(stream), &ctx->prof, ctx->force_alu};
+    hipError_t e = wave_path ? launch_decode_wave(q, k_new, v_new, n_heads, G, pos, budget, w, cap, K_c, V_c, idx, cum,
+                                                  len, out_p, evicted, p, ctx->ws, env)
+                             : launch_decode_step(q, k_new, v_new, dtype, n_heads, G, pos, budget, w, cap, K_c, V_c,
+                                                  idx, cum, len, out_p, evicted, env);
     if (e != hipSuccess) return hip_fail(ctx, e, "decode_step: launch");
     return UNCOMP_OK;
 }

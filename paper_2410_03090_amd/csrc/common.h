@@ -108,6 +108,23 @@ hipError_t launch_select_gather(const float* score, const int32_t* budget, const
                                 const void* V, uncomp_dtype dt, int B, int H, int N, int w,
                                 const int64_t ks[3], int cap, void* K_out, void* V_out,
                                 int32_t* idx_out, int32_t* len_out, const Env& env);
+// Workspace of the bf16 decode path (two kernels per step).
+struct DecodePlan {
+    int GT;              // query heads per KV head rounded up to 4, 8 or 16
+    int wave_rows;       // rows of one head that one wave owns (128 or 256)
+    int s_rows;          // rows per head in the probability table (cap + 1 rounded up to whole waves)
+    int np_max;          // waves (128-row parts) per head
+    size_t out_off;      // float [n_heads][G][D]: attention output when the caller wants none
+    size_t p_off;        // float [n_heads][s_rows][GT]
+    size_t ml_off;       // float [n_heads][np_max][GT][2]
+    size_t acc_off;      // float [n_heads][np_max][GT][D]
+    size_t bytes;
+};
+DecodePlan plan_decode(int n_heads, int G, int cap);
+hipError_t launch_decode_wave(const void* q, const void* k_new, const void* v_new, int n_heads, int G,
+                              const int32_t* pos, const int32_t* budget, int w, int cap, void* Kc, void* Vc,
+                              int32_t* idx, float* cum, int32_t* len, float* out, int32_t* evicted,
+                              const DecodePlan& p, char* ws, const Env& env);
 hipError_t launch_decode_init(const float* score, const int32_t* idx, const int32_t* len, int n_heads,
                               int N, int w, int cap, float* cum, const Env& env);
 size_t decode_step_lds_bytes(int G, int cap);

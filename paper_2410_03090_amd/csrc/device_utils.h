@@ -32,6 +32,24 @@ __device__ __forceinline__ void load8(const float* p, float out[8]) {
     out[4] = b.x; out[5] = b.y; out[6] = b.z; out[7] = b.w;
 }
 
+// Operand / accumulator vectors of v_mfma_f32_16x16x32_bf16.  Lane l holds: A row l%16 (or
+// B column l%16), k = 8*(l/16) .. +8; accumulator column l%16, rows 4*(l/16) .. +4.
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+
+// Lane layout: four rows of 16 lanes.  For four registers X, Y, Z, W returns, in lane row
+// 0 / 1 / 2 / 3, the sum over all four rows of X / Z / Y / W (per lane%16).
+// v_permlane32_swap(a,b) -> ([a.lo32, b.lo32], [a.hi32, b.hi32]);
+// v_permlane16_swap(a,b) -> ([a.r0, b.r0, a.r2, b.r2], [a.r1, b.r1, a.r3, b.r3]).
+__device__ __forceinline__ float reduce4_over_rows(float x, float y, float z, float w) {
+    auto s1 = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(y), false, false);
+    auto s2 = __builtin_amdgcn_permlane32_swap(__float_as_uint(z), __float_as_uint(w), false, false);
+    const float t1 = __uint_as_float(s1[0]) + __uint_as_float(s1[1]);
+    const float t2 = __uint_as_float(s2[0]) + __uint_as_float(s2[1]);
+    auto s3 = __builtin_amdgcn_permlane16_swap(__float_as_uint(t1), __float_as_uint(t2), false, false);
+    return __uint_as_float(s3[0]) + __uint_as_float(s3[1]);
+}
+
 __device__ __forceinline__ float wave_max(float v) {
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));

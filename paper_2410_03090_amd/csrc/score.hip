@@ -101,24 +101,8 @@ __global__ __launch_bounds__(512) void score_stats_alu_kernel(
 // ---------------------------------------------------------------------------------------
 namespace {
 
-typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
-typedef float f32x4_t __attribute__((ext_vector_type(4)));
-
 constexpr int kTile = 64;                 // tokens per key tile
 constexpr int kRowBytes = 2 * kD + 16;    // padded LDS row of one query
-
-// Lane layout: four rows of 16 lanes.  For four registers X, Y, Z, W returns, in lane row
-// 0 / 1 / 2 / 3, the sum over all four rows of X / Z / Y / W (per lane%16).
-// v_permlane32_swap(a,b) -> ([a.lo32, b.lo32], [a.hi32, b.hi32]);
-// v_permlane16_swap(a,b) -> ([a.r0, b.r0, a.r2, b.r2], [a.r1, b.r1, a.r3, b.r3]).
-__device__ __forceinline__ float reduce4_over_rows(float x, float y, float z, float w) {
-    auto s1 = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(y), false, false);
-    auto s2 = __builtin_amdgcn_permlane32_swap(__float_as_uint(z), __float_as_uint(w), false, false);
-    const float t1 = __uint_as_float(s1[0]) + __uint_as_float(s1[1]);
-    const float t2 = __uint_as_float(s2[0]) + __uint_as_float(s2[1]);
-    auto s3 = __builtin_amdgcn_permlane16_swap(__float_as_uint(t1), __float_as_uint(t2), false, false);
-    return __uint_as_float(s3[0]) + __uint_as_float(s3[1]);
-}
 
 }  // namespace
 

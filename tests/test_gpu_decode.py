@@ -93,29 +93,35 @@ def _random_state(n_heads, cap, lens, pos0, dtype, seed, w):
     return State(Kc.to(DEV), Vc.to(DEV), idx.to(DEV), cum.to(DEV), ln.to(DEV))
 
 
-@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
+@pytest.mark.parametrize("dtype,plain_alu", [(torch.bfloat16, False), (torch.bfloat16, True), (torch.float32, False)])
 @pytest.mark.parametrize("G", [1, 4, 7, 16])
-def test_decode_step_matches_oracle_every_step(ctx, dtype, G):
-    cap, w, steps = 96, 8, 28
-    lens = [0, 5, 40, 95, 96, 64]
-    budgets = [96, 3, 40, 96, 200, 50]          # below w, equal to len, above cap, below len
-    n_heads = len(lens)
-    pos0 = [500 + 10 * h for h in range(n_heads)]
-    st = _random_state(n_heads, cap, lens, pos0, dtype, seed=100 + G, w=w)
-    budget = torch.tensor(budgets, dtype=torch.int32)
-    g = torch.Generator().manual_seed(7 * G + (1 if dtype == torch.float32 else 0))
-    swaps = 0
-    for t in range(steps):
-        q = (torch.randn(n_heads, G, D, generator=g) * 2.5).to(dtype)
-        kn = torch.randn(n_heads, D, generator=g).to(dtype)
-        vn = torch.randn(n_heads, D, generator=g).to(dtype)
-        pos = torch.tensor([p + t for p in pos0], dtype=torch.int32)
-        before = st.host()
-        out, ev = ctx.decode_step(q.to(DEV), kn.to(DEV), vn.to(DEV), pos.to(DEV), budget.to(DEV), w,
-                                  st.Kc, st.Vc, st.idx, st.cum, st.ln)
-        torch.cuda.synchronize()
-        swaps += _check_step(before, st.host(), out.cpu().numpy(), ev.cpu().numpy(), q, kn, vn, pos.numpy(),
-                             budget.numpy(), w, cap)
+def test_decode_step_matches_oracle_every_step(ctx, dtype, plain_alu, G):
+    """bf16 through the two-kernel MFMA path and through the one-kernel path, fp32 through the latter.
+    cap = 300 spans three 128-row wave parts with a ragged last one."""
+    cap, w, steps = 300, 8, 28
+    lens = [0, 5, 127, 128, 299, 300, 200]
+    budgets = [300, 3, 127, 300, 300, 500, 150]   # below w, equal to len, above cap, below len
+    ctx.set_kernel_path(plain_alu)
+    try:
+        n_heads = len(lens)
+        pos0 = [500 + 10 * h for h in range(n_heads)]
+        st = _random_state(n_heads, cap, lens, pos0, dtype, seed=100 + G, w=w)
+        budget = torch.tensor(budgets, dtype=torch.int32)
+        g = torch.Generator().manual_seed(7 * G + (1 if dtype == torch.float32 else 0))
+        swaps = 0
+        for t in range(steps):
+            q = (torch.randn(n_heads, G, D, generator=g) * 2.5).to(dtype)
+            kn = torch.randn(n_heads, D, generator=g).to(dtype)
+            vn = torch.randn(n_heads, D, generator=g).to(dtype)
+            pos = torch.tensor([p + t for p in pos0], dtype=torch.int32)
+            before = st.host()
+            out, ev = ctx.decode_step(q.to(DEV), kn.to(DEV), vn.to(DEV), pos.to(DEV), budget.to(DEV), w,
+                                      st.Kc, st.Vc, st.idx, st.cum, st.ln)
+            torch.cuda.synchronize()
+            swaps += _check_step(before, st.host(), out.cpu().numpy(), ev.cpu().numpy(), q, kn, vn, pos.numpy(),
+                                 budget.numpy(), w, cap)
+    finally:
+        ctx.set_kernel_path(False)
     assert swaps <= 2
     # occupancy: never above max(start, clamp(budget)); heads with room grew by one per step
     ln = st.ln.cpu().numpy()
@@ -242,10 +248,17 @@ def test_decode_argument_errors(ctx):
                                      pos.data_ptr(), bud.data_ptr(), w, cap, st.Kc.data_ptr(), st.Vc.data_ptr(),
                                      st.idx.data_ptr(), st.cum.data_ptr(), st.ln.data_ptr(), None, None, None)
     assert st_code == binding.ERR_UNSUPPORTED                                                   # D != 128
-    st_code = lib.uncomp_decode_step(ctx.handle, q.data_ptr(), kn.data_ptr(), kn.data_ptr(), binding.BF16, n_heads, G, D,
+    st_code = lib.uncomp_decode_step(ctx.handle, q.data_ptr(), kn.data_ptr(), kn.data_ptr(), binding.F32, n_heads, G, D,
                                      pos.data_ptr(), bud.data_ptr(), w, 20000, st.Kc.data_ptr(), st.Vc.data_ptr(),
                                      st.idx.data_ptr(), st.cum.data_ptr(), st.ln.data_ptr(), None, None, None)
-    assert st_code == binding.ERR_UNSUPPORTED                                                   # probability table too large
+    assert st_code == binding.ERR_UNSUPPORTED                                 # fp32: probability table too large for LDS
+    small = binding.Context(0, 1 << 20)
+    st_code = lib.uncomp_decode_step(small.handle, q.data_ptr(), kn.data_ptr(), kn.data_ptr(), binding.BF16, 4096, G, D,
+                                     pos.data_ptr(), bud.data_ptr(), w, 4096, st.Kc.data_ptr(), st.Vc.data_ptr(),
+                                     st.idx.data_ptr(), st.cum.data_ptr(), st.ln.data_ptr(), None, None, None)
+    assert st_code == binding.ERR_WORKSPACE                                   # bf16: partial results do not fit
+    assert binding.Context.decode_workspace_bytes(4096, G, 4096) > (1 << 20)
+    small.close()
     st_code = lib.uncomp_decode_step(ctx.handle, None, kn.data_ptr(), kn.data_ptr(), binding.BF16, n_heads, G, D,
                                      pos.data_ptr(), bud.data_ptr(), w, cap, st.Kc.data_ptr(), st.Vc.data_ptr(),
                                      st.idx.data_ptr(), st.cum.data_ptr(), st.ln.data_ptr(), None, None, None)
@@ -277,6 +290,36 @@ def test_decode_without_output_buffers(ctx):
     torch.cuda.synchronize()
     for a, b in zip(sa.host(), sb.host()):
         assert np.array_equal(raw_bits(a) if isinstance(a, torch.Tensor) else a, raw_bits(b) if isinstance(b, torch.Tensor) else b)
+
+
+def test_decode_many_heads(ctx):
+    """1024 heads with 8 query heads each: enough waves for the 256-rows-per-wave variant (two parts
+    per head, the second ragged).  Sampled heads against the oracle."""
+    n_heads, G, cap, w = 1024, 8, 300, 8
+    g = torch.Generator(device=DEV).manual_seed(21)
+    Kc = torch.randn(n_heads, cap, D, generator=g, device=DEV).to(torch.bfloat16)
+    Vc = torch.randn(n_heads, cap, D, generator=g, device=DEV).to(torch.bfloat16)
+    ln = torch.randint(0, cap + 1, (n_heads,), generator=g, device=DEV).to(torch.int32)
+    ln[:4] = torch.tensor([0, 255, 256, 300], dtype=torch.int32, device=DEV)
+    budget = torch.randint(w, cap + 40, (n_heads,), generator=g, device=DEV).to(torch.int32)
+    idx = torch.argsort(torch.rand(n_heads, 1000, generator=g, device=DEV), dim=1)[:, :cap].to(torch.int32).contiguous()
+    cum = torch.rand(n_heads, cap, generator=g, device=DEV) * 2
+    st = State(Kc, Vc, idx, cum, ln)
+    sample = [0, 1, 2, 3, 500, 1023]
+    for t in range(3):
+        q = (torch.randn(n_heads, G, D, generator=g, device=DEV) * 2).to(torch.bfloat16)
+        kn = torch.randn(n_heads, D, generator=g, device=DEV).to(torch.bfloat16)
+        vn = torch.randn(n_heads, D, generator=g, device=DEV).to(torch.bfloat16)
+        pos = torch.full((n_heads,), 1000 + t, dtype=torch.int32, device=DEV)
+        before = st.host()
+        out, ev = ctx.decode_step(q, kn, vn, pos, budget, w, st.Kc, st.Vc, st.idx, st.cum, st.ln)
+        torch.cuda.synchronize()
+        after = st.host()
+        _check_step(before, after, out.cpu().numpy(), ev.cpu().numpy(), q.cpu(), kn.cpu(), vn.cpu(), pos.cpu().numpy(),
+                    budget.cpu().numpy(), w, cap, heads=sample)
+        b = np.clip(budget.cpu().numpy(), w, cap)
+        assert np.all(after[4] == np.where(before[4] + 1 > b, before[4], before[4] + 1))
+        assert np.isfinite(out.cpu().numpy()).all() and np.isfinite(after[3]).all()
 
 
 def test_decode_full_size_llama3_8b_128k(ctx):
