@@ -176,7 +176,9 @@ uncomp_status uncomp_head_entropy(uncomp_ctx* ctx, const void* X, uncomp_dtype d
         env.s = ctx->side;
         ctx->side_pending = true;
     }
-    e = launch_jacobi_entropy(n_mat, N, k_trunc, flags, p, ws, entropy_out, eig_out, env);
+    // the plain-ALU switch also selects the fp32 Jacobi eigen stage (an independent cross-check)
+    e = ctx->force_alu ? launch_jacobi_entropy(n_mat, N, k_trunc, flags, p, ws, entropy_out, eig_out, env)
+                       : launch_tridiag_entropy(n_mat, N, k_trunc, flags, p, ws, entropy_out, eig_out, env);
     if (e != hipSuccess) return hip_fail(ctx, e, "head_entropy: eigen launch");
     return UNCOMP_OK;
 }

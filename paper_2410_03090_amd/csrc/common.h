@@ -97,6 +97,9 @@ hipError_t launch_gram(const void* X, uncomp_dtype dt, int n_mat, int N, int64_t
 hipError_t launch_jacobi_entropy(int n_mat, int N, int k_trunc, unsigned flags,
                                  const EntropyPlan& p, char* ws, float* entropy_out,
                                  float* eig_out, const Env& env);
+hipError_t launch_tridiag_entropy(int n_mat, int N, int k_trunc, unsigned flags,
+                                  const EntropyPlan& p, char* ws, float* entropy_out,
+                                  float* eig_out, const Env& env);
 hipError_t launch_budgets(const float* entropy, int L, int B, int H, int M, int n_max, int step,
                           int N, int w, float eps, int delta_n, unsigned flags,
                           int32_t* head_budget, int32_t* head_group, int32_t* layer_group,

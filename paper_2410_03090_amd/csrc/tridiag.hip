@@ -1,0 +1,318 @@
+// Eigen stage of the truncated matrix entropy (Lemma 2: entropy from the eigenvalues of
+// the covariance; Sec. 3.2 Eq. 5: only the k largest enter; proof of Lemma 4: unit trace),
+// by Householder tridiagonalisation and Sturm-sequence multisection, all in fp64.
+//
+// One workgroup of 256 threads per matrix:
+//   1. add the Gram partials of the matrix in fp64, subtract the mean term s s^T / N
+//      (Eq. 1; the common factor 1/(N-1) drops out under the unit-trace scaling) and divide
+//      by the trace.  The matrix lives in registers: thread (c, hf) holds rows 64*hf .. +64
+//      of column c as 64 doubles.
+//   2. 126 Householder reflections H = I - beta v v^T bring it to tridiagonal form
+//      (A <- A - v w^T - w v^T with p = beta A v, w = p - (beta/2)(v^T p) v).  Per reflection:
+//      the pivot row was left in LDS by the previous update, every wave forms the norm of its
+//      tail on its own (identical bits in all waves, so the whole workgroup takes the same
+//      branch), a matrix-vector product with v read from LDS at wave-uniform addresses, one
+//      exchange of the two row halves, every wave forms v^T A v on its own, and the rank-2
+//      update; three workgroup barriers.  Rows that are already done are skipped by uniform
+//      branches; no register is ever indexed dynamically.
+//   3. The eigenvalues of the tridiagonal matrix (d, e) are found by counting sign changes of
+//      the characteristic-polynomial recurrence p_i = (d_i - x) p_{i-1} - e_{i-1}^2 p_{i-2}
+//      (= number of eigenvalues below x; no division, rescaled against underflow): every
+//      wanted eigenvalue owns a group of L lanes that cut its bracket into L+1 pieces per
+//      round (ballot + count-trailing-zeros picks the piece).  Brackets start at
+//      [0, 1 + 2^-10]: the matrix has unit trace and is positive semi-definite up to rounding,
+//      and an eigenvalue that rounding pushed below zero is reported as zero, which is what
+//      the definition asks for.  Only the k largest are computed unless the caller wants the
+//      whole spectrum.
+//   4. truncated entropy in fp64.
+#include "common.h"
+#include "device_utils.h"
+
+namespace uncomp {
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kHalf = kD / 2;
+
+struct TriSmem {
+    double s[kD];            // column sums of X (for the mean correction)
+    double red[8];
+    double xbuf[kD];         // pivot row i, entries at columns <= i zeroed
+    double ybuf[kD];         // row i + 1
+    double pbuf[2][kD];      // the two row halves of A v
+    double2 vw[kD];          // (v_r, w_r)
+    double2 de[kD];          // (d_i, e_{i-1}^2), e_{-1} = 0
+    double lam[kD];          // eigenvalues, descending
+};
+
+template <int CTRL>
+__device__ __forceinline__ double dpp_move(double v) {
+    const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(v), CTRL, 0xF, 0xF, false);
+    const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(v), CTRL, 0xF, 0xF, false);
+    return __hiloint2double(hi, lo);
+}
+
+// Sum over the 64 lanes, delivered to every lane with identical bits: rotations inside the
+// rows of 16 lanes (DPP row_ror 8, 4, 2, 1), then the four rows with
+// v_permlane32_swap(a,b) -> ([a.lo32, b.lo32], [a.hi32, b.hi32]) and
+// v_permlane16_swap(a,b) -> ([a.r0, b.r0, a.r2, b.r2], [a.r1, b.r1, a.r3, b.r3]).
+__device__ __forceinline__ double wave_allsum(double v) {
+    v += dpp_move<0x128>(v);
+    v += dpp_move<0x124>(v);
+    v += dpp_move<0x122>(v);
+    v += dpp_move<0x121>(v);
+    {
+        const unsigned lo = (unsigned)__double2loint(v), hi = (unsigned)__double2hiint(v);
+        auto a = __builtin_amdgcn_permlane32_swap(lo, lo, false, false);
+        auto b = __builtin_amdgcn_permlane32_swap(hi, hi, false, false);
+        v = __hiloint2double((int)b[0], (int)a[0]) + __hiloint2double((int)b[1], (int)a[1]);
+    }
+    {
+        const unsigned lo = (unsigned)__double2loint(v), hi = (unsigned)__double2hiint(v);
+        auto a = __builtin_amdgcn_permlane16_swap(lo, lo, false, false);
+        auto b = __builtin_amdgcn_permlane16_swap(hi, hi, false, false);
+        v = __hiloint2double((int)b[0], (int)a[0]) + __hiloint2double((int)b[1], (int)a[1]);
+    }
+    return v;
+}
+
+__device__ __forceinline__ double block_sum(double v, double* red, int tid) {
+    v = wave_allsum(v);
+    __syncthreads();
+    if ((tid & 63) == 0) red[tid >> 6] = v;
+    __syncthreads();
+    return red[0] + red[1] + red[2] + red[3];
+}
+
+// Number of eigenvalues of the tridiagonal matrix below x: sign changes along
+// 1, p_0, p_1, ..., p_{n-1} (a zero takes the sign '+', which gives the same total as the
+// textbook rule because the next term then has the opposite sign of the previous one).
+// The (d_i, e_{i-1}^2) pairs come from LDS eight at a time, the next eight requested before
+// the current eight are used.
+__device__ __forceinline__ int sturm_count(const double2* de, double x) {
+    double pp = 0.0, p = 1.0;                      // p_{-2}, p_{-1}
+    int cnt = 0;
+    double2 cur[8], nxt[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) cur[u] = de[u];
+#pragma clang loop unroll(disable)
+    for (int base = 0; base < kD; base += 8) {
+        const int nb = base + 8 < kD ? base + 8 : base;          // the last prefetch re-reads its own chunk
+#pragma unroll
+        for (int u = 0; u < 8; ++u) nxt[u] = de[nb + u];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const double pn = fma(cur[u].x - x, p, -(cur[u].y * pp));
+            cnt += (int)((unsigned)(__double2hiint(pn) ^ __double2hiint(p)) >> 31);
+            pp = p;
+            p = pn;
+        }
+        // |p| shrinks by at most ~2^-35 per step and grows by at most 1.25: keep it normal
+        const double sc = fabs(p) < 0x1p-300 ? 0x1p300 : 1.0;
+        p *= sc;
+        pp *= sc;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) cur[u] = nxt[u];
+    }
+    return cnt;
+}
+
+}  // namespace
+
+__global__ __launch_bounds__(kThreads) void tridiag_entropy_kernel(
+    const float* __restrict__ gram_part, const float* __restrict__ sum_part, int n_chunks, int N,
+    int k_trunc, unsigned flags, float* __restrict__ entropy_out, float* __restrict__ eig_out) {
+    __shared__ TriSmem sm;
+    const int m = blockIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int c = tid & (kD - 1);
+    const int hf = __builtin_amdgcn_readfirstlane(tid >> 7);     // wave-uniform: which 64 rows
+    const float* Gm = gram_part + (int64_t)m * n_chunks * (kD * kD);
+    const float* Sm = sum_part + (int64_t)m * n_chunks * kD;
+
+    // ---- 1. reduce partials, centre, unit trace ------------------------------------------
+    if (tid < kD) {
+        double acc = 0.0;
+        for (int ch = 0; ch < n_chunks; ++ch) acc += (double)Sm[ch * kD + tid];
+        sm.s[tid] = acc;
+    }
+    __syncthreads();
+    const bool center = (flags & UNCOMP_CENTER) != 0;
+    const double inv_n = 1.0 / (double)N;
+    double tr_c = 0.0, tr_u = 0.0;
+    if (tid < kD) {
+        double acc = 0.0;
+        for (int ch = 0; ch < n_chunks; ++ch) acc += (double)Gm[(int64_t)ch * (kD * kD) + tid * (kD + 1)];
+        tr_u = acc;
+        tr_c = center ? acc - sm.s[tid] * sm.s[tid] * inv_n : acc;
+    }
+    const double trace = block_sum(tr_c, sm.red, tid);
+    const double trace_u = block_sum(tr_u, sm.red, tid);
+    // Zero spread: a single token, or a centred trace so far below the second moment that
+    // the fp32 partial sums cannot tell it from zero.
+    const bool degenerate = !(trace > 0.0) || (center && (N < 2 || trace < trace_u * 0x1p-20));
+    if (degenerate) {
+        if (tid == 0) entropy_out[m] = 0.f;
+        if (eig_out != nullptr && tid < kD) eig_out[(int64_t)m * kD + tid] = 0.f;
+        return;
+    }
+    double a[kHalf];                                             // a[k] = A[64 hf + k][c]
+#pragma unroll
+    for (int k = 0; k < kHalf; ++k) a[k] = 0.0;
+    for (int ch = 0; ch < n_chunks; ++ch) {
+        const float* g = Gm + (int64_t)ch * (kD * kD) + (hf * kHalf) * kD + c;
+#pragma unroll
+        for (int k = 0; k < kHalf; ++k) a[k] += (double)g[k * kD];
+    }
+    {
+        const double inv_tr = 1.0 / trace;
+        const double sc = center ? sm.s[c] * inv_n : 0.0;
+#pragma unroll
+        for (int k = 0; k < kHalf; ++k) a[k] = (a[k] - sm.s[hf * kHalf + k] * sc) * inv_tr;
+    }
+
+    // ---- 2. Householder tridiagonalisation ---------------------------------------------------
+    // Copies row `row` of the matrix (held by the 128 threads of one half, in a register whose
+    // number depends on `row`) to LDS: two levels of uniform branches reach the register
+    // without indexing it.  Entries at columns <= cmin are written as zero; the diagonal
+    // entry goes to de[row].x when asked for.
+    auto publish = [&](double* buf, int row, int cmin, bool with_diag) {
+        const int kk = row - hf * kHalf;
+        if (kk < 0 || kk >= kHalf) return;
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            if ((kk >> 4) == b) {
+#pragma unroll
+                for (int u = 0; u < 16; ++u) {
+                    if ((kk & 15) == u) {
+                        buf[c] = c > cmin ? a[16 * b + u] : 0.0;
+                        if (with_diag && c == row) sm.de[row].x = a[16 * b + u];
+                    }
+                }
+            }
+        }
+    };
+    publish(sm.xbuf, 0, 0, true);
+    publish(sm.ybuf, 1, -1, false);
+    for (int i = 0; i < kD - 2; ++i) {
+        __syncthreads();                                         // xbuf = row i (masked), ybuf = row i + 1
+        const double x1 = sm.xbuf[i + 1];
+        const double xa = lane > i + 1 ? sm.xbuf[lane] : 0.0;
+        const double xb = lane + 64 > i + 1 ? sm.xbuf[lane + 64] : 0.0;
+        const double tail = wave_allsum(xa * xa + xb * xb);      // sum_{r > i+1} x_r^2, same bits in every wave
+        if (tail == 0.0) {
+            // the column is already in tridiagonal form: nothing to reflect
+            if (tid == 0) sm.de[i + 1].y = x1 * x1;
+            __syncthreads();                                     // both rows read by all before they are replaced
+        } else {
+            const double sigma = tail + x1 * x1;
+            const double nrm = sqrt(sigma);
+            const double alpha = x1 >= 0.0 ? -nrm : nrm;
+            const double beta = 1.0 / (sigma - alpha * x1);
+            if (tid == 0) sm.de[i + 1].y = sigma;                // e_i^2 = alpha^2
+            // v = x - alpha e_{i+1}.  This thread's part of (A x)_c over the rows of its half; blocks
+            // of 16 rows that are done (x = 0 there) are skipped.  A e_{i+1} is row i + 1.
+            double p0 = 0.0, p1 = 0.0, p2 = 0.0, p3 = 0.0;
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                if (hf * kHalf + 16 * b + 15 > i) {
+#pragma unroll
+                    for (int u = 0; u < 16; u += 4) {
+                        const double2 xv0 = *reinterpret_cast<const double2*>(&sm.xbuf[hf * kHalf + 16 * b + u]);
+                        const double2 xv1 = *reinterpret_cast<const double2*>(&sm.xbuf[hf * kHalf + 16 * b + u + 2]);
+                        p0 = fma(a[16 * b + u], xv0.x, p0);
+                        p1 = fma(a[16 * b + u + 1], xv0.y, p1);
+                        p2 = fma(a[16 * b + u + 2], xv1.x, p2);
+                        p3 = fma(a[16 * b + u + 3], xv1.y, p3);
+                    }
+                }
+            }
+            sm.pbuf[hf][c] = (p0 + p1) + (p2 + p3);
+            __syncthreads();
+            auto v_of = [&](int r) { return sm.xbuf[r] - (r == i + 1 ? alpha : 0.0); };
+            auto Av_of = [&](int r) { return (sm.pbuf[0][r] + sm.pbuf[1][r]) - alpha * sm.ybuf[r]; };
+            const double vAv = wave_allsum(v_of(lane) * Av_of(lane) + v_of(lane + 64) * Av_of(lane + 64));
+            const double K = 0.5 * beta * beta * vAv;
+            const double vc = v_of(c);
+            const double wc = c > i ? beta * Av_of(c) - K * vc : 0.0;
+            if (hf == 0) sm.vw[c] = make_double2(vc, wc);
+            __syncthreads();
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                if (hf * kHalf + 16 * b + 15 > i) {
+#pragma unroll
+                    for (int u = 0; u < 16; ++u) {
+                        const double2 t = sm.vw[hf * kHalf + 16 * b + u];
+                        a[16 * b + u] = fma(-t.x, wc, fma(-t.y, vc, a[16 * b + u]));
+                    }
+                }
+            }
+        }
+        publish(sm.xbuf, i + 1, i + 1, true);
+        if (i + 2 < kD) publish(sm.ybuf, i + 2, -1, false);
+    }
+    __syncthreads();                                             // xbuf = row 126 (masked)
+    if (tid == 0) {
+        sm.de[kD - 1].y = sm.xbuf[kD - 1] * sm.xbuf[kD - 1];
+        sm.de[0].y = 0.0;
+    }
+    if (tid == kThreads - 1) sm.de[kD - 1].x = a[kHalf - 1];
+    if (tid < kD) sm.lam[tid] = 0.0;
+    __syncthreads();
+
+    // ---- 3. eigenvalues by multisection on the Sturm count ------------------------------------
+    const int k = k_trunc < kD ? k_trunc : kD;
+    const int n_need = eig_out != nullptr ? kD : k;
+    const int L = n_need <= 16 ? 16 : (n_need <= 32 ? 8 : (n_need <= 64 ? 4 : 2));   // lanes per eigenvalue
+    const int rounds = L == 16 ? 8 : (L == 8 ? 10 : (L == 4 ? 14 : 20));           // (L+1)^rounds >= 2^31
+    {
+        const int q = tid / L, s = tid % L;                      // eigenvalue q (0 = largest), piece s
+        const int j = kD - 1 - q;                                // its index in ascending order
+        const double inv = 1.0 / (double)(L + 1);
+        double lo = 0.0, hi = 1.0 + 0x1p-10;
+        for (int it = 0; it < rounds; ++it) {
+            const double step = (hi - lo) * inv;
+            const int cnt = sturm_count(sm.de, lo + step * (double)(s + 1));
+            const unsigned long long mask = __ballot(cnt > j);
+            const unsigned bits = (unsigned)(mask >> (lane - s)) & ((1u << L) - 1u);
+            const int piece = bits ? __builtin_ctz(bits) : L;    // first cut with more than j eigenvalues below it
+            const double nlo = lo + step * (double)piece;
+            hi = piece == L ? hi : lo + step * (double)(piece + 1);
+            lo = nlo;
+        }
+        if (s == 0 && q < n_need) {
+            const double v = 0.5 * (lo + hi);
+            sm.lam[q] = v > 0.0 ? v : 0.0;
+        }
+    }
+    __syncthreads();
+
+    // ---- 4. entropy --------------------------------------------------------------------------
+    const double mine = tid < kD ? sm.lam[tid] : 0.0;
+    const double total = block_sum(tid < kD ? sm.de[tid].x : 0.0, sm.red, tid);   // the trace: sum of all eigenvalues
+    const double topk = block_sum(tid < k ? mine : 0.0, sm.red, tid);
+    const double denom = (flags & UNCOMP_TRUNC_RENORM) ? topk : total;
+    double term = 0.0;
+    if (tid < k && mine > 0.0 && denom > 0.0) {
+        const double sgm = mine / denom;
+        term = -sgm * log(sgm);
+    }
+    const double H = block_sum(term, sm.red, tid);
+    if (tid == 0) entropy_out[m] = (float)H;
+    if (eig_out != nullptr && tid < kD)
+        eig_out[(int64_t)m * kD + tid] = total > 0.0 ? (float)(mine / total) : 0.f;
+}
+
+hipError_t launch_tridiag_entropy(int n_mat, int N, int k_trunc, unsigned flags, const EntropyPlan& p,
+                                  char* ws, float* entropy_out, float* eig_out, const Env& env) {
+    const float* gram = reinterpret_cast<const float*>(ws + p.gram_off);
+    const float* sums = reinterpret_cast<const float*>(ws + p.sum_off);
+    env.begin("tridiag_entropy");
+    tridiag_entropy_kernel<<<dim3(n_mat), dim3(kThreads), 0, env.s>>>(gram, sums, p.n_chunks, N, k_trunc, flags,
+                                                                      entropy_out, eig_out);
+    env.end();
+    return hipGetLastError();
+}
+
+}  // namespace uncomp
