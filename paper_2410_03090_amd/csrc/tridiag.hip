@@ -32,15 +32,18 @@ namespace uncomp {
 
 namespace {
 
-constexpr int kThreads = 256;
-constexpr int kHalf = kD / 2;
+// The kernel comes in two shapes.  kParts = 4: 512 threads per matrix, 32 rows of a column per
+// thread, two waves per SIMD from the one matrix a CU works on (a launch with fewer matrices
+// than the chip can hold two per CU).  kParts = 2: 256 threads, 64 rows per thread, registers
+// capped so that two matrices share a CU and fill each other's waits (large launches).
 
+template <int kParts>
 struct TriSmem {
     double s[kD];            // column sums of X (for the mean correction)
     double red[8];
     double xbuf[kD];         // pivot row i, entries at columns <= i zeroed
     double ybuf[kD];         // row i + 1
-    double pbuf[2][kD];      // the two row halves of A v
+    double pbuf[kParts][kD]; // the row slices of A x
     double2 vw[kD];          // (v_r, w_r)
     double2 de[kD];          // (d_i, e_{i-1}^2), e_{-1} = 0
     double lam[kD];          // eigenvalues, descending
@@ -77,12 +80,16 @@ __device__ __forceinline__ double wave_allsum(double v) {
     return v;
 }
 
+template <int kWaves>
 __device__ __forceinline__ double block_sum(double v, double* red, int tid) {
     v = wave_allsum(v);
     __syncthreads();
     if ((tid & 63) == 0) red[tid >> 6] = v;
     __syncthreads();
-    return red[0] + red[1] + red[2] + red[3];
+    double t = red[0];
+#pragma unroll
+    for (int x = 1; x < kWaves; ++x) t += red[x];
+    return t;
 }
 
 // Number of eigenvalues of the tridiagonal matrix below x: sign changes along
@@ -120,14 +127,17 @@ __device__ __forceinline__ int sturm_count(const double2* de, double x) {
 
 }  // namespace
 
-__global__ __launch_bounds__(kThreads) void tridiag_entropy_kernel(
+template <int kParts>
+__global__ __launch_bounds__(kD * kParts, kParts == 2 ? 2 : 1) void tridiag_entropy_kernel(
     const float* __restrict__ gram_part, const float* __restrict__ sum_part, int n_chunks, int N,
     int k_trunc, unsigned flags, float* __restrict__ entropy_out, float* __restrict__ eig_out) {
-    __shared__ TriSmem sm;
+    constexpr int kThreads = kD * kParts, kWaves = kThreads / 64;
+    constexpr int kHalf = kD / kParts;                           // rows of a column per thread
+    __shared__ TriSmem<kParts> sm;
     const int m = blockIdx.x;
     const int tid = threadIdx.x, lane = tid & 63;
     const int c = tid & (kD - 1);
-    const int hf = __builtin_amdgcn_readfirstlane(tid >> 7);     // wave-uniform: which 64 rows
+    const int hf = __builtin_amdgcn_readfirstlane(tid >> 7);     // wave-uniform: which slice of rows
     const float* Gm = gram_part + (int64_t)m * n_chunks * (kD * kD);
     const float* Sm = sum_part + (int64_t)m * n_chunks * kD;
 
@@ -147,8 +157,8 @@ __global__ __launch_bounds__(kThreads) void tridiag_entropy_kernel(
         tr_u = acc;
         tr_c = center ? acc - sm.s[tid] * sm.s[tid] * inv_n : acc;
     }
-    const double trace = block_sum(tr_c, sm.red, tid);
-    const double trace_u = block_sum(tr_u, sm.red, tid);
+    const double trace = block_sum<kWaves>(tr_c, sm.red, tid);
+    const double trace_u = block_sum<kWaves>(tr_u, sm.red, tid);
     // Zero spread: a single token, or a centred trace so far below the second moment that
     // the fp32 partial sums cannot tell it from zero.
     const bool degenerate = !(trace > 0.0) || (center && (N < 2 || trace < trace_u * 0x1p-20));
@@ -163,7 +173,13 @@ __global__ __launch_bounds__(kThreads) void tridiag_entropy_kernel(
     for (int ch = 0; ch < n_chunks; ++ch) {
         const float* g = Gm + (int64_t)ch * (kD * kD) + (hf * kHalf) * kD + c;
 #pragma unroll
-        for (int k = 0; k < kHalf; ++k) a[k] += (double)g[k * kD];
+        for (int kb = 0; kb < kHalf; kb += 16) {                 // 16 independent loads in flight
+            float t[16];
+#pragma unroll
+            for (int u = 0; u < 16; ++u) t[u] = g[(kb + u) * kD];
+#pragma unroll
+            for (int u = 0; u < 16; ++u) a[kb + u] += (double)t[u];
+        }
     }
     {
         const double inv_tr = 1.0 / trace;
@@ -173,84 +189,94 @@ __global__ __launch_bounds__(kThreads) void tridiag_entropy_kernel(
     }
 
     // ---- 2. Householder tridiagonalisation ---------------------------------------------------
-    // Copies row `row` of the matrix (held by the 128 threads of one half, in a register whose
-    // number depends on `row`) to LDS: two levels of uniform branches reach the register
-    // without indexing it.  Entries at columns <= cmin are written as zero; the diagonal
-    // entry goes to de[row].x when asked for.
-    auto publish = [&](double* buf, int row, int cmin, bool with_diag) {
-        const int kk = row - hf * kHalf;
-        if (kk < 0 || kk >= kHalf) return;
-#pragma unroll
-        for (int b = 0; b < 4; ++b) {
-            if ((kk >> 4) == b) {
-#pragma unroll
-                for (int u = 0; u < 16; ++u) {
-                    if ((kk & 15) == u) {
-                        buf[c] = c > cmin ? a[16 * b + u] : 0.0;
-                        if (with_diag && c == row) sm.de[row].x = a[16 * b + u];
-                    }
-                }
-            }
+    // Leaves rows `row` and `row + 1` of the matrix in LDS for the next reflection: row `row` in
+    // xbuf with the entries at columns <= row zeroed (its diagonal entry goes to de[row].x), row
+    // `row + 1` in ybuf.  A row is held by the 128 threads of one half in a register whose number
+    // depends on the row; a switch on that (wave-uniform) number reaches it without indexing.
+#define UNCOMP_TRI_CASE(K)                                                      \
+    case K:                                                                     \
+        if constexpr (K < kHalf) {                                              \
+            sm.xbuf[c] = c > row ? a[K] : 0.0;                                  \
+            if (c == row) sm.de[row].x = a[K];                                  \
+            if (K + 1 < kHalf) sm.ybuf[c] = a[K + 1 < kHalf ? K + 1 : K];       \
+        }                                                                       \
+        break;
+#define UNCOMP_TRI_CASE8(K)                                                                          \
+    UNCOMP_TRI_CASE(K) UNCOMP_TRI_CASE(K + 1) UNCOMP_TRI_CASE(K + 2) UNCOMP_TRI_CASE(K + 3)          \
+    UNCOMP_TRI_CASE(K + 4) UNCOMP_TRI_CASE(K + 5) UNCOMP_TRI_CASE(K + 6) UNCOMP_TRI_CASE(K + 7)
+    auto publish2 = [&](int row) {
+        switch (row - hf * kHalf) {
+            case -1:                                             // row + 1 is the first row of this half
+                sm.ybuf[c] = a[0];
+                break;
+            UNCOMP_TRI_CASE8(0) UNCOMP_TRI_CASE8(8) UNCOMP_TRI_CASE8(16) UNCOMP_TRI_CASE8(24)
+            UNCOMP_TRI_CASE8(32) UNCOMP_TRI_CASE8(40) UNCOMP_TRI_CASE8(48) UNCOMP_TRI_CASE8(56)
+            default:
+                break;
         }
     };
-    publish(sm.xbuf, 0, 0, true);
-    publish(sm.ybuf, 1, -1, false);
+#undef UNCOMP_TRI_CASE8
+#undef UNCOMP_TRI_CASE
+    publish2(0);
     for (int i = 0; i < kD - 2; ++i) {
         __syncthreads();                                         // xbuf = row i (masked), ybuf = row i + 1
         const double x1 = sm.xbuf[i + 1];
         const double xa = lane > i + 1 ? sm.xbuf[lane] : 0.0;
         const double xb = lane + 64 > i + 1 ? sm.xbuf[lane + 64] : 0.0;
+        // This thread's part of (A x)_c over the rows of its half (x is zero on the rows that are
+        // done).  It does not depend on the reflection's scalars, so it runs beside their reduction.
+        double p0 = 0.0, p1 = 0.0, p2 = 0.0, p3 = 0.0;
+        const bool half_live = hf * kHalf + kHalf - 1 > i;
+        if (half_live) {
+#pragma unroll
+            for (int k = 0; k < kHalf; k += 4) {
+                const double2 xv0 = *reinterpret_cast<const double2*>(&sm.xbuf[hf * kHalf + k]);
+                const double2 xv1 = *reinterpret_cast<const double2*>(&sm.xbuf[hf * kHalf + k + 2]);
+                p0 = fma(a[k], xv0.x, p0);
+                p1 = fma(a[k + 1], xv0.y, p1);
+                p2 = fma(a[k + 2], xv1.x, p2);
+                p3 = fma(a[k + 3], xv1.y, p3);
+            }
+        }
         const double tail = wave_allsum(xa * xa + xb * xb);      // sum_{r > i+1} x_r^2, same bits in every wave
         if (tail == 0.0) {
             // the column is already in tridiagonal form: nothing to reflect
             if (tid == 0) sm.de[i + 1].y = x1 * x1;
             __syncthreads();                                     // both rows read by all before they are replaced
         } else {
+            // v = x - alpha e_{i+1};  A v = A x - alpha (row i + 1)
             const double sigma = tail + x1 * x1;
             const double nrm = sqrt(sigma);
             const double alpha = x1 >= 0.0 ? -nrm : nrm;
-            const double beta = 1.0 / (sigma - alpha * x1);
+            const double den = sigma - alpha * x1;               // = sigma + |x1| sqrt(sigma) > 0
+            double beta = __builtin_amdgcn_rcp(den);
+            beta = fma(fma(-den, beta, 1.0), beta, beta);        // two Newton steps on the hardware estimate
+            beta = fma(fma(-den, beta, 1.0), beta, beta);
             if (tid == 0) sm.de[i + 1].y = sigma;                // e_i^2 = alpha^2
-            // v = x - alpha e_{i+1}.  This thread's part of (A x)_c over the rows of its half; blocks
-            // of 16 rows that are done (x = 0 there) are skipped.  A e_{i+1} is row i + 1.
-            double p0 = 0.0, p1 = 0.0, p2 = 0.0, p3 = 0.0;
-#pragma unroll
-            for (int b = 0; b < 4; ++b) {
-                if (hf * kHalf + 16 * b + 15 > i) {
-#pragma unroll
-                    for (int u = 0; u < 16; u += 4) {
-                        const double2 xv0 = *reinterpret_cast<const double2*>(&sm.xbuf[hf * kHalf + 16 * b + u]);
-                        const double2 xv1 = *reinterpret_cast<const double2*>(&sm.xbuf[hf * kHalf + 16 * b + u + 2]);
-                        p0 = fma(a[16 * b + u], xv0.x, p0);
-                        p1 = fma(a[16 * b + u + 1], xv0.y, p1);
-                        p2 = fma(a[16 * b + u + 2], xv1.x, p2);
-                        p3 = fma(a[16 * b + u + 3], xv1.y, p3);
-                    }
-                }
-            }
             sm.pbuf[hf][c] = (p0 + p1) + (p2 + p3);
             __syncthreads();
             auto v_of = [&](int r) { return sm.xbuf[r] - (r == i + 1 ? alpha : 0.0); };
-            auto Av_of = [&](int r) { return (sm.pbuf[0][r] + sm.pbuf[1][r]) - alpha * sm.ybuf[r]; };
+            auto Av_of = [&](int r) {
+                double t = sm.pbuf[0][r];
+#pragma unroll
+                for (int x = 1; x < kParts; ++x) t += sm.pbuf[x][r];
+                return t - alpha * sm.ybuf[r];
+            };
             const double vAv = wave_allsum(v_of(lane) * Av_of(lane) + v_of(lane + 64) * Av_of(lane + 64));
             const double K = 0.5 * beta * beta * vAv;
             const double vc = v_of(c);
             const double wc = c > i ? beta * Av_of(c) - K * vc : 0.0;
             if (hf == 0) sm.vw[c] = make_double2(vc, wc);
             __syncthreads();
+            if (half_live) {
 #pragma unroll
-            for (int b = 0; b < 4; ++b) {
-                if (hf * kHalf + 16 * b + 15 > i) {
-#pragma unroll
-                    for (int u = 0; u < 16; ++u) {
-                        const double2 t = sm.vw[hf * kHalf + 16 * b + u];
-                        a[16 * b + u] = fma(-t.x, wc, fma(-t.y, vc, a[16 * b + u]));
-                    }
+                for (int k = 0; k < kHalf; ++k) {
+                    const double2 t = sm.vw[hf * kHalf + k];
+                    a[k] = fma(-t.x, wc, fma(-t.y, vc, a[k]));
                 }
             }
         }
-        publish(sm.xbuf, i + 1, i + 1, true);
-        if (i + 2 < kD) publish(sm.ybuf, i + 2, -1, false);
+        publish2(i + 1);
     }
     __syncthreads();                                             // xbuf = row 126 (masked)
     if (tid == 0) {
@@ -264,7 +290,8 @@ __global__ __launch_bounds__(kThreads) void tridiag_entropy_kernel(
     // ---- 3. eigenvalues by multisection on the Sturm count ------------------------------------
     const int k = k_trunc < kD ? k_trunc : kD;
     const int n_need = eig_out != nullptr ? kD : k;
-    const int L = n_need <= 16 ? 16 : (n_need <= 32 ? 8 : (n_need <= 64 ? 4 : 2));   // lanes per eigenvalue
+    // lanes per eigenvalue: as many as the workgroup can give every wanted eigenvalue
+    const int L = kThreads / 16 >= n_need ? 16 : (kThreads / 8 >= n_need ? 8 : (kThreads / 4 >= n_need ? 4 : 2));
     const int rounds = L == 16 ? 8 : (L == 8 ? 10 : (L == 4 ? 14 : 20));           // (L+1)^rounds >= 2^31
     {
         const int q = tid / L, s = tid % L;                      // eigenvalue q (0 = largest), piece s
@@ -290,15 +317,15 @@ __global__ __launch_bounds__(kThreads) void tridiag_entropy_kernel(
 
     // ---- 4. entropy --------------------------------------------------------------------------
     const double mine = tid < kD ? sm.lam[tid] : 0.0;
-    const double total = block_sum(tid < kD ? sm.de[tid].x : 0.0, sm.red, tid);   // the trace: sum of all eigenvalues
-    const double topk = block_sum(tid < k ? mine : 0.0, sm.red, tid);
+    const double total = block_sum<kWaves>(tid < kD ? sm.de[tid].x : 0.0, sm.red, tid);   // the trace: sum of all eigenvalues
+    const double topk = block_sum<kWaves>(tid < k ? mine : 0.0, sm.red, tid);
     const double denom = (flags & UNCOMP_TRUNC_RENORM) ? topk : total;
     double term = 0.0;
     if (tid < k && mine > 0.0 && denom > 0.0) {
         const double sgm = mine / denom;
         term = -sgm * log(sgm);
     }
-    const double H = block_sum(term, sm.red, tid);
+    const double H = block_sum<kWaves>(term, sm.red, tid);
     if (tid == 0) entropy_out[m] = (float)H;
     if (eig_out != nullptr && tid < kD)
         eig_out[(int64_t)m * kD + tid] = total > 0.0 ? (float)(mine / total) : 0.f;
@@ -309,8 +336,12 @@ hipError_t launch_tridiag_entropy(int n_mat, int N, int k_trunc, unsigned flags,
     const float* gram = reinterpret_cast<const float*>(ws + p.gram_off);
     const float* sums = reinterpret_cast<const float*>(ws + p.sum_off);
     env.begin("tridiag_entropy");
-    tridiag_entropy_kernel<<<dim3(n_mat), dim3(kThreads), 0, env.s>>>(gram, sums, p.n_chunks, N, k_trunc, flags,
-                                                                      entropy_out, eig_out);
+    if (n_mat < 512)
+        tridiag_entropy_kernel<4><<<dim3(n_mat), dim3(4 * kD), 0, env.s>>>(gram, sums, p.n_chunks, N, k_trunc, flags,
+                                                                         entropy_out, eig_out);
+    else
+        tridiag_entropy_kernel<2><<<dim3(n_mat), dim3(2 * kD), 0, env.s>>>(gram, sums, p.n_chunks, N, k_trunc, flags,
+                                                                         entropy_out, eig_out);
     env.end();
     return hipGetLastError();
 }

@@ -49,6 +49,20 @@ def test_entropy_matches_oracle(ctx, dtype, N):
             np.testing.assert_allclose(eig.cpu().numpy(), eref, rtol=0, atol=2e-5)
 
 
+def test_entropy_many_matrices(ctx):
+    """600 matrices in one call: the launch shape used for large batches (two matrices per CU)."""
+    X = _rand_lowrank(600, 200, 128, 20, torch.bfloat16, seed=600)
+    H, eig = ctx.head_entropy(X.to(DEV), k_trunc=32, want_eig=True)
+    H2 = ctx.head_entropy(X.to(DEV), k_trunc=32)                 # top-k only (no spectrum requested)
+    torch.cuda.synchronize()
+    sample = list(range(0, 600, 37)) + [599]
+    Href, eref = O.head_entropy(to_f64(X[sample]), k_trunc=32)
+    np.testing.assert_allclose(H.cpu().numpy()[sample], Href, rtol=1e-4)
+    np.testing.assert_allclose(H2.cpu().numpy()[sample], Href, rtol=1e-4)
+    np.testing.assert_allclose(eig.cpu().numpy()[sample], eref, rtol=0, atol=2e-5)
+    np.testing.assert_allclose(H.cpu().numpy(), H2.cpu().numpy(), rtol=1e-6)
+
+
 def test_entropy_config0(ctx):
     cfg = synth.CONFIGS[0]
     K, V, Q = synth.gen_all(cfg, seed0=1234)
