@@ -102,7 +102,9 @@ uncomp_status uncomp_set_overlap(uncomp_ctx* ctx, int on);
 uncomp_status uncomp_join(uncomp_ctx* ctx, void* stream);
 
 /* Kernel selection for testing: plain_alu != 0 makes the bf16 calls use the plain-ALU
- * kernels (the ones fp32 inputs always use) instead of the MFMA kernels.  Default 0. */
+ * kernels (the ones fp32 inputs always use) instead of the MFMA kernels, the eigen stage the
+ * fp32 Jacobi iteration instead of the fp64 tridiagonalisation, and uncomp_decode_step its
+ * one-kernel path.  Default 0. */
 uncomp_status uncomp_set_kernel_path(uncomp_ctx* ctx, int plain_alu);
 
 /*
