@@ -31,6 +31,11 @@ Parity status of each function (what pins it lives in tests/test_oracle_*.py):
                     probability mass G per step; a dominant key takes the whole step;
                     the evicted entry checked by exhaustive search on tiny caches;
                     occupancy and recent-window invariants over long runs.
+* hidden_evict      pinned: the score equals the head sum of the pinned window score with
+                    a one-token window and no pooling; zero queries give the uniform 1/N
+                    closed form (ties then keep the lowest positions); total mass = number
+                    of query heads; a dominant key is always kept; exhaustive subset
+                    search on tiny inputs; rows copied bit for bit.
 """
 from __future__ import annotations
 
@@ -310,3 +315,42 @@ def decode_step(Kc: np.ndarray, Vc: np.ndarray, idx: np.ndarray, cum: np.ndarray
         keep = np.arange(n + 1) != best
         keys, vals, where, total = keys[keep], vals[keep], where[keep], total[keep]
     return keys, vals, where.astype(np.int32), total, out, evicted
+
+
+# --------------------------------------------------------------------------
+# O6  stage-1 hidden-state eviction  (Sec. 3.3.2 "Hidden State Eviction": the
+#     tokens entering layer i+1 are the N_{i+1} that receive the most attention
+#     from the last token in layer i; N_{i+1} from Eq. 10)
+# --------------------------------------------------------------------------
+def last_token_score(q_last: np.ndarray, K: np.ndarray, G: int) -> np.ndarray:
+    """q_last [Hq, D] the last position's queries, K [H, N, D] the layer's keys
+    (query head q reads KV head q // G).  score[j] = sum over the Hq query heads
+    of softmax_j(q . k_j / sqrt(D)), the last token attending to all N positions."""
+    q_last = np.asarray(q_last, dtype=np.float64)
+    K = np.asarray(K, dtype=np.float64)
+    Hq, D = q_last.shape
+    N = K.shape[1]
+    score = np.zeros(N)
+    for q in range(Hq):
+        logits = K[q // G] @ q_last[q] / np.sqrt(D)
+        ex = np.exp(logits - logits.max())
+        score += ex / ex.sum()
+    return score
+
+
+def hidden_evict(q_last, K, Hs, n_keep: int, w: int, G: int):
+    """q_last [B, Hq, D], K [B, H, N, D], Hs [B, N, Dm] (any dtype; rows are copied
+    verbatim).  Per batch entry the n_keep positions that survive are the last w
+    (kept unconditionally: the last token carries the next prediction) plus the
+    n_keep - w earlier positions of largest last-token score, equal scores
+    towards the lower position; n_keep is clamped to [min(w, N), N].  Returns
+    (rows [B, n, Dm], idx [B, n] int32 ascending, score [B, N] float64)."""
+    B, N = Hs.shape[0], Hs.shape[1]
+    rows, idx, scores = [], [], []
+    for b in range(B):
+        sc = last_token_score(q_last[b], K[b], G)
+        sel = select_indices(sc[: N - w], n_keep, N, w)
+        rows.append(np.stack([Hs[b, j] for j in sel]) if len(sel) else Hs[b, :0])
+        idx.append(sel)
+        scores.append(sc)
+    return np.stack(rows), np.stack(idx), np.stack(scores)
