@@ -13,6 +13,10 @@
  *   uncomp_decode_init     cumulative scores of the compacted cache from the prefill score
  *   uncomp_decode_step     one token: attention over the cache, score update, eviction
  *
+ * and, between the layers of the prefill where the token count drops:
+ *
+ *   uncomp_hidden_evict    last-token attention -> top-N rows of the hidden states
+ *
  * Conventions that hold for every call:
  *   - Pointers named X, K, V, Qwin, *_out, entropy, score, budget are DEVICE pointers
  *     owned by the caller; the library never allocates, frees or keeps them.  The
@@ -231,6 +235,33 @@ uncomp_status uncomp_decode_step(uncomp_ctx* ctx, const void* q, const void* k_n
                                  const int32_t* pos, const int32_t* budget, int w, int cap,
                                  void* K_c, void* V_c, int32_t* idx, float* cum, int32_t* len,
                                  float* out, int32_t* evicted, void* stream);
+
+/*
+ * Stage-1 hidden-state eviction (Sec. 3.3.2 "Hidden State Eviction": the tokens that enter the
+ * next layer group are the N_{i+1} that receive the most attention from the last token in the
+ * current layer; N_{i+1} is layer_tokens of uncomp_assign_budgets, Eq. 10).
+ *
+ * q_last [B][H*G][D] dense: the queries of the last position; K as in uncomp_window_score (the
+ * current layer's keys over its N positions).  score[b][j] = sum over the H*G query heads of
+ * softmax_j(q . k_j / sqrt(D)), j in [0, N), in fp32.  n_keep is a DEVICE pointer to one int32
+ * (typically &layer_tokens[l + 1]) used for every batch entry.  Per batch entry:
+ * n = clamp(*n_keep, w, min(N, cap)); the last w positions are kept unconditionally (the last
+ * token carries the next prediction), plus the n - w earlier positions of largest score, equal
+ * scores by lower position.  idx_out[b][0..n) lists them ascending, len_out[b] = n,
+ * Hs_out[b][r][:] = Hs[b][idx[r]][:] bit for bit (rows of Dm elements of `dtype`; batch b, row t
+ * of Hs at element b*hs_strides[0] + t*hs_strides[1]).  Outputs are dense [B][cap][Dm] / [B][cap];
+ * rows at r >= n are left untouched.  score_out, if not NULL, receives score[b][0 .. N-w) as
+ * [B][N-w] floats.  Hs / Hs_out may be NULL together to obtain indices only.
+ * Requires 1 <= w < N, w <= cap, D == 128, Dm*sizeof(element) and the Hs strides in bytes
+ * multiples of 16.  Workspace: uncomp_hidden_workspace_bytes.
+ */
+size_t uncomp_hidden_workspace_bytes(int B, int H, int G, int N, int w);
+uncomp_status uncomp_hidden_evict(uncomp_ctx* ctx, const void* q_last, const void* K,
+                                  uncomp_dtype dtype, int B, int H, int G, int N, int D,
+                                  const int64_t k_strides[3], const int32_t* n_keep, int w,
+                                  const void* Hs, const int64_t hs_strides[2], int Dm, int cap,
+                                  void* Hs_out, int32_t* idx_out, int32_t* len_out,
+                                  float* score_out, void* stream);
 
 #ifdef __cplusplus
 }

@@ -26,6 +26,7 @@ EXPORTS = (
     "uncomp_profile", "uncomp_profile_read", "uncomp_set_kernel_path", "uncomp_set_overlap", "uncomp_join",
     "uncomp_head_entropy", "uncomp_assign_budgets", "uncomp_window_score", "uncomp_select_gather",
     "uncomp_decode_init", "uncomp_decode_step", "uncomp_decode_workspace_bytes",
+    "uncomp_hidden_evict", "uncomp_hidden_workspace_bytes",
 )
 
 _lib = None
@@ -83,6 +84,11 @@ def load_library() -> ctypes.CDLL:
     lib.uncomp_decode_step.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, vp, vp, i32, i32,
                                        vp, vp, vp, vp, vp, vp, vp, vp]
     lib.uncomp_decode_step.restype = i32
+    lib.uncomp_hidden_workspace_bytes.argtypes = [i32] * 5
+    lib.uncomp_hidden_workspace_bytes.restype = c.c_size_t
+    lib.uncomp_hidden_evict.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, i32, c.POINTER(i64), vp, i32,
+                                        vp, c.POINTER(i64), i32, i32, vp, vp, vp, vp, vp]
+    lib.uncomp_hidden_evict.restype = i32
     lib.uncomp_decode_workspace_bytes.argtypes = [i32, i32, i32]
     lib.uncomp_decode_workspace_bytes.restype = c.c_size_t
     _lib = lib
@@ -124,6 +130,10 @@ class Context:
     @staticmethod
     def decode_workspace_bytes(n_heads: int, G: int, cap: int) -> int:
         return int(load_library().uncomp_decode_workspace_bytes(n_heads, G, cap))
+
+    @staticmethod
+    def hidden_workspace_bytes(B: int, H: int, G: int, N: int, w: int) -> int:
+        return int(load_library().uncomp_hidden_workspace_bytes(B, H, G, N, w))
 
     def close(self):
         if getattr(self, "handle", None) is not None and self.handle:
@@ -270,3 +280,33 @@ class Context:
             pos.data_ptr(), budget.data_ptr(), int(w), cap, K_c.data_ptr(), V_c.data_ptr(), idx.data_ptr(),
             cum.data_ptr(), length.data_ptr(), _ptr(out), evicted.data_ptr(), _stream()))
         return out, evicted
+
+    # -- stage-1 hidden-state eviction ------------------------------------------------------
+    def hidden_evict(self, q_last: torch.Tensor, K: torch.Tensor, G: int, n_keep: torch.Tensor, w: int,
+                     Hs, cap: int, want_score: bool = False, out=None):
+        """q_last [B, H*G, D] contiguous, K [B, H, N, D] (last dim contiguous), n_keep a one-element int32
+        device tensor, Hs [B, N, Dm] (last dim contiguous) or None.
+        Returns Hs_out [B, cap, Dm] (None without Hs), idx [B, cap] int32, len [B] int32, score [B, N-w] or None."""
+        B, Hq, D = q_last.shape
+        _, H, N, _ = K.shape
+        assert q_last.is_contiguous() and K.stride(3) == 1 and Hq == H * G and q_last.dtype == K.dtype
+        assert n_keep.dtype == torch.int32 and n_keep.numel() >= 1
+        ks = (ctypes.c_int64 * 3)(K.stride(0), K.stride(1), K.stride(2))
+        dev = K.device
+        if Hs is not None:
+            assert Hs.stride(2) == 1 and Hs.dtype == K.dtype and Hs.shape[0] == B and Hs.shape[1] == N
+            Dm = Hs.shape[2]
+            hs = (ctypes.c_int64 * 2)(Hs.stride(0), Hs.stride(1))
+        else:
+            Dm, hs = 0, None
+        if out is None:
+            out = (torch.zeros(B, cap, Dm, dtype=K.dtype, device=dev) if Hs is not None else None,
+                   torch.full((B, cap), -1, dtype=torch.int32, device=dev),
+                   torch.zeros(B, dtype=torch.int32, device=dev))
+        Ho, idx, ln = out
+        score = torch.empty(B, N - w, dtype=torch.float32, device=dev) if want_score else None
+        self._check(self.lib.uncomp_hidden_evict(
+            self.handle, q_last.data_ptr(), K.data_ptr(), _dtype_code(K), B, H, int(G), N, D, ks,
+            n_keep.data_ptr(), int(w), _ptr(Hs), hs, Dm, int(cap), _ptr(Ho), idx.data_ptr(), ln.data_ptr(),
+            _ptr(score), _stream()))
+        return Ho, idx, ln, score

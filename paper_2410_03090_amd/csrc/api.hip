@@ -272,6 +272,75 @@ uncomp_status uncomp_select_gather(uncomp_ctx* ctx, const float* score, const in
     return UNCOMP_OK;
 }
 
+namespace {
+struct HiddenPlan {
+    ScorePlan sp;
+    size_t score_off, sum_off, bytes;
+};
+HiddenPlan plan_hidden(int B, int H, int G, int N, int w) {
+    HiddenPlan p;
+    p.sp = plan_score(B, H, G, N, 1);
+    p.score_off = align_up(kBudgetScratch + p.sp.bytes, 256);
+    p.sum_off = align_up(p.score_off + (size_t)B * H * (N - 1) * sizeof(float), 256);
+    p.bytes = align_up(p.sum_off + (size_t)B * (N - w) * sizeof(float), 256);
+    return p;
+}
+}  // namespace
+
+size_t uncomp_hidden_workspace_bytes(int B, int H, int G, int N, int w) {
+    if (B <= 0 || H <= 0 || G <= 0 || N < 2 || w < 1 || w >= N) return 0;
+    return plan_hidden(B, H, G, N, w).bytes;
+}
+
+uncomp_status uncomp_hidden_evict(uncomp_ctx* ctx, const void* q_last, const void* K, uncomp_dtype dtype, int B,
+                                  int H, int G, int N, int D, const int64_t k_strides[3], const int32_t* n_keep,
+                                  int w, const void* Hs, const int64_t hs_strides[2], int Dm, int cap,
+                                  void* Hs_out, int32_t* idx_out, int32_t* len_out, float* score_out,
+                                  void* stream) {
+    if (ctx == nullptr) return UNCOMP_ERR_INVALID_ARG;
+    if (q_last == nullptr || K == nullptr || k_strides == nullptr || n_keep == nullptr || idx_out == nullptr ||
+        len_out == nullptr)
+        return fail(ctx, UNCOMP_ERR_INVALID_ARG, "hidden_evict: null pointer");
+    if ((Hs == nullptr) != (Hs_out == nullptr) || (Hs != nullptr && hs_strides == nullptr))
+        return fail(ctx, UNCOMP_ERR_INVALID_ARG, "hidden_evict: Hs, hs_strides and Hs_out must be given together");
+    if (B <= 0 || H <= 0 || G <= 0 || N <= 0 || cap <= 0) return fail(ctx, UNCOMP_ERR_INVALID_ARG, "hidden_evict: sizes must be positive");
+    if (dtype != UNCOMP_BF16 && dtype != UNCOMP_F32) return fail(ctx, UNCOMP_ERR_UNSUPPORTED, "hidden_evict: dtype");
+    if (D != kD) return fail(ctx, UNCOMP_ERR_UNSUPPORTED, "hidden_evict: D must be 128");
+    if (w < 1 || w >= N) return fail(ctx, UNCOMP_ERR_UNSUPPORTED, "hidden_evict: need 1 <= w < N");
+    if (cap < w) return fail(ctx, UNCOMP_ERR_INVALID_ARG, "hidden_evict: cap must be >= w");
+    if (G > 512) return fail(ctx, UNCOMP_ERR_UNSUPPORTED, "hidden_evict: G must be <= 512");
+    if (k_strides[2] < D || (k_strides[0] & 7) || (k_strides[1] & 7) || (k_strides[2] & 7) || k_strides[0] < 0 ||
+        k_strides[1] < 0 || !aligned16(K) || !aligned16(q_last))
+        return fail(ctx, UNCOMP_ERR_INVALID_ARG, "hidden_evict: key strides must be multiples of 8 elements, token stride >= D, 16-byte aligned pointers");
+    const int esz = dtype == UNCOMP_BF16 ? 2 : 4;
+    if (Hs != nullptr) {
+        if (Dm <= 0 || ((int64_t)Dm * esz) % 16 != 0 || hs_strides[1] < Dm || (hs_strides[0] * esz) % 16 != 0 ||
+            (hs_strides[1] * esz) % 16 != 0 || hs_strides[0] < 0 || !aligned16(Hs) || !aligned16(Hs_out))
+            return fail(ctx, UNCOMP_ERR_INVALID_ARG, "hidden_evict: hidden rows must be whole 16-byte units with 16-byte aligned strides and pointers");
+    }
+    if ((int64_t)B * H * ((N + 255) / 256) > 0x7fffffffLL || (int64_t)B * ((cap + 3) / 4) > 0x7fffffffLL)
+        return fail(ctx, UNCOMP_ERR_UNSUPPORTED, "hidden_evict: problem too large");
+    const HiddenPlan p = plan_hidden(B, H, G, N, w);
+    if (p.bytes > ctx->ws_bytes)
+        return fail(ctx, UNCOMP_ERR_WORKSPACE, "hidden_evict: needs %zu workspace bytes, context has %zu", p.bytes,
+                    ctx->ws_bytes);
+    uncomp_status js = uncomp_join(ctx, stream);          // the whole workspace is used: wait for side-stream work
+    if (js != UNCOMP_OK) return js;
+    const Env env{static_cast<hipStream_t>(stream), &ctx->prof, ctx->force_alu};
+    float* score = reinterpret_cast<float*>(ctx->ws + p.score_off);
+    float* sum = score_out != nullptr ? score_out : reinterpret_cast<float*>(ctx->ws + p.sum_off);
+    // the last token's attention = window score with a one-token window and no pooling
+    hipError_t e = launch_window_score(q_last, K, dtype, B, H, G, N, 1, 1, k_strides, p.sp, ctx->ws + kBudgetScratch,
+                                       score, env);
+    if (e == hipSuccess) e = launch_head_sum(score, B, H, N - 1, N - w, sum, env);
+    if (e == hipSuccess) e = launch_select_rows(sum, n_keep, 0, B, N, w, cap, idx_out, len_out, env);
+    if (e == hipSuccess && Hs != nullptr)
+        e = launch_gather_rows(Hs, idx_out, len_out, B, cap, Dm * esz, hs_strides[0] * esz, hs_strides[1] * esz, Hs_out,
+                               env);
+    if (e != hipSuccess) return hip_fail(ctx, e, "hidden_evict: launch");
+    return UNCOMP_OK;
+}
+
 size_t uncomp_decode_workspace_bytes(int n_heads, int G, int cap) {
     if (n_heads <= 0 || G <= 0 || cap <= 0) return 0;
     return plan_decode(n_heads, G, cap).bytes;

@@ -111,6 +111,12 @@ hipError_t launch_select_gather(const float* score, const int32_t* budget, const
                                 const void* V, uncomp_dtype dt, int B, int H, int N, int w,
                                 const int64_t ks[3], int cap, void* K_out, void* V_out,
                                 int32_t* idx_out, int32_t* len_out, const Env& env);
+hipError_t launch_select_rows(const float* score, const int32_t* budget, int budget_stride, int n_groups,
+                              int N, int w, int cap, int32_t* idx_out, int32_t* len_out, const Env& env);
+hipError_t launch_gather_rows(const void* src, const int32_t* idx, const int32_t* len, int n_groups, int cap,
+                              int row_bytes, int64_t group_stride_bytes, int64_t row_stride_bytes, void* dst,
+                              const Env& env);
+hipError_t launch_head_sum(const float* score, int B, int H, int P_in, int P_out, float* out, const Env& env);
 // Workspace of the bf16 decode path (two kernels per step).
 struct DecodePlan {
     int GT;              // query heads per KV head rounded up to 4, 8 or 16

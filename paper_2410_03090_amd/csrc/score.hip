@@ -88,6 +88,88 @@ __global__ __launch_bounds__(512) void score_stats_alu_kernel(
 }
 
 // ---------------------------------------------------------------------------------------
+// Pass 1 for a one-token window (w = 1: the last token's attention, R = G rows per head).  The
+// kernel above gives a thread to every query row, which leaves most of the machine idle when
+// there are only G of them; here the tokens are spread over the threads instead: 16 lanes read
+// one key row (8 features each), the G queries sit in registers, dot products are closed with
+// DPP row rotations and every group of 16 lanes keeps running (maximum, sum) pairs that are
+// merged at the end.  Same output layout as the kernel above.
+// ---------------------------------------------------------------------------------------
+template <typename T, int GT>
+__global__ __launch_bounds__(256) void score_stats_lastrow_kernel(
+    const T* __restrict__ Q, const T* __restrict__ K, int H, int G, int N, int64_t ks_b, int64_t ks_h,
+    int64_t ks_t, int n_chunks, int chunk, float2* __restrict__ stats) {
+    __shared__ float2 part[16][GT];
+    const int bh = blockIdx.x / n_chunks, c = blockIdx.x % n_chunks;
+    const int b = bh / H, h = bh % H;
+    const int tid = threadIdx.x, sub = tid & 15, rg = tid >> 4;
+    const T* Kh = K + b * ks_b + h * ks_h;
+    const float scale2 = kLog2e * rsqrtf((float)kD);
+    float qf[GT][8];
+#pragma unroll
+    for (int g = 0; g < GT; ++g) {
+        if (g < G) {
+            load8(Q + ((int64_t)bh * G + g) * kD + 8 * sub, qf[g]);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) qf[g][e] *= scale2;
+        } else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) qf[g][e] = 0.f;
+        }
+    }
+    float mx[GT], sum[GT];
+#pragma unroll
+    for (int g = 0; g < GT; ++g) {
+        mx[g] = -INFINITY;
+        sum[g] = 0.f;
+    }
+    const int t_begin = c * chunk, t_end = min(N, t_begin + chunk);
+    constexpr int U = 4;
+    for (int t0 = t_begin; t0 < t_end; t0 += 16 * U) {
+        float kv[U][8];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int t = min(t0 + 16 * u + rg, t_end - 1);          // clamped, never predicated
+            load8(Kh + (int64_t)t * ks_t + 8 * sub, kv[u]);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const bool live = t0 + 16 * u + rg < t_end;
+#pragma unroll
+            for (int g = 0; g < GT; ++g) {
+                float d = 0.f;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) d = fmaf(qf[g][e], kv[u][e], d);
+                d += __uint_as_float(__builtin_amdgcn_update_dpp(0u, __float_as_uint(d), 0x128, 0xF, 0xF, false));
+                d += __uint_as_float(__builtin_amdgcn_update_dpp(0u, __float_as_uint(d), 0x124, 0xF, 0xF, false));
+                d += __uint_as_float(__builtin_amdgcn_update_dpp(0u, __float_as_uint(d), 0x122, 0xF, 0xF, false));
+                d += __uint_as_float(__builtin_amdgcn_update_dpp(0u, __float_as_uint(d), 0x121, 0xF, 0xF, false));
+                if (live) {
+                    const float m_new = fmaxf(mx[g], d);
+                    sum[g] = sum[g] * exp2f(mx[g] - m_new) + exp2f(d - m_new);
+                    mx[g] = m_new;
+                }
+            }
+        }
+    }
+    if (sub == 0) {
+#pragma unroll
+        for (int g = 0; g < GT; ++g) part[rg][g] = make_float2(mx[g], sum[g]);
+    }
+    __syncthreads();
+    if (tid < G) {
+        float m = -INFINITY;
+        for (int r = 0; r < 16; ++r) m = fmaxf(m, part[r][tid].x);
+        float l = 0.f;
+        for (int r = 0; r < 16; ++r) {
+            const float2 pr = part[r][tid];
+            if (pr.y > 0.f) l += pr.y * exp2f(pr.x - m);               // groups that saw no token hold (-inf, 0)
+        }
+        stats[((int64_t)bh * n_chunks + c) * G + tid] = make_float2(m, l);
+    }
+}
+
+// ---------------------------------------------------------------------------------------
 // bf16 MFMA kernels.  Logits S = Q K^T contract over the 128 features, which are contiguous
 // in memory, so both operands of v_mfma_f32_16x16x32_bf16 load straight from rows.  Both
 // passes use the same barrier-free streaming scheme: the query rows of the KV head sit in
@@ -546,7 +628,19 @@ static hipError_t run_score(const T* Q, const T* K, int B, int H, int G, int N, 
             n_parts = p.n_chunks * 4;
         }
     }
-    if (!mfma) {
+    if (!mfma && w == 1 && G <= 16) {
+        env.begin("score_stats_lastrow");
+        if (G <= 4)
+            score_stats_lastrow_kernel<T, 4><<<grid1, dim3(256), 0, s>>>(Q, K, H, G, N, ks[0], ks[1], ks[2], p.n_chunks,
+                                                                         p.chunk, stats);
+        else if (G <= 8)
+            score_stats_lastrow_kernel<T, 8><<<grid1, dim3(256), 0, s>>>(Q, K, H, G, N, ks[0], ks[1], ks[2], p.n_chunks,
+                                                                         p.chunk, stats);
+        else
+            score_stats_lastrow_kernel<T, 16><<<grid1, dim3(256), 0, s>>>(Q, K, H, G, N, ks[0], ks[1], ks[2], p.n_chunks,
+                                                                          p.chunk, stats);
+        env.end();
+    } else if (!mfma) {
         const int threads1 = (p.R + 63) / 64 * 64;
         env.begin("score_stats_alu");
         score_stats_alu_kernel<T><<<grid1, dim3(threads1), 0, s>>>(Q, K, H, G, N, w, ks[0], ks[1], ks[2],

@@ -63,8 +63,9 @@ __device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, SelSmem& sm, uin
 }  // namespace
 
 __global__ __launch_bounds__(kSelThreads) void select_kernel(const float* __restrict__ score,
-                                                             const int32_t* __restrict__ budget, int N,
-                                                             int w, int cap, int32_t* __restrict__ idx_out,
+                                                             const int32_t* __restrict__ budget,
+                                                             int budget_stride, int N, int w, int cap,
+                                                             int32_t* __restrict__ idx_out,
                                                              int32_t* __restrict__ len_out) {
     __shared__ SelSmem sm;
     const int bh = blockIdx.x;
@@ -73,7 +74,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const float* __rest
     const float* sc = score + (int64_t)bh * P;
     int32_t* idx = idx_out + (int64_t)bh * cap;
 
-    int bud = budget[bh];
+    int bud = budget[(int64_t)bh * budget_stride];     // stride 0: one budget for every row of scores
     const int hi = N < cap ? N : cap;
     bud = bud < w ? w : bud;
     bud = bud > hi ? hi : bud;
@@ -248,7 +249,7 @@ hipError_t launch_select_gather(const float* score, const int32_t* budget, const
     hipStream_t s = env.s;
     const int BH = B * H;
     env.begin("select");
-    select_kernel<<<dim3(BH), dim3(kSelThreads), 0, s>>>(score, budget, N, w, cap, idx_out, len_out);
+    select_kernel<<<dim3(BH), dim3(kSelThreads), 0, s>>>(score, budget, 1, N, w, cap, idx_out, len_out);
     env.end();
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || K == nullptr) return e;
@@ -262,6 +263,45 @@ hipError_t launch_select_gather(const float* score, const int32_t* budget, const
         static_cast<const uint4*>(K), static_cast<const uint4*>(V), idx_out, len_out, H, cap, lanes,
         ks[0] / per16, ks[1] / per16, ks[2] / per16, n_row_tiles, static_cast<uint4*>(K_out),
         static_cast<uint4*>(V_out));
+    env.end();
+    return hipGetLastError();
+}
+
+// Rows of any width: idx[g][r] names the source row of output row r of group g; rows are
+// copied in 16-byte units, four rows per workgroup.
+__global__ __launch_bounds__(256) void gather_rows_kernel(const uint4* __restrict__ src,
+                                                          const int32_t* __restrict__ idx,
+                                                          const int32_t* __restrict__ len, int cap, int units,
+                                                          int64_t group_stride, int64_t row_stride,
+                                                          int n_row_tiles, uint4* __restrict__ dst) {
+    const int g = blockIdx.x / n_row_tiles, tile = blockIdx.x % n_row_tiles;
+    const int n = len[g];
+    for (int rr = 0; rr < 4; ++rr) {
+        const int r = tile * 4 + rr;
+        if (r >= n || r >= cap) return;
+        const uint4* s = src + g * group_stride + (int64_t)idx[(int64_t)g * cap + r] * row_stride;
+        uint4* d = dst + ((int64_t)g * cap + r) * units;
+        for (int u = threadIdx.x; u < units; u += 256) d[u] = s[u];
+    }
+}
+
+hipError_t launch_select_rows(const float* score, const int32_t* budget, int budget_stride, int n_groups,
+                              int N, int w, int cap, int32_t* idx_out, int32_t* len_out, const Env& env) {
+    env.begin("select");
+    select_kernel<<<dim3(n_groups), dim3(kSelThreads), 0, env.s>>>(score, budget, budget_stride, N, w, cap, idx_out,
+                                                                  len_out);
+    env.end();
+    return hipGetLastError();
+}
+
+hipError_t launch_gather_rows(const void* src, const int32_t* idx, const int32_t* len, int n_groups, int cap,
+                              int row_bytes, int64_t group_stride_bytes, int64_t row_stride_bytes, void* dst,
+                              const Env& env) {
+    const int n_row_tiles = (cap + 3) / 4;
+    env.begin("gather_rows");
+    gather_rows_kernel<<<dim3((unsigned)(n_groups * n_row_tiles)), dim3(256), 0, env.s>>>(
+        static_cast<const uint4*>(src), idx, len, cap, row_bytes / 16, group_stride_bytes / 16, row_stride_bytes / 16,
+        n_row_tiles, static_cast<uint4*>(dst));
     env.end();
     return hipGetLastError();
 }
