@@ -68,6 +68,7 @@ def main():
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="also run one plain device copy of this many MiB (reference for HBM byte counters)")
     ap.add_argument("--cpu-heads", type=int, default=0, help="heads in the oracle sample (0 = auto)")
+    ap.add_argument("--no-hidden-evict", action="store_true", help="skip the stage-1 hidden-state eviction leg")
     ap.add_argument("--decode-steps", type=int, default=64,
                     help="generated tokens to run through uncomp_decode_step after the timed prefill steps (0 = skip)")
     args = ap.parse_args()
@@ -94,6 +95,8 @@ def main():
     ws = binding.Context.workspace_bytes(LB * H, N, D, LB, H, G, w)
     if args.decode_steps > 0:
         ws = max(ws, binding.Context.decode_workspace_bytes(LB * H, G, cfg.cap))
+    if not args.no_hidden_evict:
+        ws = max(ws, binding.Context.hidden_workspace_bytes(B, H, G, N, w))
     ctx = binding.Context(0, ws)
     ctx.set_overlap(not args.no_overlap)
     i32 = dict(dtype=torch.int32, device=dev)
@@ -160,6 +163,7 @@ def main():
                         "frac": None, "traffic": None}
 
     decode = decode_leg(cfg, ctx, score, bud[0], outs, args) if args.decode_steps > 0 else None
+    hidden = None if args.no_hidden_evict else hidden_leg(cfg, ctx, K, Q, args)
 
     cpu = None
     if not args.no_cpu_baseline:
@@ -175,10 +179,45 @@ def main():
                    "head_dim": D, "window": w, "pool": cfg.pool, "k_trunc": cfg.k_trunc,
                    "avg_budget": cfg.avg_budget, "mean_kept": round(kept, 1), "rho": round(kept / N, 5),
                    "head_tokens_per_s": round(value * L * H, 1)},
-        "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels, "decode": decode,
+        "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels, "decode": decode, "hidden_evict": hidden,
         "gen_seconds": round(t_gen, 1),
     }
     print(json.dumps(out))
+
+
+def hidden_leg(cfg, ctx, K, Q, args):
+    """Not part of `value`: one stage-1 hidden-state eviction (uncomp_hidden_evict) at a layer-group
+    boundary: the last token's attention over one layer's keys picks the N - 512 rows (Eq. 10 with the
+    paper's increment) of the [N, 4096] hidden states that enter the next group.  HBM-bound on the row
+    copy; reports per-kernel times and the rate on the bytes that must move."""
+    import torch
+    dev = K.device
+    B, H, N, D, G, w = cfg.B, cfg.H, cfg.N, cfg.D, cfg.G, cfg.w
+    Dm = 4096 if cfg.H * cfg.G * D <= 4096 else 8192                    # model width of the config's family
+    n_keep = max(N - 512, w + 1)
+    e = 2 if cfg.dtype == "bf16" else 4
+    g = torch.Generator(device=dev).manual_seed(args.seed + 404)
+    Hs = torch.randn(B, N, Dm, generator=g, device=dev, dtype=torch.float32).to(K.dtype)
+    q = Q[0][:, :, -1, :].contiguous()
+    nk = torch.tensor([n_keep], dtype=torch.int32, device=dev)
+    out = ctx.hidden_evict(q, K[0], G, nk, w, Hs, cap=n_keep)[:3]
+    torch.cuda.synchronize()
+    reps = 5
+    ctx.profile(True)
+    for _ in range(reps):
+        ctx.hidden_evict(q, K[0], G, nk, w, Hs, cap=n_keep, out=out)
+    torch.cuda.synchronize()
+    per = {}
+    for name, m in ctx.profile_read():
+        per.setdefault(name, []).append(m)
+    ctx.profile(False)
+    kern = {name: sum(v) / len(v) for name, v in per.items()}
+    total = sum(kern.values())
+    byt = B * (2 * H * N * D * e + 2 * n_keep * Dm * e)                 # keys twice (two scoring passes), rows in and out
+    return {"layer_tokens_in": N, "layer_tokens_out": n_keep, "hidden_width": Dm, "kernel_us": round(total * 1e3, 1),
+            "algorithmic_bytes": int(byt), "GBps": round(byt / total / 1e6, 1),
+            "hbm_frac": round(byt / total / 1e6 / HBM_PEAK_GBS, 4),
+            "kernels_us": {k: round(v * 1e3, 1) for k, v in kern.items()}}
 
 
 def decode_leg(cfg, ctx, score, head_budget, outs, args):
