@@ -24,11 +24,13 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
 MEASURED_TRAFFIC_BYTES = {
     "llama3-8b-128k": {
         "gram_mfma": int((8.000 + 0.126) * 2**30),
-        "score_stats_wave": int((8.134 + 0.016) * 2**30),
+        "score_stats_wave": int((8.133 + 0.016) * 2**30),
         "score_vote_wave": int((8.123 + 0.500) * 2**30),
         "score_pool": int((0.531 + 0.125) * 2**30),
         "select": int((0.532 + 0.002) * 2**30),
         "gather": int((0.256 + 0.250) * 2**30),
+        "decode_attend_wave": int((0.252 + 0.012) * 2**30),
+        "gather_rows": int((1.000 + 0.996) * 2**30),
     },
 }
 
@@ -64,7 +66,9 @@ def main():
     ap.add_argument("--config", type=int, default=3, help="index into BASELINE.json configs (default: the 128K prefill)")
     ap.add_argument("--seed", type=int, default=2410)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-overlap", action="store_true", help="keep every kernel on one stream")
+    ap.add_argument("--overlap", action="store_true",
+                    help="run the eigen stage and the budgets on the context's side stream beside the scoring kernels")
+    ap.add_argument("--no-overlap", action="store_true", help="(default) keep every kernel on one stream")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="also run one plain device copy of this many MiB (reference for HBM byte counters)")
     ap.add_argument("--cpu-heads", type=int, default=0, help="heads in the oracle sample (0 = auto)")
@@ -98,7 +102,7 @@ def main():
     if not args.no_hidden_evict:
         ws = max(ws, binding.Context.hidden_workspace_bytes(B, H, G, N, w))
     ctx = binding.Context(0, ws)
-    ctx.set_overlap(not args.no_overlap)
+    ctx.set_overlap(args.overlap and not args.no_overlap)
     i32 = dict(dtype=torch.int32, device=dev)
     ent = torch.empty(L, B, H, dtype=torch.float32, device=dev)
     bud = (torch.empty(L, B, H, **i32), torch.empty(L, B, H, **i32), torch.empty(L, **i32), torch.empty(L, **i32))
