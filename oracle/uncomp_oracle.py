@@ -36,6 +36,10 @@ Parity status of each function (what pins it lives in tests/test_oracle_*.py):
                     closed form (ties then keep the lowest positions); total mass = number
                     of query heads; a dominant key is always kept; exhaustive subset
                     search on tiny inputs; rows copied bit for bit.
+* prepare_* /       pinned: hand-worked two-sample example (mean and vote labellings that
+  budgets_from_     differ), one sample reproduces assign_budgets' groups, sample order
+  labels            does not matter, vote ties go to the lower label, budgets from labels
+                    equal the paper's printed budget vector.
 """
 from __future__ import annotations
 
@@ -354,3 +358,67 @@ def hidden_evict(q_last, K, Hs, n_keep: int, w: int, G: int):
         idx.append(sel)
         scores.append(sc)
     return np.stack(rows), np.stack(idx), np.stack(scores)
+
+
+# --------------------------------------------------------------------------
+# O7  offline preparation  (Sec. 3.3.1 "Preparation Stage", Eq. 7: the grouping
+#     metric of a head is its erank averaged over the d sampled prompts;
+#     App. "A Comprehensive Walk-Through", Alg. 1: per sample every head gets one
+#     of M labels from its entropy, the final label is the majority's)
+# --------------------------------------------------------------------------
+def _rank_groups(values: np.ndarray, M: int) -> np.ndarray:
+    """Group index of each of the H entries: rank by value, largest first, equal
+    values by lower index; rank r falls in group r // (H/M)."""
+    H = values.shape[0]
+    order = np.argsort(-np.asarray(values, dtype=np.float64), kind="stable")
+    group = np.empty(H, dtype=np.int32)
+    group[order] = np.arange(H) // (H // M)
+    return group
+
+
+def prepare_new(L: int, H: int, M: int) -> dict:
+    return {"erank_sum": np.zeros((L, H)), "votes": np.zeros((L, H, M), dtype=np.int64), "count": 0}
+
+
+def prepare_accumulate(state: dict, entropy: np.ndarray, M: int) -> None:
+    """Adds the B samples of entropy [L, B, H] to the running statistics: the sum of
+    erank = exp(entropy) per (layer, head) for Eq. 7, and one vote per sample for the
+    label the head gets inside its layer in that sample (Alg. 1; the labels are the
+    M equal-size rank groups of Sec. 3.3.3, the paper names no other clustering)."""
+    entropy = np.asarray(entropy)
+    L, B, H = entropy.shape
+    for b in range(B):
+        for l in range(L):
+            e = entropy[l, b].astype(np.float64)
+            state["erank_sum"][l] += np.exp(e)
+            g = _rank_groups(e, M)
+            for h in range(H):
+                state["votes"][l, h, g[h]] += 1
+        state["count"] += 1
+
+
+def prepare_finish(state: dict, M: int):
+    """Returns (labels_mean [L, H], labels_vote [L, H], mean_erank [L, H]).
+    labels_mean: heads of a layer ranked by their mean erank (Eq. 7) into M groups,
+    group 0 = largest.  labels_vote: the label most samples gave the head, equal
+    counts towards the lower label."""
+    mean = state["erank_sum"] / max(state["count"], 1)
+    L, H = mean.shape
+    labels_mean = np.stack([_rank_groups(mean[l], M) for l in range(L)])
+    labels_vote = np.zeros((L, H), dtype=np.int32)
+    for l in range(L):
+        for h in range(H):
+            best = 0
+            for g in range(1, M):
+                if state["votes"][l, h, g] > state["votes"][l, h, best]:
+                    best = g
+            labels_vote[l, h] = best
+    return labels_mean, labels_vote, mean
+
+
+def budgets_from_labels(labels: np.ndarray, B: int, n_max: int, step: int, N: int, w: int) -> np.ndarray:
+    """Eq. 11 from stored labels: head_budget[l, b, h] = clamp(n_max - label*step,
+    min(w, N), N), the same for every batch entry."""
+    labels = np.asarray(labels)
+    bud = np.clip(n_max - labels.astype(np.int64) * step, min(w, N), N).astype(np.int32)
+    return np.repeat(bud[:, None, :], B, axis=1)
