@@ -17,6 +17,11 @@
  *
  *   uncomp_hidden_evict    last-token attention -> top-N rows of the hidden states
  *
+ * and, before any inference, over a set of sampled prompts:
+ *
+ *   uncomp_prepare_*       running mean of erank and label votes per head -> group labels
+ *   uncomp_budgets_from_labels   per-head budgets from stored labels
+ *
  * Conventions that hold for every call:
  *   - Pointers named X, K, V, Qwin, *_out, entropy, score, budget are DEVICE pointers
  *     owned by the caller; the library never allocates, frees or keeps them.  The
@@ -262,6 +267,37 @@ uncomp_status uncomp_hidden_evict(uncomp_ctx* ctx, const void* q_last, const voi
                                   const void* Hs, const int64_t hs_strides[2], int Dm, int cap,
                                   void* Hs_out, int32_t* idx_out, int32_t* len_out,
                                   float* score_out, void* stream);
+
+/*
+ * Offline preparation (Sec. 3.3.1 "Preparation Stage", Eq. 7: a head's grouping metric is its
+ * erank_k averaged over the d sampled prompts; App. "A Comprehensive Walk-Through", Alg. 1: per
+ * sample every head gets one of M labels from its entropy, the final label is the majority's).
+ *
+ * The running statistics are DEVICE memory owned by the caller: erank_sum [n_layer][H] doubles,
+ * votes [n_layer][H][M] int32, count one int32.  uncomp_prepare_reset zeroes them.
+ * uncomp_prepare_accumulate adds the n_batch samples of entropy [n_layer][n_batch][H] (the layout
+ * uncomp_head_entropy is used with): erank_sum += exp(entropy) in double precision, samples in
+ * index order; per sample and layer the heads are ranked by entropy (larger first, equal values by
+ * lower head index), rank r votes for label r / (H/M); count += n_batch.
+ * uncomp_prepare_finish writes labels_mean [n_layer][H] (heads of a layer ranked by erank_sum /
+ * count into M groups, group 0 = largest) and labels_vote [n_layer][H] (the label with most votes,
+ * equal counts towards the lower label); mean_erank_out, if not NULL, gets the means as floats.
+ * uncomp_budgets_from_labels is Eq. 11 from stored labels:
+ * head_budget[l][b][h] = clamp(n_max - labels[l][h]*step, min(w, N), N), [n_layer][n_batch][H].
+ * Limits as for uncomp_assign_budgets: H <= 1024, n_layer <= 4096, M divides H.
+ */
+uncomp_status uncomp_prepare_reset(uncomp_ctx* ctx, int n_layer, int H, int M, double* erank_sum,
+                                   int32_t* votes, int32_t* count, void* stream);
+uncomp_status uncomp_prepare_accumulate(uncomp_ctx* ctx, const float* entropy, int n_layer,
+                                        int n_batch, int H, int M, double* erank_sum,
+                                        int32_t* votes, int32_t* count, void* stream);
+uncomp_status uncomp_prepare_finish(uncomp_ctx* ctx, int n_layer, int H, int M,
+                                    const double* erank_sum, const int32_t* votes,
+                                    const int32_t* count, int32_t* labels_mean,
+                                    int32_t* labels_vote, float* mean_erank_out, void* stream);
+uncomp_status uncomp_budgets_from_labels(uncomp_ctx* ctx, const int32_t* labels, int n_layer,
+                                         int n_batch, int H, int n_max, int step, int N, int w,
+                                         int32_t* head_budget, void* stream);
 
 #ifdef __cplusplus
 }

@@ -27,6 +27,7 @@ EXPORTS = (
     "uncomp_head_entropy", "uncomp_assign_budgets", "uncomp_window_score", "uncomp_select_gather",
     "uncomp_decode_init", "uncomp_decode_step", "uncomp_decode_workspace_bytes",
     "uncomp_hidden_evict", "uncomp_hidden_workspace_bytes",
+    "uncomp_prepare_reset", "uncomp_prepare_accumulate", "uncomp_prepare_finish", "uncomp_budgets_from_labels",
 )
 
 _lib = None
@@ -84,6 +85,14 @@ def load_library() -> ctypes.CDLL:
     lib.uncomp_decode_step.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, vp, vp, i32, i32,
                                        vp, vp, vp, vp, vp, vp, vp, vp]
     lib.uncomp_decode_step.restype = i32
+    lib.uncomp_prepare_reset.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp]
+    lib.uncomp_prepare_reset.restype = i32
+    lib.uncomp_prepare_accumulate.argtypes = [vp, vp, i32, i32, i32, i32, vp, vp, vp, vp]
+    lib.uncomp_prepare_accumulate.restype = i32
+    lib.uncomp_prepare_finish.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp]
+    lib.uncomp_prepare_finish.restype = i32
+    lib.uncomp_budgets_from_labels.argtypes = [vp, vp, i32, i32, i32, i32, i32, i32, i32, vp, vp]
+    lib.uncomp_budgets_from_labels.restype = i32
     lib.uncomp_hidden_workspace_bytes.argtypes = [i32] * 5
     lib.uncomp_hidden_workspace_bytes.restype = c.c_size_t
     lib.uncomp_hidden_evict.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, i32, c.POINTER(i64), vp, i32,
@@ -310,3 +319,41 @@ class Context:
             n_keep.data_ptr(), int(w), _ptr(Hs), hs, Dm, int(cap), _ptr(Ho), idx.data_ptr(), ln.data_ptr(),
             _ptr(score), _stream()))
         return Ho, idx, ln, score
+
+    # -- offline preparation ------------------------------------------------------------------
+    def prepare_new(self, L: int, H: int, M: int, device="cuda:0"):
+        """Fresh running statistics: (erank_sum [L,H] float64, votes [L,H,M] int32, count [1] int32)."""
+        st = (torch.empty(L, H, dtype=torch.float64, device=device), torch.empty(L, H, M, dtype=torch.int32, device=device),
+              torch.empty(1, dtype=torch.int32, device=device))
+        self._check(self.lib.uncomp_prepare_reset(self.handle, L, H, M, st[0].data_ptr(), st[1].data_ptr(),
+                                                  st[2].data_ptr(), _stream()))
+        return st
+
+    def prepare_accumulate(self, state, entropy: torch.Tensor):
+        """entropy [L, B, H] float32 contiguous: adds its B samples to the statistics."""
+        L, B, H = entropy.shape
+        es, votes, count = state
+        assert entropy.is_contiguous() and entropy.dtype == torch.float32 and es.shape == (L, H)
+        self._check(self.lib.uncomp_prepare_accumulate(self.handle, entropy.data_ptr(), L, B, H, votes.shape[2],
+                                                       es.data_ptr(), votes.data_ptr(), count.data_ptr(), _stream()))
+
+    def prepare_finish(self, state, want_mean: bool = False):
+        """Returns labels_mean, labels_vote [L,H] int32 (and the mean erank [L,H] float32)."""
+        es, votes, count = state
+        L, H, M = votes.shape
+        lm = torch.empty(L, H, dtype=torch.int32, device=es.device)
+        lv = torch.empty_like(lm)
+        mean = torch.empty(L, H, dtype=torch.float32, device=es.device) if want_mean else None
+        self._check(self.lib.uncomp_prepare_finish(self.handle, L, H, M, es.data_ptr(), votes.data_ptr(),
+                                                   count.data_ptr(), lm.data_ptr(), lv.data_ptr(), _ptr(mean), _stream()))
+        return (lm, lv, mean) if want_mean else (lm, lv)
+
+    def budgets_from_labels(self, labels: torch.Tensor, B: int, n_max: int, step: int, N: int, w: int, out=None):
+        """labels [L,H] int32 -> head_budget [L,B,H] int32."""
+        L, H = labels.shape
+        assert labels.is_contiguous() and labels.dtype == torch.int32
+        if out is None:
+            out = torch.empty(L, B, H, dtype=torch.int32, device=labels.device)
+        self._check(self.lib.uncomp_budgets_from_labels(self.handle, labels.data_ptr(), L, int(B), H, int(n_max),
+                                                        int(step), int(N), int(w), out.data_ptr(), _stream()))
+        return out

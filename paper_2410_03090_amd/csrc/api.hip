@@ -341,6 +341,75 @@ uncomp_status uncomp_hidden_evict(uncomp_ctx* ctx, const void* q_last, const voi
     return UNCOMP_OK;
 }
 
+namespace {
+uncomp_status check_prepare_dims(uncomp_ctx* ctx, const char* who, int L, int H, int M) {
+    if (L <= 0 || H <= 0) return fail(ctx, UNCOMP_ERR_INVALID_ARG, "%s: sizes must be positive", who);
+    if (H > 1024 || L > 4096) return fail(ctx, UNCOMP_ERR_UNSUPPORTED, "%s: H <= 1024, n_layer <= 4096", who);
+    if (M < 1 || H % M != 0) return fail(ctx, UNCOMP_ERR_UNSUPPORTED, "%s: M must divide H", who);
+    return UNCOMP_OK;
+}
+}  // namespace
+
+uncomp_status uncomp_prepare_reset(uncomp_ctx* ctx, int n_layer, int H, int M, double* erank_sum, int32_t* votes,
+                                   int32_t* count, void* stream) {
+    if (ctx == nullptr) return UNCOMP_ERR_INVALID_ARG;
+    if (erank_sum == nullptr || votes == nullptr || count == nullptr)
+        return fail(ctx, UNCOMP_ERR_INVALID_ARG, "prepare_reset: null pointer");
+    uncomp_status st = check_prepare_dims(ctx, "prepare_reset", n_layer, H, M);
+    if (st != UNCOMP_OK) return st;
+    hipError_t e = launch_prepare_reset(n_layer, H, M, erank_sum, votes, count,
+                                        Env{static_cast<hipStream_t>(stream), &ctx->prof, ctx->force_alu});
+    if (e != hipSuccess) return hip_fail(ctx, e, "prepare_reset: launch");
+    return UNCOMP_OK;
+}
+
+uncomp_status uncomp_prepare_accumulate(uncomp_ctx* ctx, const float* entropy, int n_layer, int n_batch, int H, int M,
+                                        double* erank_sum, int32_t* votes, int32_t* count, void* stream) {
+    if (ctx == nullptr) return UNCOMP_ERR_INVALID_ARG;
+    if (entropy == nullptr || erank_sum == nullptr || votes == nullptr || count == nullptr)
+        return fail(ctx, UNCOMP_ERR_INVALID_ARG, "prepare_accumulate: null pointer");
+    if (n_batch <= 0) return fail(ctx, UNCOMP_ERR_INVALID_ARG, "prepare_accumulate: sizes must be positive");
+    uncomp_status st = check_prepare_dims(ctx, "prepare_accumulate", n_layer, H, M);
+    if (st != UNCOMP_OK) return st;
+    // in overlap mode the entropies may still be under way on the side stream
+    st = uncomp_join(ctx, stream);
+    if (st != UNCOMP_OK) return st;
+    hipError_t e = launch_prepare_accumulate(entropy, n_layer, n_batch, H, M, erank_sum, votes, count,
+                                             Env{static_cast<hipStream_t>(stream), &ctx->prof, ctx->force_alu});
+    if (e != hipSuccess) return hip_fail(ctx, e, "prepare_accumulate: launch");
+    return UNCOMP_OK;
+}
+
+uncomp_status uncomp_prepare_finish(uncomp_ctx* ctx, int n_layer, int H, int M, const double* erank_sum,
+                                    const int32_t* votes, const int32_t* count, int32_t* labels_mean,
+                                    int32_t* labels_vote, float* mean_erank_out, void* stream) {
+    if (ctx == nullptr) return UNCOMP_ERR_INVALID_ARG;
+    if (erank_sum == nullptr || votes == nullptr || count == nullptr || labels_mean == nullptr ||
+        labels_vote == nullptr)
+        return fail(ctx, UNCOMP_ERR_INVALID_ARG, "prepare_finish: null pointer");
+    uncomp_status st = check_prepare_dims(ctx, "prepare_finish", n_layer, H, M);
+    if (st != UNCOMP_OK) return st;
+    hipError_t e = launch_prepare_finish(n_layer, H, M, erank_sum, votes, count, labels_mean, labels_vote,
+                                         mean_erank_out, Env{static_cast<hipStream_t>(stream), &ctx->prof, ctx->force_alu});
+    if (e != hipSuccess) return hip_fail(ctx, e, "prepare_finish: launch");
+    return UNCOMP_OK;
+}
+
+uncomp_status uncomp_budgets_from_labels(uncomp_ctx* ctx, const int32_t* labels, int n_layer, int n_batch, int H,
+                                         int n_max, int step, int N, int w, int32_t* head_budget, void* stream) {
+    if (ctx == nullptr) return UNCOMP_ERR_INVALID_ARG;
+    if (labels == nullptr || head_budget == nullptr)
+        return fail(ctx, UNCOMP_ERR_INVALID_ARG, "budgets_from_labels: null pointer");
+    if (n_layer <= 0 || n_batch <= 0 || H <= 0 || N <= 0)
+        return fail(ctx, UNCOMP_ERR_INVALID_ARG, "budgets_from_labels: sizes must be positive");
+    if (w <= 0 || w >= N) return fail(ctx, UNCOMP_ERR_UNSUPPORTED, "budgets_from_labels: need 0 < w < N");
+    if (step < 0 || n_max < 0) return fail(ctx, UNCOMP_ERR_INVALID_ARG, "budgets_from_labels: negative n_max or step");
+    hipError_t e = launch_labels_to_budget(labels, n_layer, n_batch, H, n_max, step, N, w, head_budget,
+                                           Env{static_cast<hipStream_t>(stream), &ctx->prof, ctx->force_alu});
+    if (e != hipSuccess) return hip_fail(ctx, e, "budgets_from_labels: launch");
+    return UNCOMP_OK;
+}
+
 size_t uncomp_decode_workspace_bytes(int n_heads, int G, int cap) {
     if (n_heads <= 0 || G <= 0 || cap <= 0) return 0;
     return plan_decode(n_heads, G, cap).bytes;

@@ -117,6 +117,15 @@ hipError_t launch_gather_rows(const void* src, const int32_t* idx, const int32_t
                               int row_bytes, int64_t group_stride_bytes, int64_t row_stride_bytes, void* dst,
                               const Env& env);
 hipError_t launch_head_sum(const float* score, int B, int H, int P_in, int P_out, float* out, const Env& env);
+hipError_t launch_prepare_reset(int L, int H, int M, double* erank_sum, int32_t* votes, int32_t* count,
+                                const Env& env);
+hipError_t launch_prepare_accumulate(const float* entropy, int L, int B, int H, int M, double* erank_sum,
+                                     int32_t* votes, int32_t* count, const Env& env);
+hipError_t launch_prepare_finish(int L, int H, int M, const double* erank_sum, const int32_t* votes,
+                                 const int32_t* count, int32_t* labels_mean, int32_t* labels_vote, float* mean_out,
+                                 const Env& env);
+hipError_t launch_labels_to_budget(const int32_t* labels, int L, int B, int H, int n_max, int step, int N, int w,
+                                   int32_t* head_budget, const Env& env);
 // Workspace of the bf16 decode path (two kernels per step).
 struct DecodePlan {
     int GT;              // query heads per KV head rounded up to 4, 8 or 16
