@@ -72,6 +72,7 @@ def main():
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="also run one plain device copy of this many MiB (reference for HBM byte counters)")
     ap.add_argument("--cpu-heads", type=int, default=0, help="heads in the oracle sample (0 = auto)")
+    ap.add_argument("--no-prepare", action="store_true", help="skip the offline-preparation leg")
     ap.add_argument("--no-hidden-evict", action="store_true", help="skip the stage-1 hidden-state eviction leg")
     ap.add_argument("--decode-steps", type=int, default=64,
                     help="generated tokens to run through uncomp_decode_step after the timed prefill steps (0 = skip)")
@@ -168,6 +169,7 @@ def main():
 
     decode = decode_leg(cfg, ctx, score, bud[0], outs, args) if args.decode_steps > 0 else None
     hidden = None if args.no_hidden_evict else hidden_leg(cfg, ctx, K, Q, args)
+    prepare = None if args.no_prepare else prepare_leg(cfg, ctx, Kf, ent, args)
 
     cpu = None
     if not args.no_cpu_baseline:
@@ -183,10 +185,37 @@ def main():
                    "head_dim": D, "window": w, "pool": cfg.pool, "k_trunc": cfg.k_trunc,
                    "avg_budget": cfg.avg_budget, "mean_kept": round(kept, 1), "rho": round(kept / N, 5),
                    "head_tokens_per_s": round(value * L * H, 1)},
-        "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels, "decode": decode, "hidden_evict": hidden,
+        "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels, "decode": decode, "hidden_evict": hidden, "prepare": prepare,
         "gen_seconds": round(t_gen, 1),
     }
     print(json.dumps(out))
+
+
+def prepare_leg(cfg, ctx, Kf, ent, args):
+    """Not part of `value`: the offline preparation (Eq. 7 / Alg. 1).  Every sampled prompt costs one
+    entropy pass over all its layers plus the accumulation of the statistics; the resident prompt stands
+    for each of the samples.  Reports prompts per second at this sequence length."""
+    import torch
+    L, B, H, N, D = cfg.L, cfg.B, cfg.H, cfg.N, cfg.D
+    st = ctx.prepare_new(L, H, cfg.M)
+    reps = 4
+    X = Kf.reshape(L * B * H, N, D)
+
+    def one():
+        ctx.head_entropy(X, k_trunc=cfg.k_trunc, entropy_out=ent.reshape(-1))
+        ctx.prepare_accumulate(st, ent)
+
+    one()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        one()
+    labels = ctx.prepare_finish(st)
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / reps
+    groups = torch.bincount(labels[0].reshape(-1).long(), minlength=cfg.M).tolist()
+    return {"ms_per_batch_of_prompts": round(dt * 1e3, 3), "prompts_per_s": round(B / dt, 1), "seq_len": N,
+            "samples_accumulated": int(st[2][0]), "heads_per_group": groups}
 
 
 def hidden_leg(cfg, ctx, K, Q, args):
