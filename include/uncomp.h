@@ -136,6 +136,24 @@ uncomp_status uncomp_head_entropy(uncomp_ctx* ctx, const void* X, uncomp_dtype d
                                   float* entropy_out, float* eig_out, void* stream);
 
 /*
+ * Truncated matrix entropy of wide token matrices (same definition as uncomp_head_entropy, for
+ * D = 256 ... 16384 in multiples of 128: e.g. the hidden states H_m of Sec. 3.3.2, whose erank
+ * the paper's layer analysis plots).  The D x D covariance is never formed: the k_trunc <= 128
+ * largest eigenvalues are taken as the Ritz values of a 128-dimensional subspace after n_iter
+ * rounds of block power iteration (each round reads X twice).  Their error falls like
+ * (sigma_129 / sigma_k)^(2 n_iter): a few rounds when the spectrum drops before the 129th
+ * eigenvalue, many when it is flat there.  entropy_out [n_mat]; eig_out, if not NULL, receives
+ * the 128 Ritz values of each matrix as shares of the full trace, descending ([n_mat][128]).
+ * X as in uncomp_head_entropy (any ldx >= D; no alignment beyond the element's).  Matrices are
+ * processed one after the other.  Workspace: uncomp_matrix_workspace_bytes(N, D).
+ */
+size_t uncomp_matrix_workspace_bytes(int N, int D);
+uncomp_status uncomp_matrix_entropy(uncomp_ctx* ctx, const void* X, uncomp_dtype dtype,
+                                    int n_mat, int N, int D, int64_t mat_stride, int64_t ldx,
+                                    int k_trunc, unsigned flags, int n_iter,
+                                    float* entropy_out, float* eig_out, void* stream);
+
+/*
  * Budgets from entropies (Sec. 3.3.3 "Design", Eq. 11; Sec. 3.3.2 Eq. 8-10).
  *
  * entropy is [n_layer][n_batch][H] floats.  Per (layer, batch): heads are ranked by entropy,

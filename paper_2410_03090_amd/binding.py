@@ -27,6 +27,7 @@ EXPORTS = (
     "uncomp_head_entropy", "uncomp_assign_budgets", "uncomp_window_score", "uncomp_select_gather",
     "uncomp_decode_init", "uncomp_decode_step", "uncomp_decode_workspace_bytes",
     "uncomp_hidden_evict", "uncomp_hidden_workspace_bytes",
+    "uncomp_matrix_entropy", "uncomp_matrix_workspace_bytes",
     "uncomp_prepare_reset", "uncomp_prepare_accumulate", "uncomp_prepare_finish", "uncomp_budgets_from_labels",
 )
 
@@ -85,6 +86,10 @@ def load_library() -> ctypes.CDLL:
     lib.uncomp_decode_step.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, vp, vp, i32, i32,
                                        vp, vp, vp, vp, vp, vp, vp, vp]
     lib.uncomp_decode_step.restype = i32
+    lib.uncomp_matrix_workspace_bytes.argtypes = [i32, i32]
+    lib.uncomp_matrix_workspace_bytes.restype = c.c_size_t
+    lib.uncomp_matrix_entropy.argtypes = [vp, vp, i32, i32, i32, i32, i64, i64, i32, u32, i32, vp, vp, vp]
+    lib.uncomp_matrix_entropy.restype = i32
     lib.uncomp_prepare_reset.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp]
     lib.uncomp_prepare_reset.restype = i32
     lib.uncomp_prepare_accumulate.argtypes = [vp, vp, i32, i32, i32, i32, vp, vp, vp, vp]
@@ -143,6 +148,10 @@ class Context:
     @staticmethod
     def hidden_workspace_bytes(B: int, H: int, G: int, N: int, w: int) -> int:
         return int(load_library().uncomp_hidden_workspace_bytes(B, H, G, N, w))
+
+    @staticmethod
+    def matrix_workspace_bytes(N: int, D: int) -> int:
+        return int(load_library().uncomp_matrix_workspace_bytes(N, D))
 
     def close(self):
         if getattr(self, "handle", None) is not None and self.handle:
@@ -357,3 +366,17 @@ class Context:
         self._check(self.lib.uncomp_budgets_from_labels(self.handle, labels.data_ptr(), L, int(B), H, int(n_max),
                                                         int(step), int(N), int(w), out.data_ptr(), _stream()))
         return out
+
+    # -- entropy of wide token matrices --------------------------------------------------------
+    def matrix_entropy(self, X: torch.Tensor, k_trunc: int = 32, flags: int = DEFAULT_FLAGS, n_iter: int = 8,
+                       want_eig: bool = False):
+        """X [n_mat, N, D] (last dim contiguous), D a multiple of 128 above 128.
+        Returns entropy [n_mat] (and the 128 Ritz values [n_mat, 128] as shares of the trace)."""
+        n_mat, N, D = X.shape
+        assert X.stride(2) == 1
+        ent = torch.empty(n_mat, dtype=torch.float32, device=X.device)
+        eig = torch.empty(n_mat, 128, dtype=torch.float32, device=X.device) if want_eig else None
+        self._check(self.lib.uncomp_matrix_entropy(
+            self.handle, X.data_ptr(), _dtype_code(X), n_mat, N, D, X.stride(0), X.stride(1), int(k_trunc), int(flags),
+            int(n_iter), ent.data_ptr(), _ptr(eig), _stream()))
+        return (ent, eig) if want_eig else ent

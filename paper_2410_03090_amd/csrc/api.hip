@@ -287,6 +287,38 @@ HiddenPlan plan_hidden(int B, int H, int G, int N, int w) {
 }
 }  // namespace
 
+size_t uncomp_matrix_workspace_bytes(int N, int D) {
+    if (N <= 0 || D <= 0 || D % kD != 0) return 0;
+    return kBudgetScratch + plan_matrix(N, D).bytes;
+}
+
+uncomp_status uncomp_matrix_entropy(uncomp_ctx* ctx, const void* X, uncomp_dtype dtype, int n_mat, int N, int D,
+                                    int64_t mat_stride, int64_t ldx, int k_trunc, unsigned flags, int n_iter,
+                                    float* entropy_out, float* eig_out, void* stream) {
+    if (ctx == nullptr) return UNCOMP_ERR_INVALID_ARG;
+    if (X == nullptr || entropy_out == nullptr) return fail(ctx, UNCOMP_ERR_INVALID_ARG, "matrix_entropy: null pointer");
+    if (n_mat <= 0 || N <= 0) return fail(ctx, UNCOMP_ERR_INVALID_ARG, "matrix_entropy: n_mat and N must be positive");
+    if (dtype != UNCOMP_BF16 && dtype != UNCOMP_F32) return fail(ctx, UNCOMP_ERR_UNSUPPORTED, "matrix_entropy: dtype");
+    if (D < 2 * kD || D > 16384 || D % kD != 0)
+        return fail(ctx, UNCOMP_ERR_UNSUPPORTED, "matrix_entropy: D must be a multiple of 128 in [256, 16384]");
+    if (k_trunc < 1 || k_trunc > kD) return fail(ctx, UNCOMP_ERR_UNSUPPORTED, "matrix_entropy: need 1 <= k_trunc <= 128");
+    if (n_iter < 1 || n_iter > 1000) return fail(ctx, UNCOMP_ERR_INVALID_ARG, "matrix_entropy: need 1 <= n_iter <= 1000");
+    if (flags & ~(UNCOMP_CENTER | UNCOMP_TRUNC_RENORM | UNCOMP_LAYER_DELTA_INCREASE))
+        return fail(ctx, UNCOMP_ERR_UNSUPPORTED, "matrix_entropy: unknown flag bits");
+    if (ldx < D || mat_stride < 0) return fail(ctx, UNCOMP_ERR_INVALID_ARG, "matrix_entropy: ldx >= D, mat_stride >= 0");
+    const MatrixPlan p = plan_matrix(N, D);
+    if (kBudgetScratch + p.bytes > ctx->ws_bytes)
+        return fail(ctx, UNCOMP_ERR_WORKSPACE, "matrix_entropy: needs %zu workspace bytes, context has %zu",
+                    kBudgetScratch + p.bytes, ctx->ws_bytes);
+    uncomp_status js = uncomp_join(ctx, stream);
+    if (js != UNCOMP_OK) return js;
+    hipError_t e = launch_matrix_entropy(X, dtype, n_mat, N, D, mat_stride, ldx, k_trunc, flags, n_iter, p,
+                                         ctx->ws + kBudgetScratch, entropy_out, eig_out,
+                                         Env{static_cast<hipStream_t>(stream), &ctx->prof, ctx->force_alu});
+    if (e != hipSuccess) return hip_fail(ctx, e, "matrix_entropy: launch");
+    return UNCOMP_OK;
+}
+
 size_t uncomp_hidden_workspace_bytes(int B, int H, int G, int N, int w) {
     if (B <= 0 || H <= 0 || G <= 0 || N < 2 || w < 1 || w >= N) return 0;
     return plan_hidden(B, H, G, N, w).bytes;

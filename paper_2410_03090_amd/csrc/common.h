@@ -97,9 +97,12 @@ hipError_t launch_gram(const void* X, uncomp_dtype dt, int n_mat, int N, int64_t
 hipError_t launch_jacobi_entropy(int n_mat, int N, int k_trunc, unsigned flags,
                                  const EntropyPlan& p, char* ws, float* entropy_out,
                                  float* eig_out, const Env& env);
+// trace_total: optional DEVICE pointer to two doubles, the raw (unnormalised) centred and
+// uncentred traces of the larger matrix that the one handed in is a projection of: Eq. 5 without
+// renormalisation divides by the one that applies, and a larger matrix without spread gives 0.
 hipError_t launch_tridiag_entropy(int n_mat, int N, int k_trunc, unsigned flags,
                                   const EntropyPlan& p, char* ws, float* entropy_out,
-                                  float* eig_out, const Env& env);
+                                  float* eig_out, const Env& env, const double* trace_total = nullptr);
 hipError_t launch_budgets(const float* entropy, int L, int B, int H, int M, int n_max, int step,
                           int N, int w, float eps, int delta_n, unsigned flags,
                           int32_t* head_budget, int32_t* head_group, int32_t* layer_group,
@@ -126,6 +129,19 @@ hipError_t launch_prepare_finish(int L, int H, int M, const double* erank_sum, c
                                  const Env& env);
 hipError_t launch_labels_to_budget(const int32_t* labels, int L, int B, int H, int n_max, int step, int N, int w,
                                    int32_t* head_budget, const Env& env);
+// Workspace of the wide-matrix entropy (one matrix at a time).
+struct MatrixPlan {
+    int stat_chunks, stat_chunk;     // token chunks of the column statistics
+    int w_chunks, w_chunk;           // token chunks of W = X^T Z
+    int gram_slices;                 // row slices of the fp64 Gram of W
+    EntropyPlan ep;                  // the 128-wide entropy path on the projected tokens
+    size_t ep_off, statpart_off, s_off, trace_off, zsum_off, q_off, w_off, wpart_off, z_off, gpart_off, rinv_off;
+    size_t bytes;
+};
+MatrixPlan plan_matrix(int N, int D);
+hipError_t launch_matrix_entropy(const void* X, uncomp_dtype dt, int n_mat, int N, int D, int64_t mat_stride,
+                                 int64_t ldx, int k_trunc, unsigned flags, int n_iter, const MatrixPlan& p, char* ws,
+                                 float* entropy_out, float* eig_out, const Env& env);
 // Workspace of the bf16 decode path (two kernels per step).
 struct DecodePlan {
     int GT;              // query heads per KV head rounded up to 4, 8 or 16

@@ -1,0 +1,404 @@
+// Truncated matrix entropy of wide token matrices (Sec. 3.1 Eq. 1, Lemma 2; Sec. 3.2 Eq. 5-6 for
+// D = 256 ... 8192, e.g. the hidden states H_m of Sec. 3.3.2) without ever forming the D x D
+// covariance: only its k largest eigenvalues enter Eq. 5, and those are the Ritz values of a
+// 128-dimensional subspace that block power iteration drives onto the dominant eigenvectors.
+//
+//   x_bar = mean token, C = sum_t (x_t - x_bar)(x_t - x_bar)^T            (never stored)
+//   Q_0   = fixed pseudo-random D x 128 block, orthonormalised
+//   repeat:  Z = X Q  (N x 128),  W = C Q = X^T Z - s (s^T Q)/N  (D x 128),  Q = orth(W)
+//   end:     Z = X Q;  the centred covariance of the N projected tokens z_t is Q^T C Q, whose
+//            eigenvalues (the ordinary 128-wide entropy path) are the Ritz values; Eq. 5 without
+//            renormalisation divides them by trace(C), which one pass over X provides.
+//
+// Every iteration reads X twice (HBM-bound: 2 N D e bytes) and costs 4 N D 128 flops; forming C
+// would cost 2 N D^2.  orth() is a Cholesky QR with the 128 x 128 Gram of W accumulated in fp64;
+// a pivot that vanishes (rank below 128) retires its column.  Convergence of the k-th value goes
+// with (lambda_129 / lambda_k)^(2 iterations): fast when the spectrum falls off before the 129th
+// eigenvalue, as it does for the matrices the method looks at (that fall-off is the paper's point).
+#include "common.h"
+#include "device_utils.h"
+
+namespace uncomp {
+
+namespace {
+
+constexpr int kP = 128;                  // width of the iterated block
+
+__device__ __forceinline__ float elem(const bf16_bits* p) { return bf16_to_f32(*p); }
+__device__ __forceinline__ float elem(const float* p) { return *p; }
+
+// splitmix-style hash -> value in [-1, 1): the start block must be the same on every run
+__device__ __forceinline__ float start_value(uint32_t d, uint32_t j) {
+    uint64_t z = ((uint64_t)d << 32 | j) + 0x9E3779B97F4A7C15ull;
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    z ^= z >> 31;
+    return (float)((double)(z >> 11) * (2.0 / 9007199254740992.0) - 1.0);
+}
+
+}  // namespace
+
+__global__ __launch_bounds__(256) void sub_start_kernel(float* __restrict__ W, int D) {
+    const int e = blockIdx.x * 256 + threadIdx.x;
+    if (e < D * kP) W[e] = start_value((uint32_t)(e / kP), (uint32_t)(e % kP));
+}
+
+// Column sums and sums of squares of X over a chunk of tokens, in fp64: part[chunk][2][D].
+template <typename T>
+__global__ __launch_bounds__(256) void sub_colstats_kernel(const T* __restrict__ X, int N, int D, int64_t ldx,
+                                                           int chunk, double* __restrict__ part) {
+    const int d = blockIdx.x * 256 + threadIdx.x;
+    const int c = blockIdx.y;
+    if (d >= D) return;
+    const int t0 = c * chunk, t1 = min(N, t0 + chunk);
+    double s = 0.0, q = 0.0;
+    for (int t = t0; t < t1; ++t) {
+        const double v = (double)elem(X + (int64_t)t * ldx + d);
+        s += v;
+        q += v * v;
+    }
+    part[((int64_t)c * 2 + 0) * D + d] = s;
+    part[((int64_t)c * 2 + 1) * D + d] = q;
+}
+
+// s[d] = sum over chunks; trace[0] = sum_d (q_d - s_d^2 / N), trace[1] = sum_d q_d.  One workgroup.
+__global__ __launch_bounds__(256) void sub_colstats_finish_kernel(const double* __restrict__ part, int n_chunks, int D,
+                                                                  int N, double* __restrict__ s,
+                                                                  double* __restrict__ trace) {
+    __shared__ double red[2][4];
+    double tc = 0.0, tu = 0.0;
+    for (int d = threadIdx.x; d < D; d += 256) {
+        double a = 0.0, q = 0.0;
+        for (int c = 0; c < n_chunks; ++c) {
+            a += part[((int64_t)c * 2 + 0) * D + d];
+            q += part[((int64_t)c * 2 + 1) * D + d];
+        }
+        s[d] = a;
+        tc += q - a * a / (double)N;
+        tu += q;
+    }
+    tc = wave_sum(tc);
+    tu = wave_sum(tu);
+    if ((threadIdx.x & 63) == 0) {
+        red[0][threadIdx.x >> 6] = tc;
+        red[1][threadIdx.x >> 6] = tu;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        trace[0] = (red[0][0] + red[0][1]) + (red[0][2] + red[0][3]);
+        trace[1] = (red[1][0] + red[1][1]) + (red[1][2] + red[1][3]);
+    }
+}
+
+// Tall-skinny product with 128 output columns, fp32 accumulation on the plain ALUs.
+//   A_KM == false:  out[m][j] = sum_k A[m][k] B[k][j]      (A is M x K, row stride lda)       Z = X Q
+//   A_KM == true :  out[m][j] = sum_k A[k][m] B[k][j]      (A is K x M, row stride lda)       W = X^T Z
+// blockIdx.x: 64 rows of the output, blockIdx.y: a chunk of k (partial results out[chunk][M][128]).
+// B is fp32, K x 128, row stride 128.  A workgroup stages 16 k at a time in LDS; a thread owns
+// 4 rows x 8 columns.
+template <typename T, bool A_KM>
+__global__ __launch_bounds__(256) void sub_gemm_kernel(const T* __restrict__ A, int64_t lda, const float* __restrict__ B,
+                                                       int M, int K, int k_chunk, float* __restrict__ out) {
+    __shared__ float As[16][64 + 4];
+    __shared__ __align__(16) float Bs[16][kP];
+    const int m0 = blockIdx.x * 64;
+    const int kc = blockIdx.y;
+    const int k_begin = kc * k_chunk, k_end = min(K, k_begin + k_chunk);
+    const int tid = threadIdx.x, ty = tid >> 4, tx = tid & 15;
+    float acc[4][8];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[i][j] = 0.f;
+    for (int k0 = k_begin; k0 < k_end; k0 += 16) {
+        // stage A: 64 rows x 16 k (four elements per thread)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int idx = tid + 256 * e;
+            int m, k;
+            if (A_KM) {
+                m = idx & 63;
+                k = idx >> 6;
+            } else {
+                k = idx & 15;
+                m = idx >> 4;
+            }
+            float v = 0.f;
+            if (m0 + m < M && k0 + k < k_end)
+                v = A_KM ? elem(A + (int64_t)(k0 + k) * lda + m0 + m) : elem(A + (int64_t)(m0 + m) * lda + k0 + k);
+            As[k][m] = v;
+        }
+        // stage B: 16 k x 128 (eight floats per thread)
+        {
+            const int k = tid >> 4, j = (tid & 15) * 8;
+            float4 b0 = make_float4(0.f, 0.f, 0.f, 0.f), b1 = b0;
+            if (k0 + k < k_end) {
+                b0 = *reinterpret_cast<const float4*>(B + (int64_t)(k0 + k) * kP + j);
+                b1 = *reinterpret_cast<const float4*>(B + (int64_t)(k0 + k) * kP + j + 4);
+            }
+            *reinterpret_cast<float4*>(&Bs[k][j]) = b0;
+            *reinterpret_cast<float4*>(&Bs[k][j + 4]) = b1;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int k = 0; k < 16; ++k) {
+            float a[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) a[i] = As[k][4 * ty + i];
+            const float4 b0 = *reinterpret_cast<const float4*>(&Bs[k][8 * tx]);
+            const float4 b1 = *reinterpret_cast<const float4*>(&Bs[k][8 * tx + 4]);
+            const float b[8] = {b0.x, b0.y, b0.z, b0.w, b1.x, b1.y, b1.z, b1.w};
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 8; ++j) acc[i][j] = fmaf(a[i], b[j], acc[i][j]);
+        }
+        __syncthreads();
+    }
+    float* o = out + (int64_t)kc * M * kP;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int m = m0 + 4 * ty + i;
+        if (m < M) {
+            *reinterpret_cast<float4*>(o + (int64_t)m * kP + 8 * tx) = make_float4(acc[i][0], acc[i][1], acc[i][2], acc[i][3]);
+            *reinterpret_cast<float4*>(o + (int64_t)m * kP + 8 * tx + 4) = make_float4(acc[i][4], acc[i][5], acc[i][6], acc[i][7]);
+        }
+    }
+}
+
+// zsum[j] = sum_d s[d] Q[d][j] (= column sums of Z = X Q), fp64.  One workgroup of 128 threads.
+__global__ __launch_bounds__(128) void sub_zsum_kernel(const double* __restrict__ s, const float* __restrict__ Q, int D,
+                                                       double* __restrict__ zsum) {
+    const int j = threadIdx.x;
+    double a = 0.0;
+    for (int d = 0; d < D; ++d) a += s[d] * (double)Q[(int64_t)d * kP + j];
+    zsum[j] = a;
+}
+
+// W[d][j] = sum over chunks of part[c][d][j] - s[d] zsum[j] / N   (the mean correction of C Q)
+__global__ __launch_bounds__(256) void sub_reduce_kernel(const float* __restrict__ part, int n_chunks, int D,
+                                                         const double* __restrict__ s, const double* __restrict__ zsum,
+                                                         double inv_n, float* __restrict__ W) {
+    const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (e >= (int64_t)D * kP) return;
+    double a = 0.0;
+    for (int c = 0; c < n_chunks; ++c) a += (double)part[(int64_t)c * D * kP + e];
+    if (s != nullptr) a -= s[e / kP] * zsum[e % kP] * inv_n;
+    W[e] = (float)a;
+}
+
+// Partial Gram of W (D x 128, fp32) in fp64 over a slice of rows: gpart[slice][128][128].
+// Thread (ty, tx) owns the 8 x 8 block of entries (8 ty + i, 8 tx + j).
+__global__ __launch_bounds__(256) void sub_gram64_kernel(const float* __restrict__ W, int D, int rows_per_slice,
+                                                         double* __restrict__ gpart) {
+    __shared__ float rowbuf[8][kP];
+    const int tid = threadIdx.x, ty = tid >> 4, tx = tid & 15;
+    const int r0 = blockIdx.x * rows_per_slice, r1 = min(D, r0 + rows_per_slice);
+    double acc[8][8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[i][j] = 0.0;
+    for (int r = r0; r < r1; r += 8) {
+        for (int e = tid; e < 8 * kP; e += 256) {
+            const int rr = e >> 7, j = e & 127;
+            rowbuf[rr][j] = r + rr < r1 ? W[(int64_t)(r + rr) * kP + j] : 0.f;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int rr = 0; rr < 8; ++rr) {
+            double a[8], b[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                a[i] = (double)rowbuf[rr][8 * ty + i];
+                b[i] = (double)rowbuf[rr][8 * tx + i];
+            }
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+#pragma unroll
+                for (int j = 0; j < 8; ++j) acc[i][j] = fma(a[i], b[j], acc[i][j]);
+        }
+        __syncthreads();
+    }
+    double* o = gpart + (int64_t)blockIdx.x * kP * kP;
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) o[(8 * ty + i) * kP + 8 * tx + j] = acc[i][j];
+}
+
+// One workgroup: G = sum of the slices, Cholesky G = L L^T in LDS (fp64), then Rinv = L^-T as fp32
+// so that Q = W Rinv has orthonormal columns.  A pivot below 1e-12 of the largest diagonal entry
+// retires its column (its row and column of Rinv are zero).
+__global__ __launch_bounds__(256) void sub_chol_kernel(const double* __restrict__ gpart, int n_slices,
+                                                       float* __restrict__ Rinv) {
+    extern __shared__ __align__(16) double G[];                // [128][129]
+    __shared__ double dinv[kP];
+    __shared__ double maxdiag;
+    constexpr int LD = kP + 1;
+    const int tid = threadIdx.x;
+    for (int e = tid; e < kP * kP; e += 256) {
+        double a = 0.0;
+        for (int s = 0; s < n_slices; ++s) a += gpart[(int64_t)s * kP * kP + e];
+        G[(e >> 7) * LD + (e & 127)] = a;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        double m = 0.0;
+        for (int i = 0; i < kP; ++i) m = fmax(m, G[i * LD + i]);
+        maxdiag = m;
+    }
+    __syncthreads();
+    const double tol = maxdiag * 1e-12;
+    for (int j = 0; j < kP; ++j) {
+        const double piv = G[j * LD + j];
+        const bool live = piv > tol;
+        const double d = live ? sqrt(piv) : 0.0;
+        const double di = live ? 1.0 / d : 0.0;
+        __syncthreads();                                       // everyone has read the pivot
+        for (int i = j + tid; i < kP; i += 256) G[i * LD + j] = (i == j) ? d : G[i * LD + j] * di;
+        if (tid == 0) dinv[j] = di;
+        __syncthreads();
+        // trailing update of the lower triangle: G[i][k] -= L[i][j] L[k][j], j < k <= i
+        const int n = kP - 1 - j;
+        for (int e = tid; e < n * n; e += 256) {
+            const int i = j + 1 + e / n, k = j + 1 + e % n;
+            if (k <= i) G[i * LD + k] -= G[i * LD + j] * G[k * LD + j];
+        }
+    }
+    __syncthreads();
+    // column c of L^-1 by forward substitution (thread c): x_i = (delta_ic - sum_{k<i} L[i][k] x_k) / L[i][i].
+    // x is kept in row c of the (no longer needed) upper triangle, diagonal included; the reads
+    // of L touch the strict lower triangle only.
+    if (tid < kP) {
+        const int c = tid;
+        for (int i = 0; i < c; ++i) Rinv[(int64_t)c * kP + i] = 0.f;
+        for (int i = c; i < kP; ++i) {
+            double a = (i == c) ? 1.0 : 0.0;
+            for (int k = c; k < i; ++k) a -= G[i * LD + k] * G[c * LD + k];
+            const double x = a * dinv[i];
+            G[c * LD + i] = x;
+            Rinv[(int64_t)c * kP + i] = (float)x;             // Rinv = (L^-1)^T: Rinv[c][i] = Linv[i][c]
+        }
+    }
+}
+
+MatrixPlan plan_matrix(int N, int D) {
+    MatrixPlan p;
+    p.stat_chunks = N < 64 * 256 ? (N + 255) / 256 : 64;
+    p.stat_chunk = (N + p.stat_chunks - 1) / p.stat_chunks;
+    p.stat_chunks = (N + p.stat_chunk - 1) / p.stat_chunk;
+    // split of the token sum in W = X^T Z: enough workgroups for the chip, partials kept modest
+    const int row_blocks = (D + 63) / 64;
+    int kc = (1024 + row_blocks - 1) / row_blocks;
+    if (kc > 16) kc = 16;
+    const int max_kc = (N + 255) / 256;
+    if (kc > max_kc) kc = max_kc;
+    if (kc < 1) kc = 1;
+    p.w_chunk = ((N + kc - 1) / kc + 15) / 16 * 16;
+    p.w_chunks = (N + p.w_chunk - 1) / p.w_chunk;
+    p.gram_slices = (D + 255) / 256;
+    p.ep = plan_entropy(1, N);
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        const size_t at = off;
+        off = align_up(off + bytes, 256);
+        return at;
+    };
+    p.ep_off = take(p.ep.bytes);
+    p.statpart_off = take((size_t)p.stat_chunks * 2 * D * sizeof(double));
+    p.s_off = take((size_t)D * sizeof(double));
+    p.trace_off = take(2 * sizeof(double));
+    p.zsum_off = take(kP * sizeof(double));
+    p.q_off = take((size_t)D * kP * sizeof(float));
+    p.w_off = take((size_t)D * kP * sizeof(float));
+    p.wpart_off = take((size_t)p.w_chunks * D * kP * sizeof(float));
+    p.z_off = take((size_t)N * kP * sizeof(float));
+    p.gpart_off = take((size_t)p.gram_slices * kP * kP * sizeof(double));
+    p.rinv_off = take((size_t)kP * kP * sizeof(float));
+    p.bytes = off;
+    return p;
+}
+
+template <typename T>
+static hipError_t run_matrix_entropy(const T* X, int n_mat, int N, int D, int64_t mat_stride, int64_t ldx,
+                                     int k_trunc, unsigned flags, int n_iter, const MatrixPlan& p, char* ws,
+                                     float* entropy_out, float* eig_out, const Env& env) {
+    hipStream_t s = env.s;
+    const bool center = (flags & UNCOMP_CENTER) != 0;
+    double* statpart = reinterpret_cast<double*>(ws + p.statpart_off);
+    double* sv = reinterpret_cast<double*>(ws + p.s_off);
+    double* trace = reinterpret_cast<double*>(ws + p.trace_off);
+    double* zsum = reinterpret_cast<double*>(ws + p.zsum_off);
+    float* Q = reinterpret_cast<float*>(ws + p.q_off);
+    float* W = reinterpret_cast<float*>(ws + p.w_off);
+    float* Wpart = reinterpret_cast<float*>(ws + p.wpart_off);
+    float* Z = reinterpret_cast<float*>(ws + p.z_off);
+    double* gpart = reinterpret_cast<double*>(ws + p.gpart_off);
+    float* Rinv = reinterpret_cast<float*>(ws + p.rinv_off);
+    const size_t chol_lds = (size_t)kP * (kP + 1) * sizeof(double);
+    static bool chol_attr = false;
+    if (!chol_attr) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(sub_chol_kernel),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)chol_lds);
+        if (e != hipSuccess) return e;
+        chol_attr = true;
+    }
+    const unsigned dp_blocks = (unsigned)(((int64_t)D * kP + 255) / 256);
+    // Q = orth(W): Cholesky QR with the Gram in fp64
+    auto orth = [&]() {
+        sub_gram64_kernel<<<dim3((unsigned)p.gram_slices), dim3(256), 0, s>>>(W, D, 256, gpart);
+        sub_chol_kernel<<<dim3(1), dim3(256), chol_lds, s>>>(gpart, p.gram_slices, Rinv);
+        sub_gemm_kernel<float, false><<<dim3((unsigned)((D + 63) / 64), 1), dim3(256), 0, s>>>(W, kP, Rinv, D, kP, kP, Q);
+    };
+    auto project = [&](const T* Xm) {       // Z = X Q
+        sub_gemm_kernel<T, false><<<dim3((unsigned)((N + 63) / 64), 1), dim3(256), 0, s>>>(Xm, ldx, Q, N, D, D, Z);
+    };
+    for (int m = 0; m < n_mat; ++m) {
+        const T* Xm = X + (int64_t)m * mat_stride;
+        env.begin("matrix_colstats");
+        sub_colstats_kernel<T><<<dim3((unsigned)((D + 255) / 256), (unsigned)p.stat_chunks), dim3(256), 0, s>>>(
+            Xm, N, D, ldx, p.stat_chunk, statpart);
+        sub_colstats_finish_kernel<<<dim3(1), dim3(256), 0, s>>>(statpart, p.stat_chunks, D, N, sv, trace);
+        env.end();
+        env.begin("matrix_subspace");
+        sub_start_kernel<<<dim3(dp_blocks), dim3(256), 0, s>>>(W, D);
+        orth();
+        for (int it = 0; it < n_iter; ++it) {
+            project(Xm);
+            if (center) sub_zsum_kernel<<<dim3(1), dim3(128), 0, s>>>(sv, Q, D, zsum);
+            sub_gemm_kernel<T, true><<<dim3((unsigned)((D + 63) / 64), (unsigned)p.w_chunks), dim3(256), 0, s>>>(
+                Xm, ldx, Z, D, N, p.w_chunk, Wpart);
+            sub_reduce_kernel<<<dim3(dp_blocks), dim3(256), 0, s>>>(Wpart, p.w_chunks, D, center ? sv : nullptr, zsum,
+                                                                    1.0 / (double)N, W);
+            orth();
+            if (it == n_iter - 1) {          // once more: the last Q is orthonormal to fp32 rounding
+                hipError_t e = hipMemcpyAsync(W, Q, (size_t)D * kP * sizeof(float), hipMemcpyDeviceToDevice, s);
+                if (e != hipSuccess) return e;
+                orth();
+            }
+        }
+        project(Xm);
+        env.end();
+        // the projected tokens go through the 128-wide entropy path; trace(C) replaces its own trace
+        hipError_t e = launch_gram(Z, UNCOMP_F32, 1, N, (int64_t)N * kP, kP, p.ep, ws + p.ep_off, env);
+        if (e != hipSuccess) return e;
+        e = launch_tridiag_entropy(1, N, k_trunc, flags, p.ep, ws + p.ep_off, entropy_out + m,
+                                   eig_out != nullptr ? eig_out + (int64_t)m * kP : nullptr, env,
+                                   trace);
+        if (e != hipSuccess) return e;
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_matrix_entropy(const void* X, uncomp_dtype dt, int n_mat, int N, int D, int64_t mat_stride,
+                                 int64_t ldx, int k_trunc, unsigned flags, int n_iter, const MatrixPlan& p, char* ws,
+                                 float* entropy_out, float* eig_out, const Env& env) {
+    if (dt == UNCOMP_BF16)
+        return run_matrix_entropy(static_cast<const bf16_bits*>(X), n_mat, N, D, mat_stride, ldx, k_trunc, flags, n_iter,
+                                  p, ws, entropy_out, eig_out, env);
+    return run_matrix_entropy(static_cast<const float*>(X), n_mat, N, D, mat_stride, ldx, k_trunc, flags, n_iter, p, ws,
+                              entropy_out, eig_out, env);
+}
+
+}  // namespace uncomp

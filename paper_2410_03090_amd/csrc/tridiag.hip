@@ -130,7 +130,8 @@ __device__ __forceinline__ int sturm_count(const double2* de, double x) {
 template <int kParts>
 __global__ __launch_bounds__(kD * kParts, kParts == 2 ? 2 : 1) void tridiag_entropy_kernel(
     const float* __restrict__ gram_part, const float* __restrict__ sum_part, int n_chunks, int N,
-    int k_trunc, unsigned flags, float* __restrict__ entropy_out, float* __restrict__ eig_out) {
+    int k_trunc, unsigned flags, float* __restrict__ entropy_out, float* __restrict__ eig_out,
+    const double* __restrict__ trace_total) {
     constexpr int kThreads = kD * kParts, kWaves = kThreads / 64;
     constexpr int kHalf = kD / kParts;                           // rows of a column per thread
     __shared__ TriSmem<kParts> sm;
@@ -161,7 +162,14 @@ __global__ __launch_bounds__(kD * kParts, kParts == 2 ? 2 : 1) void tridiag_entr
     const double trace_u = block_sum<kWaves>(tr_u, sm.red, tid);
     // Zero spread: a single token, or a centred trace so far below the second moment that
     // the fp32 partial sums cannot tell it from zero.
-    const bool degenerate = !(trace > 0.0) || (center && (N < 2 || trace < trace_u * 0x1p-20));
+    bool degenerate = !(trace > 0.0) || (center && (N < 2 || trace < trace_u * 0x1p-20));
+    // A projection of a larger matrix: the verdict comes from the larger matrix' own traces
+    // (centred, uncentred; accumulated in fp64), the projection of a constant matrix being noise.
+    double whole_raw = 0.0;
+    if (trace_total != nullptr) {
+        whole_raw = center ? trace_total[0] : trace_total[1];
+        degenerate = degenerate || !(whole_raw > 0.0) || (center && whole_raw < trace_total[1] * 0x1p-30);
+    }
     if (degenerate) {
         if (tid == 0) entropy_out[m] = 0.f;
         if (eig_out != nullptr && tid < kD) eig_out[(int64_t)m * kD + tid] = 0.f;
@@ -319,7 +327,10 @@ __global__ __launch_bounds__(kD * kParts, kParts == 2 ? 2 : 1) void tridiag_entr
     const double mine = tid < kD ? sm.lam[tid] : 0.0;
     const double total = block_sum<kWaves>(tid < kD ? sm.de[tid].x : 0.0, sm.red, tid);   // the trace: sum of all eigenvalues
     const double topk = block_sum<kWaves>(tid < k ? mine : 0.0, sm.red, tid);
-    const double denom = (flags & UNCOMP_TRUNC_RENORM) ? topk : total;
+    // total = 1 up to rounding (the matrix was scaled to unit trace).  When the matrix is a projection
+    // of a larger one, the eigenvalues' share of the larger trace is what Eq. 5 and eig_out mean.
+    const double whole = trace_total != nullptr ? total * (whole_raw / trace) : total;
+    const double denom = (flags & UNCOMP_TRUNC_RENORM) ? topk : whole;
     double term = 0.0;
     if (tid < k && mine > 0.0 && denom > 0.0) {
         const double sgm = mine / denom;
@@ -328,20 +339,21 @@ __global__ __launch_bounds__(kD * kParts, kParts == 2 ? 2 : 1) void tridiag_entr
     const double H = block_sum<kWaves>(term, sm.red, tid);
     if (tid == 0) entropy_out[m] = (float)H;
     if (eig_out != nullptr && tid < kD)
-        eig_out[(int64_t)m * kD + tid] = total > 0.0 ? (float)(mine / total) : 0.f;
+        eig_out[(int64_t)m * kD + tid] = whole > 0.0 ? (float)(mine / whole) : 0.f;
 }
 
 hipError_t launch_tridiag_entropy(int n_mat, int N, int k_trunc, unsigned flags, const EntropyPlan& p,
-                                  char* ws, float* entropy_out, float* eig_out, const Env& env) {
+                                  char* ws, float* entropy_out, float* eig_out, const Env& env,
+                                  const double* trace_total) {
     const float* gram = reinterpret_cast<const float*>(ws + p.gram_off);
     const float* sums = reinterpret_cast<const float*>(ws + p.sum_off);
     env.begin("tridiag_entropy");
     if (n_mat < 512)
         tridiag_entropy_kernel<4><<<dim3(n_mat), dim3(4 * kD), 0, env.s>>>(gram, sums, p.n_chunks, N, k_trunc, flags,
-                                                                         entropy_out, eig_out);
+                                                                         entropy_out, eig_out, trace_total);
     else
         tridiag_entropy_kernel<2><<<dim3(n_mat), dim3(2 * kD), 0, env.s>>>(gram, sums, p.n_chunks, N, k_trunc, flags,
-                                                                         entropy_out, eig_out);
+                                                                         entropy_out, eig_out, trace_total);
     env.end();
     return hipGetLastError();
 }
