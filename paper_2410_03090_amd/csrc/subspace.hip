@@ -166,13 +166,22 @@ __global__ __launch_bounds__(256) void sub_gemm_kernel(const T* __restrict__ A, 
     }
 }
 
-// zsum[j] = sum_d s[d] Q[d][j] (= column sums of Z = X Q), fp64.  One workgroup of 128 threads.
-__global__ __launch_bounds__(128) void sub_zsum_kernel(const double* __restrict__ s, const float* __restrict__ Q, int D,
-                                                       double* __restrict__ zsum) {
-    const int j = threadIdx.x;
+// zsum[j] = sum_d s[d] Q[d][j] (= column sums of Z = X Q), fp64.  One workgroup: thread (slice, j)
+// adds every eighth d, the eight slices meet in LDS.
+__global__ __launch_bounds__(1024) void sub_zsum_kernel(const double* __restrict__ s, const float* __restrict__ Q, int D,
+                                                        double* __restrict__ zsum) {
+    __shared__ double part[8][kP];
+    const int j = threadIdx.x & (kP - 1), sl = threadIdx.x >> 7;
     double a = 0.0;
-    for (int d = 0; d < D; ++d) a += s[d] * (double)Q[(int64_t)d * kP + j];
-    zsum[j] = a;
+    for (int d = sl; d < D; d += 8) a += s[d] * (double)Q[(int64_t)d * kP + j];
+    part[sl][j] = a;
+    __syncthreads();
+    if (sl == 0) {
+        double t = part[0][j];
+#pragma unroll
+        for (int x = 1; x < 8; ++x) t += part[x][j];
+        zsum[j] = t;
+    }
 }
 
 // W[d][j] = sum over chunks of part[c][d][j] - s[d] zsum[j] / N   (the mean correction of C Q)
@@ -227,21 +236,25 @@ __global__ __launch_bounds__(256) void sub_gram64_kernel(const float* __restrict
         for (int j = 0; j < 8; ++j) o[(8 * ty + i) * kP + 8 * tx + j] = acc[i][j];
 }
 
-// One workgroup: G = sum of the slices, Cholesky G = L L^T in LDS (fp64), then Rinv = L^-T as fp32
+// gsum = sum of the slices (fixed order).
+__global__ __launch_bounds__(256) void sub_gram64_sum_kernel(const double* __restrict__ gpart, int n_slices,
+                                                             double* __restrict__ gsum) {
+    const int e = blockIdx.x * 256 + threadIdx.x;
+    double a = 0.0;
+    for (int s = 0; s < n_slices; ++s) a += gpart[(int64_t)s * kP * kP + e];
+    gsum[e] = a;
+}
+
+// One workgroup: Cholesky G = L L^T in LDS (fp64), then Rinv = L^-T as fp32
 // so that Q = W Rinv has orthonormal columns.  A pivot below 1e-12 of the largest diagonal entry
 // retires its column (its row and column of Rinv are zero).
-__global__ __launch_bounds__(256) void sub_chol_kernel(const double* __restrict__ gpart, int n_slices,
-                                                       float* __restrict__ Rinv) {
+__global__ __launch_bounds__(256) void sub_chol_kernel(const double* __restrict__ gsum, float* __restrict__ Rinv) {
     extern __shared__ __align__(16) double G[];                // [128][129]
     __shared__ double dinv[kP];
     __shared__ double maxdiag;
     constexpr int LD = kP + 1;
     const int tid = threadIdx.x;
-    for (int e = tid; e < kP * kP; e += 256) {
-        double a = 0.0;
-        for (int s = 0; s < n_slices; ++s) a += gpart[(int64_t)s * kP * kP + e];
-        G[(e >> 7) * LD + (e & 127)] = a;
-    }
+    for (int e = tid; e < kP * kP; e += 256) G[(e >> 7) * LD + (e & 127)] = gsum[e];
     __syncthreads();
     if (tid == 0) {
         double m = 0.0;
@@ -260,10 +273,9 @@ __global__ __launch_bounds__(256) void sub_chol_kernel(const double* __restrict_
         if (tid == 0) dinv[j] = di;
         __syncthreads();
         // trailing update of the lower triangle: G[i][k] -= L[i][j] L[k][j], j < k <= i
-        const int n = kP - 1 - j;
-        for (int e = tid; e < n * n; e += 256) {
-            const int i = j + 1 + e / n, k = j + 1 + e % n;
-            if (k <= i) G[i * LD + k] -= G[i * LD + j] * G[k * LD + j];
+        for (int i = j + 1 + (tid >> 4); i < kP; i += 16) {
+            const double lij = G[i * LD + j];
+            for (int k = j + 1 + (tid & 15); k <= i; k += 16) G[i * LD + k] -= lij * G[k * LD + j];
         }
     }
     __syncthreads();
@@ -314,7 +326,7 @@ MatrixPlan plan_matrix(int N, int D) {
     p.w_off = take((size_t)D * kP * sizeof(float));
     p.wpart_off = take((size_t)p.w_chunks * D * kP * sizeof(float));
     p.z_off = take((size_t)N * kP * sizeof(float));
-    p.gpart_off = take((size_t)p.gram_slices * kP * kP * sizeof(double));
+    p.gpart_off = take((size_t)(p.gram_slices + 1) * kP * kP * sizeof(double));     // slices, then their sum
     p.rinv_off = take((size_t)kP * kP * sizeof(float));
     p.bytes = off;
     return p;
@@ -335,6 +347,7 @@ static hipError_t run_matrix_entropy(const T* X, int n_mat, int N, int D, int64_
     float* Wpart = reinterpret_cast<float*>(ws + p.wpart_off);
     float* Z = reinterpret_cast<float*>(ws + p.z_off);
     double* gpart = reinterpret_cast<double*>(ws + p.gpart_off);
+    double* gsum = gpart + (size_t)p.gram_slices * kP * kP;
     float* Rinv = reinterpret_cast<float*>(ws + p.rinv_off);
     const size_t chol_lds = (size_t)kP * (kP + 1) * sizeof(double);
     static bool chol_attr = false;
@@ -348,7 +361,8 @@ static hipError_t run_matrix_entropy(const T* X, int n_mat, int N, int D, int64_
     // Q = orth(W): Cholesky QR with the Gram in fp64
     auto orth = [&]() {
         sub_gram64_kernel<<<dim3((unsigned)p.gram_slices), dim3(256), 0, s>>>(W, D, 256, gpart);
-        sub_chol_kernel<<<dim3(1), dim3(256), chol_lds, s>>>(gpart, p.gram_slices, Rinv);
+        sub_gram64_sum_kernel<<<dim3(kP * kP / 256), dim3(256), 0, s>>>(gpart, p.gram_slices, gsum);
+        sub_chol_kernel<<<dim3(1), dim3(256), chol_lds, s>>>(gsum, Rinv);
         sub_gemm_kernel<float, false><<<dim3((unsigned)((D + 63) / 64), 1), dim3(256), 0, s>>>(W, kP, Rinv, D, kP, kP, Q);
     };
     auto project = [&](const T* Xm) {       // Z = X Q
@@ -366,7 +380,7 @@ static hipError_t run_matrix_entropy(const T* X, int n_mat, int N, int D, int64_
         orth();
         for (int it = 0; it < n_iter; ++it) {
             project(Xm);
-            if (center) sub_zsum_kernel<<<dim3(1), dim3(128), 0, s>>>(sv, Q, D, zsum);
+            if (center) sub_zsum_kernel<<<dim3(1), dim3(1024), 0, s>>>(sv, Q, D, zsum);
             sub_gemm_kernel<T, true><<<dim3((unsigned)((D + 63) / 64), (unsigned)p.w_chunks), dim3(256), 0, s>>>(
                 Xm, ldx, Z, D, N, p.w_chunk, Wpart);
             sub_reduce_kernel<<<dim3(dp_blocks), dim3(256), 0, s>>>(Wpart, p.w_chunks, D, center ? sv : nullptr, zsum,
