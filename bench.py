@@ -73,6 +73,7 @@ def main():
                     help="also run one plain device copy of this many MiB (reference for HBM byte counters)")
     ap.add_argument("--cpu-heads", type=int, default=0, help="heads in the oracle sample (0 = auto)")
     ap.add_argument("--no-prepare", action="store_true", help="skip the offline-preparation leg")
+    ap.add_argument("--no-matrix-entropy", action="store_true", help="skip the wide-matrix (hidden-state) entropy leg")
     ap.add_argument("--no-hidden-evict", action="store_true", help="skip the stage-1 hidden-state eviction leg")
     ap.add_argument("--decode-steps", type=int, default=64,
                     help="generated tokens to run through uncomp_decode_step after the timed prefill steps (0 = skip)")
@@ -102,6 +103,8 @@ def main():
         ws = max(ws, binding.Context.decode_workspace_bytes(LB * H, G, cfg.cap))
     if not args.no_hidden_evict:
         ws = max(ws, binding.Context.hidden_workspace_bytes(B, H, G, N, w))
+    if not args.no_matrix_entropy:
+        ws = max(ws, binding.Context.matrix_workspace_bytes(N, 4096))
     ctx = binding.Context(0, ws)
     ctx.set_overlap(args.overlap and not args.no_overlap)
     i32 = dict(dtype=torch.int32, device=dev)
@@ -170,6 +173,7 @@ def main():
     decode = decode_leg(cfg, ctx, score, bud[0], outs, args) if args.decode_steps > 0 else None
     hidden = None if args.no_hidden_evict else hidden_leg(cfg, ctx, K, Q, args)
     prepare = None if args.no_prepare else prepare_leg(cfg, ctx, Kf, ent, args)
+    matrix = None if args.no_matrix_entropy else matrix_leg(cfg, ctx, args)
 
     cpu = None
     if not args.no_cpu_baseline:
@@ -185,10 +189,40 @@ def main():
                    "head_dim": D, "window": w, "pool": cfg.pool, "k_trunc": cfg.k_trunc,
                    "avg_budget": cfg.avg_budget, "mean_kept": round(kept, 1), "rho": round(kept / N, 5),
                    "head_tokens_per_s": round(value * L * H, 1)},
-        "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels, "decode": decode, "hidden_evict": hidden, "prepare": prepare,
+        "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels, "decode": decode, "hidden_evict": hidden, "prepare": prepare, "matrix_entropy": matrix,
         "gen_seconds": round(t_gen, 1),
     }
     print(json.dumps(out))
+
+
+def matrix_leg(cfg, ctx, args):
+    """Not part of `value`: truncated entropy of one [N, 4096] hidden-state matrix (low rank plus noise, as the
+    keys) by uncomp_matrix_entropy, 8 rounds.  The rounds are two tall-skinny products each on the fp32
+    ALUs; reports the time and the fp32 rate."""
+    import math
+
+    import torch
+    dev = "cuda:0"
+    N, D, r, n_iter = cfg.N, 4096, 80, 8
+    g = torch.Generator(device=dev).manual_seed(args.seed + 4096)
+    X = ((torch.randn(N, r, generator=g, device=dev) / math.sqrt(r)) @ (torch.randn(r, D, generator=g, device=dev) / math.sqrt(r))
+         + 0.1 * math.sqrt(128.0 / D) * torch.randn(N, D, generator=g, device=dev)).to(torch.bfloat16 if cfg.dtype == "bf16" else torch.float32)[None]
+    ctx.matrix_entropy(X, k_trunc=cfg.k_trunc, n_iter=n_iter)
+    torch.cuda.synchronize()
+    ctx.profile(True)
+    t0 = time.perf_counter()
+    H = ctx.matrix_entropy(X, k_trunc=cfg.k_trunc, n_iter=n_iter)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    per = {}
+    for name, m in ctx.profile_read():
+        per[name] = per.get(name, 0.0) + m
+    ctx.profile(False)
+    flops = (2 * n_iter + 1) * 2.0 * N * D * 128
+    e = 2 if cfg.dtype == "bf16" else 4
+    return {"tokens": N, "width": D, "rounds": n_iter, "entropy": round(float(H[0]), 5), "ms": round(dt * 1e3, 2),
+            "fp32_TFLOPs": round(flops / dt / 1e12, 1), "x_read_GBps": round((2 * n_iter + 2) * N * D * e / dt / 1e9, 1),
+            "stages_ms": {k: round(v, 3) for k, v in per.items()}}
 
 
 def prepare_leg(cfg, ctx, Kf, ent, args):
