@@ -63,7 +63,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", type=int, default=3, help="index into BASELINE.json configs (default: the 128K prefill)")
+    ap.add_argument("--config", type=int, default=3, help="benchmark configuration 0-4 (default 3: the 128K-token prefill)")
     ap.add_argument("--seed", type=int, default=2410)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--overlap", action="store_true",

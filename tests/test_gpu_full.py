@@ -1,5 +1,6 @@
-"""Full-size parity: BASELINE configs 1-4 at their real shapes, in the launch configuration the
-bench times (all layers handed to each call at once, overlap mode on).  The oracle checks a sample
+"""Full-size parity: benchmark configurations 1-4 at their real shapes, in the launch configuration the
+bench times (all layers handed to each call at once, every kernel on one stream; the 128K case also
+with the entropy stage on the side stream).  The oracle checks a sample
 of (layer, batch, head) units element by element; properties that hold at any size are checked on
 every head."""
 import numpy as np
@@ -22,8 +23,9 @@ def _sample_units(cfg, n, seed):
     return sorted(units)
 
 
-@pytest.mark.parametrize("ci,n_ent,n_score", [(1, 24, 6), (2, 16, 4), (3, 12, 3), (4, 24, 6)])
-def test_full_config(ci, n_ent, n_score):
+@pytest.mark.parametrize("ci,n_ent,n_score,overlap", [(1, 24, 6, False), (2, 16, 4, False), (3, 12, 3, False),
+                                                      (3, 4, 1, True), (4, 24, 6, False)])
+def test_full_config(ci, n_ent, n_score, overlap):
     from paper_2410_03090_amd import binding
     cfg = synth.CONFIGS[ci]
     L, B, H, N, D, G, w = cfg.L, cfg.B, cfg.H, cfg.N, cfg.D, cfg.G, cfg.w
@@ -31,7 +33,7 @@ def test_full_config(ci, n_ent, n_score):
     print(f"\n[{cfg.name}] generating {L}x{B}x{H} heads of {N} tokens", flush=True)
     K, V, Q = synth.gen_all(cfg, seed0=1000 + ci, device=DEV)
     ctx = binding.Context(0, binding.Context.workspace_bytes(LB * H, N, D, LB, H, G, w))
-    ctx.set_overlap(True)
+    ctx.set_overlap(overlap)
     Kf, Vf, Qf = K.reshape(LB, H, N, D), V.reshape(LB, H, N, D), Q.reshape(LB, H * G, w, D)
     ent = ctx.head_entropy(K.reshape(LB * H, N, D), k_trunc=cfg.k_trunc).reshape(L, B, H)
     hb, hg, lg, lt = ctx.assign_budgets(ent, cfg.M, cfg.n_max, cfg.step, N, w, 0.4, 512)
