@@ -139,6 +139,7 @@ __global__ __launch_bounds__(kD * kParts, kParts == 2 ? 2 : 1) void tridiag_entr
     const int tid = threadIdx.x, lane = tid & 63;
     const int c = tid & (kD - 1);
     const int hf = __builtin_amdgcn_readfirstlane(tid >> 7);     // wave-uniform: which slice of rows
+    const int col_hi = __builtin_amdgcn_readfirstlane(c | 63);   // last column of this wave
     const float* Gm = gram_part + (int64_t)m * n_chunks * (kD * kD);
     const float* Sm = sum_part + (int64_t)m * n_chunks * kD;
 
@@ -234,7 +235,8 @@ __global__ __launch_bounds__(kD * kParts, kParts == 2 ? 2 : 1) void tridiag_entr
         // This thread's part of (A x)_c over the rows of its half (x is zero on the rows that are
         // done).  It does not depend on the reflection's scalars, so it runs beside their reduction.
         double p0 = 0.0, p1 = 0.0, p2 = 0.0, p3 = 0.0;
-        const bool half_live = hf * kHalf + kHalf - 1 > i;
+        // rows of this slice still in play, and columns of this wave still in play (both wave-uniform)
+        const bool half_live = hf * kHalf + kHalf - 1 > i && col_hi > i;
         if (half_live) {
 #pragma unroll
             for (int k = 0; k < kHalf; k += 4) {
