@@ -328,6 +328,15 @@ MatrixPlan plan_matrix(int N, int D) {
     p.z_off = take((size_t)N * kP * sizeof(float));
     p.gpart_off = take((size_t)(p.gram_slices + 1) * kP * kP * sizeof(double));     // slices, then their sum
     p.rinv_off = take((size_t)kP * kP * sizeof(float));
+    // bf16 MFMA products: Q^T as two bf16 halves, partial Z of the split over d
+    const int row_wgs = (N + 255) / 256;
+    int zs = (512 + row_wgs - 1) / row_wgs;
+    if (zs > 8) zs = 8;
+    if (zs > D / 256) zs = D / 256;
+    if (zs < 1) zs = 1;
+    p.z_splits = zs;
+    p.qt_off = take((size_t)2 * kP * D * sizeof(bf16_bits));
+    p.zpart_off = take(zs > 1 ? (size_t)zs * N * kP * sizeof(float) : 0);
     p.bytes = off;
     return p;
 }
@@ -365,7 +374,22 @@ static hipError_t run_matrix_entropy(const T* X, int n_mat, int N, int D, int64_
         sub_chol_kernel<<<dim3(1), dim3(256), chol_lds, s>>>(gsum, Rinv);
         sub_gemm_kernel<float, false><<<dim3((unsigned)((D + 63) / 64), 1), dim3(256), 0, s>>>(W, kP, Rinv, D, kP, kP, Q);
     };
+    // bf16 inputs with 16-byte aligned rows take the MFMA products, everything else the fp32 ALUs
+    bool mfma = false;
+    if constexpr (sizeof(T) == 2)
+        mfma = !env.force_alu && (ldx % 8) == 0 && (mat_stride % 8) == 0 && (reinterpret_cast<uintptr_t>(X) & 15u) == 0;
+    bf16_bits* Qt_hi = reinterpret_cast<bf16_bits*>(ws + p.qt_off);
+    bf16_bits* Qt_lo = Qt_hi + (size_t)kP * D;
+    float* Zpart = reinterpret_cast<float*>(ws + p.zpart_off);
+    hipError_t perr = hipSuccess;
     auto project = [&](const T* Xm) {       // Z = X Q
+        if constexpr (sizeof(T) == 2) {
+            if (mfma) {
+                hipError_t e = launch_xq_mfma(Xm, ldx, Q, N, D, Qt_hi, Qt_lo, p.z_splits, Zpart, Z, s);
+                if (e != hipSuccess) perr = e;
+                return;
+            }
+        }
         sub_gemm_kernel<T, false><<<dim3((unsigned)((N + 63) / 64), 1), dim3(256), 0, s>>>(Xm, ldx, Q, N, D, D, Z);
     };
     for (int m = 0; m < n_mat; ++m) {
@@ -394,6 +418,7 @@ static hipError_t run_matrix_entropy(const T* X, int n_mat, int N, int D, int64_
         }
         project(Xm);
         env.end();
+        if (perr != hipSuccess) return perr;
         // the projected tokens go through the 128-wide entropy path; trace(C) replaces its own trace
         hipError_t e = launch_gram(Z, UNCOMP_F32, 1, N, (int64_t)N * kP, kP, p.ep, ws + p.ep_off, env);
         if (e != hipSuccess) return e;

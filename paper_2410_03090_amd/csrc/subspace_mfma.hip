@@ -1,0 +1,165 @@
+// bf16 MFMA versions of the two tall-skinny products of the wide-matrix entropy (Z = X Q and
+// W = X^T Z; see subspace.hip).  X is bf16 as it comes; the fp32 factor (Q, resp. Z) is split into
+// a high and a low bf16 half, x = hi + lo with |lo| <= 2^-9 |hi|, and both halves go through the
+// matrix cores with fp32 accumulation, which keeps the product at ~2^-17 relative error.
+#include "common.h"
+#include "device_utils.h"
+
+namespace uncomp {
+
+namespace {
+
+constexpr int kP = 128;
+constexpr int kQtRow = 40;               // LDS row of one column of Q^T: 32 elements + 8 of padding (80 bytes:
+                                         // 16 consecutive rows then start in 16 different 16-byte bank groups)
+
+// round-to-nearest-even bf16 of a finite float
+__device__ __forceinline__ uint32_t bf16_rne(float f) {
+    const uint32_t u = __float_as_uint(f);
+    return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+}
+
+}  // namespace
+
+// Qt_hi / Qt_lo [128][D] bf16 from Q [D][128] fp32: the transposed halves that the X Q kernel streams.
+__global__ __launch_bounds__(256) void sub_qt_split_kernel(const float* __restrict__ Q, int D, bf16_bits* __restrict__ Qt_hi,
+                                                           bf16_bits* __restrict__ Qt_lo) {
+    __shared__ float tile[32][33];
+    const int d0 = blockIdx.x * 32, j0 = blockIdx.y * 32;
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;           // 32 x 8
+    for (int r = ty; r < 32; r += 8) tile[r][tx] = Q[(int64_t)(d0 + r) * kP + j0 + tx];
+    __syncthreads();
+    for (int r = ty; r < 32; r += 8) {
+        const float v = tile[tx][r];                                  // Q[d0 + tx][j0 + r]
+        const uint32_t hi = bf16_rne(v);
+        const uint32_t lo = bf16_rne(v - __uint_as_float(hi << 16));
+        Qt_hi[(int64_t)(j0 + r) * D + d0 + tx] = (bf16_bits)hi;
+        Qt_lo[(int64_t)(j0 + r) * D + d0 + tx] = (bf16_bits)lo;
+    }
+}
+
+// out[kc][t][j] = sum over the k chunk of X[t][d] (Qt_hi[j][d] + Qt_lo[j][d]).
+// Workgroup: 256 rows of X; wave: 64 rows (four 16-row blocks) x 128 columns.  Per step of 32 d the
+// X rows come straight from global memory in MFMA A-operand layout (lane = row%16, 16 bytes), the
+// step's slice of Q^T (128 x 32, both halves) is staged in LDS by the whole workgroup, double
+// buffered, and read as B operands.
+__global__ __launch_bounds__(256) void sub_xq_mfma_kernel(const bf16_bits* __restrict__ X, int64_t ldx,
+                                                          const bf16_bits* __restrict__ Qt_hi,
+                                                          const bf16_bits* __restrict__ Qt_lo, int N, int D,
+                                                          int k_chunk, float* __restrict__ out) {
+    __shared__ __align__(16) bf16_bits qs[2][2][kP * kQtRow];         // [buffer][half][column][d]
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int n = lane & 15, kq = lane >> 4;
+    const int row0 = blockIdx.x * 256 + wv * 64;
+    const int kc = blockIdx.y;
+    const int k_begin = kc * k_chunk, k_end = min(D, k_begin + k_chunk);
+    const int n_steps = (k_end - k_begin) >> 5;
+    f32x4_t acc[4][8];
+#pragma unroll
+    for (int rb = 0; rb < 4; ++rb)
+#pragma unroll
+        for (int cb = 0; cb < 8; ++cb) acc[rb][cb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+
+    // staging: 128 columns x 4 pieces of 8 d, for both halves: four 16-byte loads per thread
+    const int s_col0 = tid >> 2, s_piece = tid & 3;                    // columns s_col0 and s_col0 + 64
+    uint4 sh0, sh1, sl0, sl1;                                        // staged pieces of Q^T (named: an array here ends up in scratch)
+    uint4 a_cur[4], a_nxt[4];
+    auto stage_load = [&](int step) {
+        const int k0 = k_begin + 32 * step + 8 * s_piece;
+        sh0 = *reinterpret_cast<const uint4*>(Qt_hi + (int64_t)s_col0 * D + k0);
+        sh1 = *reinterpret_cast<const uint4*>(Qt_hi + (int64_t)(s_col0 + 64) * D + k0);
+        sl0 = *reinterpret_cast<const uint4*>(Qt_lo + (int64_t)s_col0 * D + k0);
+        sl1 = *reinterpret_cast<const uint4*>(Qt_lo + (int64_t)(s_col0 + 64) * D + k0);
+    };
+    auto stage_store = [&](int buf) {
+        *reinterpret_cast<uint4*>(&qs[buf][0][s_col0 * kQtRow + 8 * s_piece]) = sh0;
+        *reinterpret_cast<uint4*>(&qs[buf][0][(s_col0 + 64) * kQtRow + 8 * s_piece]) = sh1;
+        *reinterpret_cast<uint4*>(&qs[buf][1][s_col0 * kQtRow + 8 * s_piece]) = sl0;
+        *reinterpret_cast<uint4*>(&qs[buf][1][(s_col0 + 64) * kQtRow + 8 * s_piece]) = sl1;
+    };
+    // rows past the end re-read the last row (clamped, never predicated); their results are not stored
+    auto load_a_next = [&](int step) {
+        const int k0 = k_begin + 32 * step + 8 * kq;
+#pragma unroll
+        for (int rb = 0; rb < 4; ++rb) {
+            const int r = min(row0 + 16 * rb + n, N - 1);
+            a_nxt[rb] = *reinterpret_cast<const uint4*>(X + (int64_t)r * ldx + k0);
+        }
+    };
+    stage_load(0);
+    load_a_next(0);
+    stage_store(0);
+#pragma unroll
+    for (int rb = 0; rb < 4; ++rb) a_cur[rb] = a_nxt[rb];
+    __syncthreads();
+    for (int step = 0; step < n_steps; ++step) {
+        const int buf = step & 1;
+        const bool more = step + 1 < n_steps;
+        if (more) {
+            stage_load(step + 1);
+            load_a_next(step + 1);
+        }
+#pragma unroll
+        for (int cb = 0; cb < 8; ++cb) {
+            const bf16x8_t bh = __builtin_bit_cast(
+                bf16x8_t, *reinterpret_cast<const uint4*>(&qs[buf][0][(16 * cb + n) * kQtRow + 8 * kq]));
+            const bf16x8_t bl = __builtin_bit_cast(
+                bf16x8_t, *reinterpret_cast<const uint4*>(&qs[buf][1][(16 * cb + n) * kQtRow + 8 * kq]));
+#pragma unroll
+            for (int rb = 0; rb < 4; ++rb) {
+                const bf16x8_t av = __builtin_bit_cast(bf16x8_t, a_cur[rb]);
+                acc[rb][cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, bh, acc[rb][cb], 0, 0, 0);
+                acc[rb][cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, bl, acc[rb][cb], 0, 0, 0);
+            }
+        }
+        if (more) stage_store(buf ^ 1);          // the other buffer: everyone left it at the last barrier
+        __syncthreads();
+#pragma unroll
+        for (int rb = 0; rb < 4; ++rb) a_cur[rb] = a_nxt[rb];
+    }
+    // accumulator lane: column 16 cb + n, rows 16 rb + 4 kq + v
+    float* o = out + (int64_t)kc * N * kP;
+#pragma unroll
+    for (int rb = 0; rb < 4; ++rb)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const int r = row0 + 16 * rb + 4 * kq + v;
+            if (r < N) {
+#pragma unroll
+                for (int cb = 0; cb < 8; ++cb) o[(int64_t)r * kP + 16 * cb + n] = acc[rb][cb][v];
+            }
+        }
+}
+
+// out[e] = sum over the chunks of part[c][e], e < total (fixed order).
+__global__ __launch_bounds__(256) void sub_sum_parts_kernel(const float* __restrict__ part, int n_parts, int64_t total,
+                                                            float* __restrict__ out) {
+    const int64_t e = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
+    if (e >= total) return;
+    float4 a = *reinterpret_cast<const float4*>(part + e);
+    for (int c = 1; c < n_parts; ++c) {
+        const float4 b = *reinterpret_cast<const float4*>(part + (int64_t)c * total + e);
+        a.x += b.x;
+        a.y += b.y;
+        a.z += b.z;
+        a.w += b.w;
+    }
+    *reinterpret_cast<float4*>(out + e) = a;
+}
+
+hipError_t launch_xq_mfma(const bf16_bits* X, int64_t ldx, const float* Q, int N, int D, bf16_bits* Qt_hi,
+                          bf16_bits* Qt_lo, int n_split, float* Zpart, float* Z, hipStream_t s) {
+    sub_qt_split_kernel<<<dim3((unsigned)(D / 32), kP / 32), dim3(256), 0, s>>>(Q, D, Qt_hi, Qt_lo);
+    const int k_chunk = ((D + n_split - 1) / n_split + 31) / 32 * 32;
+    const int splits = (D + k_chunk - 1) / k_chunk;
+    float* dst = splits == 1 ? Z : Zpart;
+    sub_xq_mfma_kernel<<<dim3((unsigned)((N + 255) / 256), (unsigned)splits), dim3(256), 0, s>>>(X, ldx, Qt_hi, Qt_lo, N, D,
+                                                                                              k_chunk, dst);
+    if (splits > 1) {
+        const int64_t total = (int64_t)N * kP;
+        sub_sum_parts_kernel<<<dim3((unsigned)((total / 4 + 255) / 256)), dim3(256), 0, s>>>(Zpart, splits, total, Z);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace uncomp
