@@ -135,12 +135,15 @@ struct MatrixPlan {
     int w_chunks, w_chunk;           // token chunks of W = X^T Z
     int gram_slices;                 // row slices of the fp64 Gram of W
     int z_splits;                    // split of the sum over d in the MFMA version of Z = X Q
-    size_t qt_off, zpart_off;
+    int t_chunks, t_chunk;           // token chunks of the MFMA version of W = X^T Z
+    size_t qt_off, zpart_off, zsplit_off;
     EntropyPlan ep;                  // the 128-wide entropy path on the projected tokens
     size_t ep_off, statpart_off, s_off, trace_off, zsum_off, q_off, w_off, wpart_off, z_off, gpart_off, rinv_off;
     size_t bytes;
 };
 MatrixPlan plan_matrix(int N, int D);
+hipError_t launch_xtz_mfma(const uint16_t* X, int64_t ldx, const float* Z, int N, int D, uint16_t* Zh, uint16_t* Zl,
+                           int t_chunk, int n_tchunks, float* Wpart, hipStream_t s);
 hipError_t launch_xq_mfma(const uint16_t* X, int64_t ldx, const float* Q, int N, int D, uint16_t* Qt_hi,
                           uint16_t* Qt_lo, int n_split, float* Zpart, float* Z, hipStream_t s);
 hipError_t launch_matrix_entropy(const void* X, uncomp_dtype dt, int n_mat, int N, int D, int64_t mat_stride,

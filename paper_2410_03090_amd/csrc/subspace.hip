@@ -324,7 +324,13 @@ MatrixPlan plan_matrix(int N, int D) {
     p.zsum_off = take(kP * sizeof(double));
     p.q_off = take((size_t)D * kP * sizeof(float));
     p.w_off = take((size_t)D * kP * sizeof(float));
-    p.wpart_off = take((size_t)p.w_chunks * D * kP * sizeof(float));
+    // token chunks of the MFMA version of W = X^T Z (whole rounds of 128 tokens)
+    int tn = (512 + D / 128 - 1) / (D / 128);
+    if (tn > 16) tn = 16;
+    if (tn < 1) tn = 1;
+    p.t_chunk = ((N + tn - 1) / tn + 127) / 128 * 128;
+    p.t_chunks = (N + p.t_chunk - 1) / p.t_chunk;
+    p.wpart_off = take((size_t)(p.w_chunks > p.t_chunks ? p.w_chunks : p.t_chunks) * D * kP * sizeof(float));
     p.z_off = take((size_t)N * kP * sizeof(float));
     p.gpart_off = take((size_t)(p.gram_slices + 1) * kP * kP * sizeof(double));     // slices, then their sum
     p.rinv_off = take((size_t)kP * kP * sizeof(float));
@@ -337,6 +343,7 @@ MatrixPlan plan_matrix(int N, int D) {
     p.z_splits = zs;
     p.qt_off = take((size_t)2 * kP * D * sizeof(bf16_bits));
     p.zpart_off = take(zs > 1 ? (size_t)zs * N * kP * sizeof(float) : 0);
+    p.zsplit_off = take((size_t)2 * N * kP * sizeof(bf16_bits));
     p.bytes = off;
     return p;
 }
@@ -381,6 +388,8 @@ static hipError_t run_matrix_entropy(const T* X, int n_mat, int N, int D, int64_
     bf16_bits* Qt_hi = reinterpret_cast<bf16_bits*>(ws + p.qt_off);
     bf16_bits* Qt_lo = Qt_hi + (size_t)kP * D;
     float* Zpart = reinterpret_cast<float*>(ws + p.zpart_off);
+    bf16_bits* Zh = reinterpret_cast<bf16_bits*>(ws + p.zsplit_off);
+    bf16_bits* Zl = Zh + (size_t)N * kP;
     hipError_t perr = hipSuccess;
     auto project = [&](const T* Xm) {       // Z = X Q
         if constexpr (sizeof(T) == 2) {
@@ -405,9 +414,20 @@ static hipError_t run_matrix_entropy(const T* X, int n_mat, int N, int D, int64_
         for (int it = 0; it < n_iter; ++it) {
             project(Xm);
             if (center) sub_zsum_kernel<<<dim3(1), dim3(1024), 0, s>>>(sv, Q, D, zsum);
-            sub_gemm_kernel<T, true><<<dim3((unsigned)((D + 63) / 64), (unsigned)p.w_chunks), dim3(256), 0, s>>>(
-                Xm, ldx, Z, D, N, p.w_chunk, Wpart);
-            sub_reduce_kernel<<<dim3(dp_blocks), dim3(256), 0, s>>>(Wpart, p.w_chunks, D, center ? sv : nullptr, zsum,
+            int w_parts = p.w_chunks;
+            bool done = false;
+            if constexpr (sizeof(T) == 2) {
+                if (mfma) {
+                    hipError_t e = launch_xtz_mfma(Xm, ldx, Z, N, D, Zh, Zl, p.t_chunk, p.t_chunks, Wpart, s);
+                    if (e != hipSuccess) return e;
+                    w_parts = p.t_chunks;
+                    done = true;
+                }
+            }
+            if (!done)
+                sub_gemm_kernel<T, true><<<dim3((unsigned)((D + 63) / 64), (unsigned)p.w_chunks), dim3(256), 0, s>>>(
+                    Xm, ldx, Z, D, N, p.w_chunk, Wpart);
+            sub_reduce_kernel<<<dim3(dp_blocks), dim3(256), 0, s>>>(Wpart, w_parts, D, center ? sv : nullptr, zsum,
                                                                     1.0 / (double)N, W);
             orth();
             if (it == n_iter - 1) {          // once more: the last Q is orthonormal to fp32 rounding
