@@ -197,8 +197,8 @@ def main():
 
 def matrix_leg(cfg, ctx, args):
     """Not part of `value`: truncated entropy of one [N, 4096] hidden-state matrix (low rank plus noise, as the
-    keys) by uncomp_matrix_entropy, 8 rounds.  The rounds are two tall-skinny products each on the fp32
-    ALUs; reports the time and the fp32 rate."""
+    keys) by uncomp_matrix_entropy, 8 rounds of two tall-skinny products each (matrix cores for bf16).
+    HBM-bound in principle: reports the time and the rate at which the matrix is streamed."""
     import math
 
     import torch
@@ -221,7 +221,8 @@ def matrix_leg(cfg, ctx, args):
     flops = (2 * n_iter + 1) * 2.0 * N * D * 128
     e = 2 if cfg.dtype == "bf16" else 4
     return {"tokens": N, "width": D, "rounds": n_iter, "entropy": round(float(H[0]), 5), "ms": round(dt * 1e3, 2),
-            "fp32_TFLOPs": round(flops / dt / 1e12, 1), "x_read_GBps": round((2 * n_iter + 2) * N * D * e / dt / 1e9, 1),
+            "TFLOPs": round(flops / dt / 1e12, 1), "x_read_GBps": round((2 * n_iter + 2) * N * D * e / dt / 1e9, 1),
+            "hbm_frac": round((2 * n_iter + 2) * N * D * e / dt / 1e9 / HBM_PEAK_GBS, 4),
             "stages_ms": {k: round(v, 3) for k, v in per.items()}}
 
 

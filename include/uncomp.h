@@ -144,8 +144,8 @@ uncomp_status uncomp_head_entropy(uncomp_ctx* ctx, const void* X, uncomp_dtype d
  * (sigma_129 / sigma_k)^(2 n_iter): a few rounds when the spectrum drops before the 129th
  * eigenvalue, many when it is flat there.  entropy_out [n_mat]; eig_out, if not NULL, receives
  * the 128 Ritz values of each matrix as shares of the full trace, descending ([n_mat][128]).
- * X as in uncomp_head_entropy (any ldx >= D; no alignment beyond the element's).  Matrices are
- * processed one after the other.  Workspace: uncomp_matrix_workspace_bytes(N, D).
+ * X as in uncomp_head_entropy (ldx >= D, strides multiples of 8 elements, 16-byte aligned).
+ * Matrices are processed one after the other.  Workspace: uncomp_matrix_workspace_bytes(N, D).
  */
 size_t uncomp_matrix_workspace_bytes(int N, int D);
 uncomp_status uncomp_matrix_entropy(uncomp_ctx* ctx, const void* X, uncomp_dtype dtype,

@@ -305,7 +305,8 @@ uncomp_status uncomp_matrix_entropy(uncomp_ctx* ctx, const void* X, uncomp_dtype
     if (n_iter < 1 || n_iter > 1000) return fail(ctx, UNCOMP_ERR_INVALID_ARG, "matrix_entropy: need 1 <= n_iter <= 1000");
     if (flags & ~(UNCOMP_CENTER | UNCOMP_TRUNC_RENORM | UNCOMP_LAYER_DELTA_INCREASE))
         return fail(ctx, UNCOMP_ERR_UNSUPPORTED, "matrix_entropy: unknown flag bits");
-    if (ldx < D || mat_stride < 0) return fail(ctx, UNCOMP_ERR_INVALID_ARG, "matrix_entropy: ldx >= D, mat_stride >= 0");
+    if (ldx < D || (ldx & 7) || (mat_stride & 7) || mat_stride < 0 || !aligned16(X))
+        return fail(ctx, UNCOMP_ERR_INVALID_ARG, "matrix_entropy: strides must be multiples of 8 elements, ldx >= D, X 16-byte aligned");
     const MatrixPlan p = plan_matrix(N, D);
     if (kBudgetScratch + p.bytes > ctx->ws_bytes)
         return fail(ctx, UNCOMP_ERR_WORKSPACE, "matrix_entropy: needs %zu workspace bytes, context has %zu",

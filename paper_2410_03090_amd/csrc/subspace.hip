@@ -44,38 +44,56 @@ __global__ __launch_bounds__(256) void sub_start_kernel(float* __restrict__ W, i
 }
 
 // Column sums and sums of squares of X over a chunk of tokens, in fp64: part[chunk][2][D].
+// A thread owns 8 consecutive columns (D is a multiple of 128) and reads them with load8.
 template <typename T>
 __global__ __launch_bounds__(256) void sub_colstats_kernel(const T* __restrict__ X, int N, int D, int64_t ldx,
                                                            int chunk, double* __restrict__ part) {
-    const int d = blockIdx.x * 256 + threadIdx.x;
+    const int d = (blockIdx.x * 256 + threadIdx.x) * 8;
     const int c = blockIdx.y;
     if (d >= D) return;
     const int t0 = c * chunk, t1 = min(N, t0 + chunk);
-    double s = 0.0, q = 0.0;
-    for (int t = t0; t < t1; ++t) {
-        const double v = (double)elem(X + (int64_t)t * ldx + d);
-        s += v;
-        q += v * v;
+    double s[8], q[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) s[i] = q[i] = 0.0;
+    for (int t = t0; t < t1; t += 4) {                              // four rows in flight
+        float v[4][8];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) load8(X + (int64_t)min(t + u, t1 - 1) * ldx + d, v[u]);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            if (t + u < t1) {
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    const double x = (double)v[u][i];
+                    s[i] += x;
+                    q[i] = fma(x, x, q[i]);
+                }
+            }
+        }
     }
-    part[((int64_t)c * 2 + 0) * D + d] = s;
-    part[((int64_t)c * 2 + 1) * D + d] = q;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        part[((int64_t)c * 2 + 0) * D + d + i] = s[i];
+        part[((int64_t)c * 2 + 1) * D + d + i] = q[i];
+    }
 }
 
-// s[d] = sum over chunks; trace[0] = sum_d (q_d - s_d^2 / N), trace[1] = sum_d q_d.  One workgroup.
+// s[d] = sum over chunks; tpart[wg] = this workgroup's share of (sum_d (q_d - s_d^2 / N), sum_d q_d).
 __global__ __launch_bounds__(256) void sub_colstats_finish_kernel(const double* __restrict__ part, int n_chunks, int D,
                                                                   int N, double* __restrict__ s,
-                                                                  double* __restrict__ trace) {
+                                                                  double* __restrict__ tpart) {
     __shared__ double red[2][4];
+    const int d = blockIdx.x * 256 + threadIdx.x;
     double tc = 0.0, tu = 0.0;
-    for (int d = threadIdx.x; d < D; d += 256) {
+    if (d < D) {
         double a = 0.0, q = 0.0;
         for (int c = 0; c < n_chunks; ++c) {
             a += part[((int64_t)c * 2 + 0) * D + d];
             q += part[((int64_t)c * 2 + 1) * D + d];
         }
         s[d] = a;
-        tc += q - a * a / (double)N;
-        tu += q;
+        tc = q - a * a / (double)N;
+        tu = q;
     }
     tc = wave_sum(tc);
     tu = wave_sum(tu);
@@ -85,8 +103,16 @@ __global__ __launch_bounds__(256) void sub_colstats_finish_kernel(const double* 
     }
     __syncthreads();
     if (threadIdx.x == 0) {
-        trace[0] = (red[0][0] + red[0][1]) + (red[0][2] + red[0][3]);
-        trace[1] = (red[1][0] + red[1][1]) + (red[1][2] + red[1][3]);
+        tpart[2 * blockIdx.x + 0] = (red[0][0] + red[0][1]) + (red[0][2] + red[0][3]);
+        tpart[2 * blockIdx.x + 1] = (red[1][0] + red[1][1]) + (red[1][2] + red[1][3]);
+    }
+}
+// trace[0] = centred, trace[1] = uncentred trace: the workgroups' shares added in order.
+__global__ void sub_trace_kernel(const double* __restrict__ tpart, int n, double* __restrict__ trace) {
+    if (threadIdx.x < 2) {
+        double t = 0.0;
+        for (int i = 0; i < n; ++i) t += tpart[2 * i + threadIdx.x];
+        trace[threadIdx.x] = t;
     }
 }
 
@@ -166,22 +192,29 @@ __global__ __launch_bounds__(256) void sub_gemm_kernel(const T* __restrict__ A, 
     }
 }
 
-// zsum[j] = sum_d s[d] Q[d][j] (= column sums of Z = X Q), fp64.  One workgroup: thread (slice, j)
-// adds every eighth d, the eight slices meet in LDS.
-__global__ __launch_bounds__(1024) void sub_zsum_kernel(const double* __restrict__ s, const float* __restrict__ Q, int D,
-                                                        double* __restrict__ zsum) {
+// zsum[j] = sum_d s[d] Q[d][j] (= column sums of Z = X Q), fp64, in two steps: workgroup b adds the
+// rows d = b, b + 32, ... (thread (slice, j): every eighth of those), then the 32 partial rows are
+// added in a fixed order.
+constexpr int kZsumParts = 32;
+__global__ __launch_bounds__(1024) void sub_zsum_part_kernel(const double* __restrict__ s, const float* __restrict__ Q,
+                                                             int D, double* __restrict__ zpart) {
     __shared__ double part[8][kP];
     const int j = threadIdx.x & (kP - 1), sl = threadIdx.x >> 7;
     double a = 0.0;
-    for (int d = sl; d < D; d += 8) a += s[d] * (double)Q[(int64_t)d * kP + j];
+    for (int d = blockIdx.x + kZsumParts * sl; d < D; d += kZsumParts * 8) a += s[d] * (double)Q[(int64_t)d * kP + j];
     part[sl][j] = a;
     __syncthreads();
     if (sl == 0) {
         double t = part[0][j];
 #pragma unroll
         for (int x = 1; x < 8; ++x) t += part[x][j];
-        zsum[j] = t;
+        zpart[blockIdx.x * kP + j] = t;
     }
+}
+__global__ __launch_bounds__(128) void sub_zsum_kernel(const double* __restrict__ zpart, double* __restrict__ zsum) {
+    double t = 0.0;
+    for (int b = 0; b < kZsumParts; ++b) t += zpart[b * kP + threadIdx.x];
+    zsum[threadIdx.x] = t;
 }
 
 // W[d][j] = sum over chunks of part[c][d][j] - s[d] zsum[j] / N   (the mean correction of C Q)
@@ -297,7 +330,7 @@ __global__ __launch_bounds__(256) void sub_chol_kernel(const double* __restrict_
 
 MatrixPlan plan_matrix(int N, int D) {
     MatrixPlan p;
-    p.stat_chunks = N < 64 * 256 ? (N + 255) / 256 : 64;
+    p.stat_chunks = N < 128 * 64 ? (N + 63) / 64 : 128;
     p.stat_chunk = (N + p.stat_chunks - 1) / p.stat_chunks;
     p.stat_chunks = (N + p.stat_chunk - 1) / p.stat_chunk;
     // split of the token sum in W = X^T Z: enough workgroups for the chip, partials kept modest
@@ -320,8 +353,8 @@ MatrixPlan plan_matrix(int N, int D) {
     p.ep_off = take(p.ep.bytes);
     p.statpart_off = take((size_t)p.stat_chunks * 2 * D * sizeof(double));
     p.s_off = take((size_t)D * sizeof(double));
-    p.trace_off = take(2 * sizeof(double));
-    p.zsum_off = take(kP * sizeof(double));
+    p.trace_off = take((size_t)(2 + 2 * ((D + 255) / 256)) * sizeof(double));     // the traces, then per-workgroup shares
+    p.zsum_off = take((size_t)(1 + kZsumParts) * kP * sizeof(double));     // the sums, then the partial rows
     p.q_off = take((size_t)D * kP * sizeof(float));
     p.w_off = take((size_t)D * kP * sizeof(float));
     // token chunks of the MFMA version of W = X^T Z (whole rounds of 128 tokens)
@@ -404,16 +437,21 @@ static hipError_t run_matrix_entropy(const T* X, int n_mat, int N, int D, int64_
     for (int m = 0; m < n_mat; ++m) {
         const T* Xm = X + (int64_t)m * mat_stride;
         env.begin("matrix_colstats");
-        sub_colstats_kernel<T><<<dim3((unsigned)((D + 255) / 256), (unsigned)p.stat_chunks), dim3(256), 0, s>>>(
+        sub_colstats_kernel<T><<<dim3((unsigned)((D / 8 + 255) / 256), (unsigned)p.stat_chunks), dim3(256), 0, s>>>(
             Xm, N, D, ldx, p.stat_chunk, statpart);
-        sub_colstats_finish_kernel<<<dim3(1), dim3(256), 0, s>>>(statpart, p.stat_chunks, D, N, sv, trace);
+        sub_colstats_finish_kernel<<<dim3((unsigned)((D + 255) / 256)), dim3(256), 0, s>>>(statpart, p.stat_chunks, D, N, sv,
+                                                                                          trace + 2);
+        sub_trace_kernel<<<dim3(1), dim3(64), 0, s>>>(trace + 2, (D + 255) / 256, trace);
         env.end();
         env.begin("matrix_subspace");
         sub_start_kernel<<<dim3(dp_blocks), dim3(256), 0, s>>>(W, D);
         orth();
         for (int it = 0; it < n_iter; ++it) {
             project(Xm);
-            if (center) sub_zsum_kernel<<<dim3(1), dim3(1024), 0, s>>>(sv, Q, D, zsum);
+            if (center) {
+                sub_zsum_part_kernel<<<dim3(kZsumParts), dim3(1024), 0, s>>>(sv, Q, D, zsum + kP);
+                sub_zsum_kernel<<<dim3(1), dim3(128), 0, s>>>(zsum + kP, zsum);
+            }
             int w_parts = p.w_chunks;
             bool done = false;
             if constexpr (sizeof(T) == 2) {
