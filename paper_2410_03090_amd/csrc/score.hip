@@ -262,12 +262,14 @@ __global__ __launch_bounds__(256, 2) void score_stats_wave_kernel(
                 f32x4_t acc[4];
 #pragma unroll
                 for (int st = 0; st < 4; ++st) acc[st] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+                __builtin_amdgcn_s_setprio(1);                    // matrix work first: the partner wave fills the gaps
 #pragma unroll
                 for (int ks = 0; ks < 4; ++ks)
 #pragma unroll
                     for (int st = 0; st < 4; ++st)
                         acc[st] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
                             __builtin_bit_cast(bf16x8_t, cur[st][ks]), qa[kAhead ? (rb & 1) : 0][ks], acc[st], 0, 0, 0);
+                __builtin_amdgcn_s_setprio(0);
                 // fast path: all 16 logits against the current reference; a sum outside [0, 2^12]
                 // (a logit far above the reference, or no reference yet) takes the slow path
                 float t = 0.f;
@@ -406,12 +408,14 @@ __global__ __launch_bounds__(256) void score_vote_wave_kernel(
             f32x4_t acc[4];
 #pragma unroll
             for (int st = 0; st < 4; ++st) acc[st] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+            __builtin_amdgcn_s_setprio(1);                        // matrix work first: the partner wave fills the gaps
 #pragma unroll
             for (int ks = 0; ks < 4; ++ks)
 #pragma unroll
                 for (int st = 0; st < 4; ++st)
                     acc[st] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
                         rbk.a[ks], __builtin_bit_cast(bf16x8_t, cur[st][ks]), acc[st], 0, 0, 0);
+            __builtin_amdgcn_s_setprio(0);
 #pragma unroll
             for (int st = 0; st < 4; ++st)
                 pq[st] += (__builtin_amdgcn_exp2f(fmaf(acc[st][0], scale2, rbk.nl.x)) +
