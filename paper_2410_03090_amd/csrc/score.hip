@@ -12,11 +12,11 @@
 // exponential.
 #include "common.h"
 #include "device_utils.h"
+#include "score_stats_body.h"
 
 namespace uncomp {
 
 namespace {
-constexpr float kLog2e = 1.4426950408889634f;
 constexpr int kStatTile = 32;     // tokens staged per step in pass 1 (plain-ALU kernel)
 constexpr int kVoteRows = 32;     // query rows staged per step in pass 2 (plain-ALU kernel)
 }
@@ -181,12 +181,6 @@ __global__ __launch_bounds__(256) void score_stats_lastrow_kernel(
 // compiler keep exact counts of the loads in flight (a predicated load makes it wait for all
 // of them), and whatever a token past the end contributes is masked or never stored.
 // ---------------------------------------------------------------------------------------
-namespace {
-
-constexpr int kTile = 64;                 // tokens per key tile
-constexpr int kRowBytes = 2 * kD + 16;    // padded LDS row of one query
-
-}  // namespace
 
 // pass 1 without barriers: same streaming scheme as the vote kernel below (queries in LDS, every
 // wave streams its own key tiles), with the MFMA operands swapped so that an accumulator lane
@@ -202,14 +196,6 @@ __global__ __launch_bounds__(256, 2) void score_stats_wave_kernel(
     const int bh = blockIdx.x / n_chunks, c = blockIdx.x % n_chunks;
     const int b = bh / H, h = bh % H;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-    const int m = lane & 15, g = lane >> 4;
-    const int P = N - w;
-    const int n_rb = R >> 4;
-    const bf16_bits* Kh = K + b * ks_b + h * ks_h;
-    const float scale2 = kLog2e * rsqrtf((float)kD);
-    const int t_begin = c * chunk, t_end = min(N, t_begin + chunk);
-    const int n_tiles = t_end > t_begin ? (t_end - t_begin + kTile - 1) / kTile : 0;
-
     const bf16_bits* Qh = Q + (int64_t)bh * R * kD;
     for (int idx = tid; idx < 16 * NRB * 16; idx += 256) {
         const int row = idx >> 4, piece = idx & 15;
@@ -218,137 +204,10 @@ __global__ __launch_bounds__(256, 2) void score_stats_wave_kernel(
         *reinterpret_cast<uint4*>(qs + row * kRowBytes + piece * 16) = v;
     }
     __syncthreads();
-
-    float nref[NRB], sum[NRB];         // of row 16*rb + m: minus the running reference, sum of exp2(logit - reference)
-#pragma unroll
-    for (int rb = 0; rb < NRB; ++rb) {
-        nref[rb] = INFINITY;
-        sum[rb] = 0.f;
-    }
-    uint4 ka[4][4], kb[4][4];          // [sub-tile][k-step] key operands of two tiles
-    auto load_tile = [&](uint4 dst[4][4], int tile) {            // clamped, never predicated (see ktile_load)
-        const int t0 = t_begin + tile * kTile;
-#pragma unroll
-        for (int st = 0; st < 4; ++st) {
-            const int tok = min(t0 + 16 * st + m, t_end - 1);
-            const bf16_bits* src = Kh + (int64_t)tok * ks_t + 8 * g;
-#pragma unroll
-            for (int ks = 0; ks < 4; ++ks) dst[st][ks] = *reinterpret_cast<const uint4*>(src + 32 * ks);
-        }
-    };
-    auto read_block = [&](bf16x8_t a[4], int rb) {
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks)
-            a[ks] = __builtin_bit_cast(
-                bf16x8_t, *reinterpret_cast<const uint4*>(qs + (16 * rb + m) * kRowBytes + 64 * ks + 16 * g));
-    };
-    auto process = [&](const uint4 cur[4][4], uint4 nxt[4][4], int tile) {
-        load_tile(nxt, tile + 4);
-        const int t0 = t_begin + tile * kTile;
-        const bool edge = t0 + kTile > P || t0 + kTile > t_end;   // causal window or ragged end inside
-        // query operands are read one block ahead where registers allow (NRB = 8)
-        constexpr bool kAhead = NRB <= 8;
-        bf16x8_t qa[kAhead ? 2 : 1][4];
-        if (kAhead) read_block(qa[0], 0);
-#pragma unroll
-        for (int rb = 0; rb < NRB; ++rb) {
-            if (rb < n_rb) {
-                if (kAhead) {
-                    if (rb + 1 < NRB) read_block(qa[(rb + 1) & (kAhead ? 1 : 0)], min(rb + 1, n_rb - 1));
-                } else {
-                    read_block(qa[0], rb);
-                }
-                // acc[st][v] = logit of token t0 + 16 st + 4 g + v against query row 16 rb + m
-                f32x4_t acc[4];
-#pragma unroll
-                for (int st = 0; st < 4; ++st) acc[st] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-                __builtin_amdgcn_s_setprio(1);                    // matrix work first: the partner wave fills the gaps
-#pragma unroll
-                for (int ks = 0; ks < 4; ++ks)
-#pragma unroll
-                    for (int st = 0; st < 4; ++st)
-                        acc[st] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                            __builtin_bit_cast(bf16x8_t, cur[st][ks]), qa[kAhead ? (rb & 1) : 0][ks], acc[st], 0, 0, 0);
-                __builtin_amdgcn_s_setprio(0);
-                // fast path: all 16 logits against the current reference; a sum outside [0, 2^12]
-                // (a logit far above the reference, or no reference yet) takes the slow path
-                float t = 0.f;
-                bool redo = edge;
-                if (!edge) {
-                    float t4[4];
-#pragma unroll
-                    for (int st = 0; st < 4; ++st)
-                        t4[st] = (__builtin_amdgcn_exp2f(fmaf(acc[st][0], scale2, nref[rb])) +
-                                  __builtin_amdgcn_exp2f(fmaf(acc[st][1], scale2, nref[rb]))) +
-                                 (__builtin_amdgcn_exp2f(fmaf(acc[st][2], scale2, nref[rb])) +
-                                  __builtin_amdgcn_exp2f(fmaf(acc[st][3], scale2, nref[rb])));
-                    t = (t4[0] + t4[1]) + (t4[2] + t4[3]);
-                    redo = !(t <= 4096.f);
-                }
-                if (__builtin_amdgcn_ballot_w64(redo) == 0ull) {
-                    sum[rb] += t;
-                } else {
-                    const int last = P + (16 * rb + m) % w;        // last token this row may see
-                    float mx = -INFINITY;
-#pragma unroll
-                    for (int st = 0; st < 4; ++st)
-#pragma unroll
-                        for (int v = 0; v < 4; ++v) {
-                            const int j = t0 + 16 * st + 4 * g + v;
-                            if (j < t_end && j <= last) mx = fmaxf(mx, acc[st][v] * scale2);
-                        }
-                    const float r = -nref[rb];                     // -inf before the first token
-                    if (mx > r) {
-                        sum[rb] *= exp2f(r - mx);                  // exp2(-inf) = 0 on first use
-                        nref[rb] = -mx;
-                    }
-#pragma unroll
-                    for (int st = 0; st < 4; ++st)
-#pragma unroll
-                        for (int v = 0; v < 4; ++v) {
-                            const int j = t0 + 16 * st + 4 * g + v;
-                            if (j < t_end && j <= last) sum[rb] += exp2f(fmaf(acc[st][v], scale2, nref[rb]));
-                        }
-                }
-            }
-        }
-    };
-    if (n_tiles > 0) {
-        load_tile(ka, wv);
-        for (int tile = wv; tile < n_tiles; tile += 8) {
-            process(ka, kb, tile);
-            if (tile + 4 < n_tiles) process(kb, ka, tile + 4);
-        }
-    }
-
-    // the four lane groups saw different tokens of the same rows: combine, then one lane per row writes
-#pragma unroll
-    for (int rb = 0; rb < NRB; ++rb) {
-        if (rb < n_rb) {
-            float r = -nref[rb], sm = sum[rb];
-#pragma unroll
-            for (int o = 16; o < 64; o <<= 1) {
-                const float r2 = __shfl_xor(r, o, 64), s2 = __shfl_xor(sm, o, 64);
-                const float nr = fmaxf(r, r2);
-                const float a = sm > 0.f ? sm * exp2f(r - nr) : 0.f;
-                const float bb = s2 > 0.f ? s2 * exp2f(r2 - nr) : 0.f;
-                r = nr;
-                sm = a + bb;
-            }
-            if (g == 0)
-                stats[((int64_t)bh * (n_chunks * 4) + c * 4 + wv) * R + 16 * rb + m] = make_float2(r, sm);
-        }
-    }
+    const int t_begin = c * chunk, t_end = min(N, t_begin + chunk);
+    score_stats_wave_body<NRB>(qs, K + b * ks_b + h * ks_h, ks_t, t_begin, t_end, N - w, w, R, wv, lane,
+                               stats + ((int64_t)bh * (n_chunks * 4) + c * 4 + wv) * R);
 }
-
-// pass 2: vote[g][j] = sum over the w rows of query head g of exp2(logit - lse), without
-// barriers.  The query rows of the KV head (A operands) and their
-// normalisers sit in LDS for the whole kernel; every wave streams its own 64-token key tiles
-// straight from global memory in B-operand layout (lane = token lane%16 of a sub-tile,
-// features 32ks + 8*(lane/16)..), double-buffered in registers, and walks all 16-row blocks of
-// the head.  Votes of a query head accumulate in-lane over its row blocks, are summed over the
-// four lane groups with three register swaps and stored directly: no barrier, no LDS traffic
-// for keys or partial sums inside the loop.
 template <int NRB>     // LDS is sized for 16*NRB query rows
 __global__ __launch_bounds__(256) void score_vote_wave_kernel(
     const bf16_bits* __restrict__ Q, const bf16_bits* __restrict__ K, const float* __restrict__ lse, int H,
