@@ -331,10 +331,30 @@ def decode_leg(cfg, ctx, score, head_budget, outs, args):
     # per kernel: mean over the last three quarters of the steps (first-touch, clocks)
     kern = {name: sum(v[len(v) // 4:]) / len(v[len(v) // 4:]) for name, v in per.items()}
     avg = sum(kern.values())
+    # the same T steps replayed from a HIP graph (the calls only enqueue kernels): no launch overhead per step
+    graph_us = None
+    try:
+        side = torch.cuda.Stream()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(graph, stream=side):
+                for t in range(T):
+                    ctx.decode_step(qn[t], kn[t], vn[t], pos[t], budget, w, Kc, Vc, idx, cum, ln, out=out, evicted=ev)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        graph.replay()
+        torch.cuda.synchronize()
+        graph_us = (time.perf_counter() - t0) / T * 1e6
+    except Exception as exc:                                   # a torch build without graph support: report, do not fail the bench
+        graph_us = f"unavailable: {exc}"
     e = 2 if cfg.dtype == "bf16" else 4
     byt = rows * 2 * D * e
     return {"steps": T, "kv_heads_per_step": heads, "cache_rows": int(rows), "kernel_us_per_token": round(avg * 1e3, 2),
-            "wall_us_per_token": round(wall / T * 1e6, 2), "algorithmic_bytes": int(byt),
+            "wall_us_per_token": round(wall / T * 1e6, 2),
+            "graph_replay_us_per_token": round(graph_us, 2) if isinstance(graph_us, float) else graph_us,
+            "algorithmic_bytes": int(byt),
             "GBps": round(byt / avg / 1e6, 1), "hbm_frac": round(byt / avg / 1e6 / HBM_PEAK_GBS, 4),
             "kernels_us": {k: round(v * 1e3, 2) for k, v in kern.items()},
             "evicting_heads": int((ev >= 0).sum().item())}

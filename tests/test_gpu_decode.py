@@ -292,6 +292,60 @@ def test_decode_without_output_buffers(ctx):
         assert np.array_equal(raw_bits(a) if isinstance(a, torch.Tensor) else a, raw_bits(b) if isinstance(b, torch.Tensor) else b)
 
 
+def test_decode_steps_replayed_from_a_hip_graph(ctx):
+    """Four decode steps captured in a HIP graph (the calls only enqueue kernels: no allocation, no
+    memset, no synchronisation) give, on every replay, exactly the state and outputs of the eager calls.
+    Replays alternate with eager work and synchronisations."""
+    dtype, G, cap, w, n_heads, T = torch.bfloat16, 4, 300, 8, 12, 4
+    lens = [300, 299, 150, 0, 300, 257, 256, 255, 40, 300, 7, 128]
+    g = torch.Generator().manual_seed(5)
+    q = (torch.randn(T, n_heads, G, D, generator=g) * 2).to(dtype).to(DEV)
+    kn = torch.randn(T, n_heads, D, generator=g).to(dtype).to(DEV)
+    vn = torch.randn(T, n_heads, D, generator=g).to(dtype).to(DEV)
+    pos = [torch.full((n_heads,), 600 + t, dtype=torch.int32, device=DEV) for t in range(T)]
+    bud = torch.randint(w, cap + 20, (n_heads,), generator=g, dtype=torch.int32).to(DEV)
+    start = _random_state(n_heads, cap, lens, [600] * n_heads, dtype, seed=8, w=w)
+    init = [t.clone() for t in (start.Kc, start.Vc, start.idx, start.cum, start.ln)]
+    outs = [torch.empty(n_heads, G, D, device=DEV) for _ in range(T)]
+    evs = [torch.empty(n_heads, dtype=torch.int32, device=DEV) for _ in range(T)]
+
+    def reset():
+        for dst, src in zip((start.Kc, start.Vc, start.idx, start.cum, start.ln), init):
+            dst.copy_(src)
+
+    def run_steps():
+        for t in range(T):
+            ctx.decode_step(q[t], kn[t], vn[t], pos[t], bud, w, start.Kc, start.Vc, start.idx, start.cum, start.ln,
+                            out=outs[t], evicted=evs[t])
+
+    run_steps()                                                   # eager reference (also warms everything up)
+    torch.cuda.synchronize()
+    want = [t.clone() for t in (start.Kc, start.Vc, start.idx, start.cum, start.ln)] + [o.clone() for o in outs] + \
+           [e.clone() for e in evs]
+    reset()
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            run_steps()
+    torch.cuda.synchronize()
+    for replay in range(3):
+        reset()
+        for o in outs:
+            o.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = [start.Kc, start.Vc, start.idx, start.cum, start.ln] + outs + evs
+        for a, b in zip(want, got):
+            assert torch.equal(a, b), f"replay {replay}"
+        # eager work between the replays
+        reset()
+        run_steps()
+        torch.cuda.synchronize()
+
+
 def test_decode_many_heads(ctx):
     """1024 heads with 8 query heads each: enough waves for the 256-rows-per-wave variant (two parts
     per head, the second ragged).  Sampled heads against the oracle."""
