@@ -24,7 +24,6 @@ namespace uncomp {
 typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 
 constexpr int kGramBlocks = 36;                     // upper-triangular 16x16-output blocks
-constexpr int kGramStages = 3;
 
 __device__ __forceinline__ int tri_index(int ca, int cb) { return ca * 8 - ca * (ca - 1) / 2 + (cb - ca); }
 
@@ -47,8 +46,9 @@ __device__ __forceinline__ void gram_transpose(const uint4 raw[8], GramOperands&
 
 constexpr size_t kGramLdsBytes = (4 * kGramBlocks * 256 + 4 * 64 * 8) * sizeof(float);
 
-// One wave's share of a chunk: steps wv, wv + 4, ... of 32 tokens each (wv = 0..3).  `base` points at
+// One wave's share of a chunk: steps wv, wv + kWaves, ... of 32 tokens each (wv = 0..kWaves-1).  `base` points at
 // this lane's 8 features (8 * (lane % 16) ..) of token 0 of the matrix; g = lane / 16.
+template <int kGramStages, int kWaves>   // 32-token steps of loads in flight per wave; waves sharing the chunk
 __device__ __forceinline__ void gram_wave_accumulate(const bf16_bits* __restrict__ base, int64_t ldx, int t_begin,
                                                      int t_end, int wv, int g, f32x4_t acc[kGramBlocks],
                                                      float csum[8]) {
@@ -93,12 +93,12 @@ __device__ __forceinline__ void gram_wave_accumulate(const bf16_bits* __restrict
 
     // this wave's steps: wv, wv+4, ...; three in flight
 #pragma unroll
-    for (int st = 0; st < kGramStages; ++st) load_step(buf[st], wv + 4 * st);
-    for (int s0 = wv; s0 < n_steps; s0 += 4 * kGramStages) {
+    for (int st = 0; st < kGramStages; ++st) load_step(buf[st], wv + kWaves * st);
+    for (int s0 = wv; s0 < n_steps; s0 += kWaves * kGramStages) {
 #pragma unroll
         for (int st = 0; st < kGramStages; ++st) {
             compute_step(buf[st]);
-            load_step(buf[st], s0 + 4 * (st + kGramStages));
+            load_step(buf[st], s0 + kWaves * (st + kGramStages));
         }
     }
 }
@@ -113,6 +113,23 @@ __device__ __forceinline__ void gram_wave_to_lds(float* red, int wv, int lane, c
     float* sums = red + 4 * kGramBlocks * 256;       // [4][64][8]
 #pragma unroll
     for (int i = 0; i < 8; ++i) sums[(wv * 64 + lane) * 8 + i] = csum[i];
+}
+
+// Adds the partials that wave `src` left in LDS to this wave's registers (both hold the same blocks and lanes).
+__device__ __forceinline__ void gram_wave_add_from_lds(const float* red, int src, int lane, f32x4_t acc[kGramBlocks],
+                                                       float csum[8]) {
+    const float* other = red + (size_t)src * (kGramBlocks * 256);
+#pragma unroll
+    for (int b = 0; b < kGramBlocks; ++b) {
+        const float4 v = *reinterpret_cast<const float4*>(other + b * 256 + lane * 4);
+        acc[b][0] += v.x;
+        acc[b][1] += v.y;
+        acc[b][2] += v.z;
+        acc[b][3] += v.w;
+    }
+    const float* sums = red + 4 * kGramBlocks * 256;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) csum[i] += sums[(src * 64 + lane) * 8 + i];
 }
 
 // After the barrier: the four waves' partials are added; `nt` threads write the 128x128 sum of the chunk
