@@ -105,6 +105,15 @@ def test_matrix_entropy_hidden_state_width(ctx):
     np.testing.assert_allclose(eig.cpu().numpy()[:, :32], eref[:, :32], rtol=0, atol=2e-5)
 
 
+def test_matrix_entropy_is_deterministic(ctx):
+    """Fixed start block, fixed-order reductions, no atomics: two runs give the same bits."""
+    X = _lowrank(2, 1500, 768, 50, torch.bfloat16, seed=12).to(DEV)
+    a = ctx.matrix_entropy(X, k_trunc=32, n_iter=6, want_eig=True)
+    b = ctx.matrix_entropy(X, k_trunc=32, n_iter=6, want_eig=True)
+    torch.cuda.synchronize()
+    assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1])
+
+
 def test_matrix_entropy_argument_errors(ctx):
     from paper_2410_03090_amd import binding
     X = torch.zeros(1, 64, 256, dtype=torch.bfloat16, device=DEV)
