@@ -19,6 +19,7 @@ namespace {
 constexpr int kSelThreads = 1024;
 constexpr int kSelWaves = kSelThreads / 64;
 constexpr int kBins = 2048;
+constexpr int kSelLoads = 8;                // 16-byte loads a thread keeps in flight in the range and histogram passes
 
 // float -> uint32 whose unsigned order equals the float order (negative values included)
 __device__ __forceinline__ uint32_t order_key(float f) {
@@ -91,15 +92,22 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const float* __rest
         // per thread in flight; otherwise (and for the tail) plain 4-byte loads
         const int P4 = (P & 3) == 0 ? P >> 2 : 0;
         const float4* sc4 = reinterpret_cast<const float4*>(sc);
-        for (int q0 = tid; q0 < P4; q0 += 2 * kSelThreads) {
-            const float4 a = sc4[q0];
-            const float4 c = q0 + kSelThreads < P4 ? sc4[q0 + kSelThreads] : a;
-            const float vals[8] = {a.x, a.y, a.z, a.w, c.x, c.y, c.z, c.w};
+        for (int q0 = tid; q0 < P4; q0 += kSelLoads * kSelThreads) {
+            float4 v[kSelLoads];                       // kSelLoads 16-byte loads in flight per thread
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const uint32_t key = order_key(vals[e]);
-                kmin = key < kmin ? key : kmin;
-                kmax = key > kmax ? key : kmax;
+            for (int u = 0; u < kSelLoads; ++u) {
+                const int q = q0 + u * kSelThreads;
+                v[u] = sc4[q < P4 ? q : q0];           // past the end: this thread's first one again (min/max unchanged)
+            }
+#pragma unroll
+            for (int u = 0; u < kSelLoads; ++u) {
+                const float vals[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const uint32_t key = order_key(vals[e]);
+                    kmin = key < kmin ? key : kmin;
+                    kmax = key > kmax ? key : kmax;
+                }
             }
         }
         for (int j = 4 * P4 + tid; j < P; j += kSelThreads) {
@@ -138,12 +146,19 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const float* __rest
                 const uint32_t key = order_key(v);
                 if ((key & prefix_mask) == prefix) atomicAdd(&sm.hist[(key >> shift) & (nb - 1)], 1u);
             };
-            for (int q0 = tid; q0 < P4; q0 += 2 * kSelThreads) {
-                const float4 a = sc4[q0];
-                const bool two = q0 + kSelThreads < P4;
-                const float4 c = two ? sc4[q0 + kSelThreads] : a;
-                count(a.x); count(a.y); count(a.z); count(a.w);
-                if (two) { count(c.x); count(c.y); count(c.z); count(c.w); }
+            for (int q0 = tid; q0 < P4; q0 += kSelLoads * kSelThreads) {
+                float4 v[kSelLoads];
+#pragma unroll
+                for (int u = 0; u < kSelLoads; ++u) {
+                    const int q = q0 + u * kSelThreads;
+                    v[u] = sc4[q < P4 ? q : q0];
+                }
+#pragma unroll
+                for (int u = 0; u < kSelLoads; ++u) {
+                    if (q0 + u * kSelThreads < P4) {
+                        count(v[u].x); count(v[u].y); count(v[u].z); count(v[u].w);
+                    }
+                }
             }
             for (int j = 4 * P4 + tid; j < P; j += kSelThreads) count(sc[j]);
             __syncthreads();
