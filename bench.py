@@ -311,7 +311,7 @@ def hidden_leg(cfg, ctx, K, Q, args):
     ctx.profile(False)
     kern = {name: sum(v) / len(v) for name, v in per.items()}
     total = sum(kern.values())
-    byt = B * (2 * H * N * D * e + 2 * n_keep * Dm * e)                 # keys twice (two scoring passes), rows in and out
+    byt = B * ((1 if cfg.dtype == "bf16" else 2) * H * N * D * e + 2 * n_keep * Dm * e)   # keys (once for bf16), rows in and out
     return {"layer_tokens_in": N, "layer_tokens_out": n_keep, "hidden_width": Dm, "kernel_us": round(total * 1e3, 1),
             "algorithmic_bytes": int(byt), "GBps": round(byt / total / 1e6, 1),
             "hbm_frac": round(byt / total / 1e6 / HBM_PEAK_GBS, 4),

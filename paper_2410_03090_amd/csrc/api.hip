@@ -275,12 +275,15 @@ uncomp_status uncomp_select_gather(uncomp_ctx* ctx, const float* score, const in
 namespace {
 struct HiddenPlan {
     ScorePlan sp;
+    LastTokenPlan lt;            // the bf16 path's regions start where the general path's scoring region does
     size_t score_off, sum_off, bytes;
 };
 HiddenPlan plan_hidden(int B, int H, int G, int N, int w) {
     HiddenPlan p;
     p.sp = plan_score(B, H, G, N, 1);
-    p.score_off = align_up(kBudgetScratch + p.sp.bytes, 256);
+    p.lt = plan_last_token(B, H, G, N);
+    const size_t scoring = p.sp.bytes > p.lt.bytes ? p.sp.bytes : p.lt.bytes;
+    p.score_off = align_up(kBudgetScratch + scoring, 256);
     p.sum_off = align_up(p.score_off + (size_t)B * H * (N - 1) * sizeof(float), 256);
     p.bytes = align_up(p.sum_off + (size_t)B * (N - w) * sizeof(float), 256);
     return p;
@@ -362,10 +365,16 @@ uncomp_status uncomp_hidden_evict(uncomp_ctx* ctx, const void* q_last, const voi
     const Env env{static_cast<hipStream_t>(stream), &ctx->prof, ctx->force_alu};
     float* score = reinterpret_cast<float*>(ctx->ws + p.score_off);
     float* sum = score_out != nullptr ? score_out : reinterpret_cast<float*>(ctx->ws + p.sum_off);
-    // the last token's attention = window score with a one-token window and no pooling
-    hipError_t e = launch_window_score(q_last, K, dtype, B, H, G, N, 1, 1, k_strides, p.sp, ctx->ws + kBudgetScratch,
-                                       score, env);
-    if (e == hipSuccess) e = launch_head_sum(score, B, H, N - 1, N - w, sum, env);
+    hipError_t e;
+    if (dtype == UNCOMP_BF16 && !ctx->force_alu && G <= 16) {
+        // bf16: one streamed MFMA pass over the keys and a merge
+        e = launch_last_token_score(q_last, K, B, H, G, N, k_strides, N - w, p.lt, ctx->ws + kBudgetScratch, sum, env);
+    } else {
+        // the last token's attention = window score with a one-token window and no pooling
+        e = launch_window_score(q_last, K, dtype, B, H, G, N, 1, 1, k_strides, p.sp, ctx->ws + kBudgetScratch, score,
+                                env);
+        if (e == hipSuccess) e = launch_head_sum(score, B, H, N - 1, N - w, sum, env);
+    }
     if (e == hipSuccess) e = launch_select_rows(sum, n_keep, 0, B, N, w, cap, idx_out, len_out, env);
     if (e == hipSuccess && Hs != nullptr)
         e = launch_gather_rows(Hs, idx_out, len_out, B, cap, Dm * esz, hs_strides[0] * esz, hs_strides[1] * esz, Hs_out,

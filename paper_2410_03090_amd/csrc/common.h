@@ -119,6 +119,14 @@ hipError_t launch_select_rows(const float* score, const int32_t* budget, int bud
 hipError_t launch_gather_rows(const void* src, const int32_t* idx, const int32_t* len, int n_groups, int cap,
                               int row_bytes, int64_t group_stride_bytes, int64_t row_stride_bytes, void* dst,
                               const Env& env);
+// Workspace of the bf16 last-token attention of the hidden-state eviction.
+struct LastTokenPlan {
+    int GT, wave_rows, s_rows, np;
+    size_t p_off, ml_off, head_off, bytes;
+};
+LastTokenPlan plan_last_token(int B, int H, int G, int N);
+hipError_t launch_last_token_score(const void* q, const void* K, int B, int H, int G, int N, const int64_t ks[3],
+                                   int P_out, const LastTokenPlan& p, char* ws, float* out, const Env& env);
 hipError_t launch_head_sum(const float* score, int B, int H, int P_in, int P_out, float* out, const Env& env);
 hipError_t launch_prepare_reset(int L, int H, int M, double* erank_sum, int32_t* votes, int32_t* count,
                                 const Env& env);

@@ -55,6 +55,17 @@ def test_hidden_evict_matches_oracle(ctx, dtype, H, G, N, w, Dm):
         _compare(ctx, q, K, Hs, Dm, G, n_keep, w, cap=N)
 
 
+def test_hidden_evict_bf16_general_path(ctx):
+    """bf16 through the general scoring kernels (the path fp32 always takes) instead of the MFMA pass."""
+    q, K, Hs = _inputs(2, 3, 4, 700, 128, torch.bfloat16, seed=77)
+    ctx.set_kernel_path(True)
+    try:
+        _compare(ctx, q, K, Hs, 128, 4, 300, 4, cap=700)
+    finally:
+        ctx.set_kernel_path(False)
+    _compare(ctx, q, K, Hs, 128, 4, 300, 4, cap=700)
+
+
 def test_hidden_evict_strided_rows_and_small_cap(ctx):
     q, K, Hs = _inputs(2, 2, 2, 500, 128, torch.bfloat16, seed=5, row_pad=64)        # row stride 192 elements
     _compare(ctx, q, K, Hs, 128, 2, 400, 2, cap=120)                                  # n_keep above cap: clamped to cap
