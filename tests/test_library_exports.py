@@ -47,3 +47,22 @@ def test_product_package_does_not_import_the_oracle():
                 src = open(os.path.join(dirpath, f)).read()
                 assert not re.search(r"^\s*(from|import)\s+\S*oracle", src, flags=re.M), f
                 assert "uncomp_oracle" not in src, f
+
+
+def test_header_is_plain_c(tmp_path):
+    """include/uncomp.h must be usable from C: a C99 translation unit that includes it and takes the
+    address of every declared entry point compiles (syntax and types only; nothing is linked or run)."""
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        import pytest
+        pytest.skip("no C compiler")
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    from paper_2410_03090_amd import binding
+    src = tmp_path / "use_header.c"
+    body = "\n".join(f"    p[{i}] = (fn){name};" for i, name in enumerate(binding.EXPORTS))
+    src.write_text('#include "uncomp.h"\ntypedef void (*fn)(void);\nvoid take(fn* p) {\n' + body + "\n}\n")
+    r = subprocess.run([gcc, "-std=c99", "-pedantic", "-Wall", "-Werror", "-fsyntax-only", "-I", os.path.join(root, "include"), str(src)],
+                       capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
