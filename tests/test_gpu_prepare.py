@@ -20,7 +20,7 @@ def ctx():
     c.close()
 
 
-@pytest.mark.parametrize("L,H,M", [(1, 8, 8), (5, 8, 2), (3, 32, 8), (2, 12, 1), (4, 64, 16)])
+@pytest.mark.parametrize("L,H,M", [(1, 8, 8), (5, 8, 2), (3, 32, 8), (2, 12, 1), (4, 64, 16), (2, 1024, 8)])
 def test_prepare_matches_oracle(ctx, L, H, M):
     g = torch.Generator().manual_seed(L * 100 + H)
     st = ctx.prepare_new(L, H, M)
