@@ -208,7 +208,7 @@ __global__ __launch_bounds__(256, 2) void score_stats_wave_kernel(
     score_stats_wave_body<NRB>(qs, K + b * ks_b + h * ks_h, ks_t, t_begin, t_end, N - w, w, R, wv, lane,
                                stats + ((int64_t)bh * (n_chunks * 4) + c * 4 + wv) * R);
 }
-template <int NRB>     // LDS is sized for 16*NRB query rows
+template <int NRB, bool W8 = false>     // LDS is sized for 16*NRB query rows; W8: the window is 8 positions
 __global__ __launch_bounds__(256) void score_vote_wave_kernel(
     const bf16_bits* __restrict__ Q, const bf16_bits* __restrict__ K, const float* __restrict__ lse, int H,
     int G, int N, int w, int64_t ks_b, int64_t ks_h, int64_t ks_t, int n_chunks, int chunk,
@@ -281,7 +281,21 @@ __global__ __launch_bounds__(256) void score_vote_wave_kernel(
                            __builtin_amdgcn_exp2f(fmaf(acc[st][1], scale2, rbk.nl.y))) +
                           (__builtin_amdgcn_exp2f(fmaf(acc[st][2], scale2, rbk.nl.z)) +
                            __builtin_amdgcn_exp2f(fmaf(acc[st][3], scale2, rbk.nl.w)));
-            if (++in_head == bph) {
+            if constexpr (W8) {
+                // two query heads per row block (rows 0-7 and 8-15, i.e. lane rows 0,1 and 2,3): one
+                // v_permlane16_swap per pair of sub-tiles adds the lane rows pairwise; lane row g then holds
+                // head 2 rb + g / 2, sub-tile g % 2 (first pair) resp. 2 + g % 2 (second pair)
+                auto s01 = __builtin_amdgcn_permlane16_swap(__float_as_uint(pq[0]), __float_as_uint(pq[1]), false, false);
+                auto s23 = __builtin_amdgcn_permlane16_swap(__float_as_uint(pq[2]), __float_as_uint(pq[3]), false, false);
+                const float t01 = __uint_as_float(s01[0]) + __uint_as_float(s01[1]);
+                const float t23 = __uint_as_float(s23[0]) + __uint_as_float(s23[1]);
+                const int head = 2 * qh + (g >> 1);
+                const int j01 = t0 + 16 * (g & 1) + m, j23 = j01 + 32;
+                if (j01 < t_end) vote_h[(int64_t)head * P + j01] = t01;
+                if (j23 < t_end) vote_h[(int64_t)head * P + j23] = t23;
+                pq[0] = pq[1] = pq[2] = pq[3] = 0.f;
+                ++qh;                                 // counts row blocks here
+            } else if (++in_head == bph) {
                 // lane group g now receives the total of sub-tile {0,2,1,3}[g]
                 const float tot = reduce4_over_rows(pq[0], pq[1], pq[2], pq[3]);
                 const int j = t0 + 16 * (((g & 1) << 1) | (g >> 1)) + m;
@@ -519,21 +533,18 @@ static hipError_t run_score(const T* Q, const T* K, int B, int H, int G, int N, 
     if constexpr (sizeof(T) == 2) {
         if (mfma) {
             env.begin("score_vote_wave");
-            if (p.R <= 128) {
-                constexpr int lds_bytes = 16 * 8 * kRowBytes + 16 * 8 * 4;
-                hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(score_vote_wave_kernel<8>),
+            auto launch_vote = [&](auto kern, int lds_bytes) -> hipError_t {
+                hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                                    hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
                 if (e != hipSuccess) return e;
-                score_vote_wave_kernel<8><<<grid1, dim3(256), lds_bytes, s>>>(Q, K, lse, H, G, N, w, ks[0], ks[1], ks[2],
-                                                                              p.n_chunks, p.chunk, vote);
-            } else {
-                constexpr int lds_bytes = 16 * 16 * kRowBytes + 16 * 16 * 4;
-                hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(score_vote_wave_kernel<16>),
-                                                   hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
-                if (e != hipSuccess) return e;
-                score_vote_wave_kernel<16><<<grid1, dim3(256), lds_bytes, s>>>(Q, K, lse, H, G, N, w, ks[0], ks[1], ks[2],
-                                                                               p.n_chunks, p.chunk, vote);
-            }
+                kern<<<grid1, dim3(256), lds_bytes, s>>>(Q, K, lse, H, G, N, w, ks[0], ks[1], ks[2], p.n_chunks, p.chunk, vote);
+                return hipSuccess;
+            };
+            constexpr int lds8 = 16 * 8 * kRowBytes + 16 * 8 * 4, lds16 = 16 * 16 * kRowBytes + 16 * 16 * 4;
+            hipError_t ve;
+            if (w == 8) ve = p.R <= 128 ? launch_vote(score_vote_wave_kernel<8, true>, lds8) : launch_vote(score_vote_wave_kernel<16, true>, lds16);
+            else ve = p.R <= 128 ? launch_vote(score_vote_wave_kernel<8, false>, lds8) : launch_vote(score_vote_wave_kernel<16, false>, lds16);
+            if (ve != hipSuccess) return ve;
             env.end();
         }
     }
@@ -565,8 +576,9 @@ hipError_t launch_window_score(const void* Q, const void* K, uncomp_dtype dt, in
                                int N, int w, int pool, const int64_t ks[3], const ScorePlan& p,
                                char* ws, float* score_out, const Env& env) {
     if (dt == UNCOMP_BF16) {
-        // the MFMA kernels need whole 16-row blocks per query head and at most 256 rows per KV head
-        const bool mfma = !env.force_alu && (w % 16 == 0) && p.R <= 256;
+        // the MFMA kernels need whole 16-row blocks per KV head, a window of 8 (the paper's l) or a multiple of 16,
+        // and at most 256 rows per KV head
+        const bool mfma = !env.force_alu && (w % 16 == 0 || w == 8) && p.R <= 256 && p.R % 16 == 0;
         return run_score<bf16_bits>(static_cast<const bf16_bits*>(Q), static_cast<const bf16_bits*>(K), B, H,
                                     G, N, w, pool, ks, p, ws, score_out, env, mfma);
     }

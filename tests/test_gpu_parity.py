@@ -167,7 +167,8 @@ def test_score_matches_oracle(ctx, dtype, B, H, G, N, w, pool):
     np.testing.assert_allclose(s.cpu().numpy(), ref, rtol=2e-5, atol=1e-12)
 
 
-@pytest.mark.parametrize("G,N,w", [(4, 5000, 32), (4, 9000, 64), (8, 4097, 32), (2, 3000, 16), (1, 700, 48)])
+@pytest.mark.parametrize("G,N,w", [(4, 5000, 32), (4, 9000, 64), (8, 4097, 32), (2, 3000, 16), (1, 700, 48),
+                                   (4, 3000, 8), (2, 777, 8), (8, 2049, 8)])
 def test_score_mfma_and_alu_paths_agree(ctx, G, N, w):
     cfg = synth.tiny_config(dtype="bf16", B=1, H=2, G=G, N=N, w=w, rank_lo=2, rank_hi=64)
     K, V, Q = synth.gen_all(cfg, seed0=G * N)
