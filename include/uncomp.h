@@ -95,7 +95,8 @@ const char* uncomp_last_error(const uncomp_ctx* ctx);
  * caller has synchronised the stream, uncomp_profile_read copies up to max_records
  * (kernel name, milliseconds) pairs in launch order into the HOST arrays names / ms (either
  * may be NULL), clears the records and returns their count (negative = status).  At most
- * 256 launches are kept between reads; later ones go untimed.  Names are static strings. */
+ * 1024 launches are kept between reads; later ones go untimed.  The events are created by
+ * uncomp_profile(ctx, 1) itself, so a timed region creates nothing.  Names are static strings. */
 uncomp_status uncomp_profile(uncomp_ctx* ctx, int on);
 int uncomp_profile_read(uncomp_ctx* ctx, int max_records, const char** names, float* ms);
 
@@ -106,7 +107,10 @@ int uncomp_profile_read(uncomp_ctx* ctx, int max_records, const char** names, fl
  * uncomp_select_gather, or an explicit uncomp_join, makes the caller's stream wait for them.
  * Until then entropy_out / eig_out / the budget outputs are NOT ordered with the caller's
  * stream.  The workspace must hold the entropy and scoring regions side by side, which is
- * what uncomp_workspace_bytes reports. */
+ * what uncomp_workspace_bytes reports.  Every other call that touches the workspace regions
+ * of the side-stream work (a second uncomp_head_entropy, uncomp_decode_step,
+ * uncomp_hidden_evict, uncomp_matrix_entropy, uncomp_prepare_accumulate) joins first by
+ * itself, so calls may follow one another in any order. */
 uncomp_status uncomp_set_overlap(uncomp_ctx* ctx, int on);
 uncomp_status uncomp_join(uncomp_ctx* ctx, void* stream);
 
@@ -187,11 +191,18 @@ uncomp_status uncomp_assign_budgets(uncomp_ctx* ctx, const float* entropy,
  * 0 <= j' < P; score_out[b][h][j] = sum over the G query heads of pooled_q[j], j in [0, P).
  * score_out is dense [B][H][P] floats.  Strides are multiples of 8 elements, K and Qwin
  * 16-byte aligned; G*w <= 512.
+ *
+ * lse_opt (DEVICE, [B][H*G][w] floats, or NULL): the natural-log normaliser of every window
+ * row, lse[b][q][i] = ln sum over j <= P+i of exp(q_i . k_j / sqrt(D)), as the attention
+ * kernel of the model computes it for these rows anyway.  When given, the library skips
+ * its own pass over the keys for the normalisers (half of the key traffic of this call)
+ * and uses these; the caller answers for their accuracy (a relative error e in exp(lse)
+ * becomes a relative error e in that row's votes).  NULL: the library computes them.
  */
 uncomp_status uncomp_window_score(uncomp_ctx* ctx, const void* Qwin, const void* K,
                                   uncomp_dtype dtype, int B, int H, int G, int N, int D,
                                   int w, int pool, const int64_t k_strides[3],
-                                  float* score_out, void* stream);
+                                  const float* lse_opt, float* score_out, void* stream);
 
 /*
  * Per-head top-k and compaction (Sec. 3.3.3: keep the N_{i,g} highest-scoring tokens;
@@ -204,7 +215,8 @@ uncomp_status uncomp_window_score(uncomp_ctx* ctx, const void* Qwin, const void*
  * K_out/V_out[b][h][r][:] = K/V[b][h][idx[r]][:] copied bit for bit.  Rows and indices at
  * r >= len are left untouched.  K and V share kv_strides (element strides of batch, head,
  * token; features contiguous); outputs are dense [B][H][cap][D] / [B][H][cap].
- * Requires w <= cap.  K/V/K_out/V_out may be NULL together to obtain indices only.
+ * Requires w <= cap and score 16-byte aligned.  K/V/K_out/V_out may be NULL together to obtain
+ * indices only.
  */
 uncomp_status uncomp_select_gather(uncomp_ctx* ctx, const float* score, const int32_t* budget,
                                    const void* K, const void* V, uncomp_dtype dtype,
@@ -249,8 +261,12 @@ uncomp_status uncomp_decode_init(uncomp_ctx* ctx, const float* score, const int3
  * old enough to leave appends while n < cap, else drops the token and reports -2.
  * Requires 1 <= w <= cap, 1 <= G <= 16, D == 128, 16-byte aligned q / k_new / v_new / K_c /
  * V_c.  bf16 caches need uncomp_decode_workspace_bytes(n_heads, G, cap) of workspace (partial
- * results of the two kernels the step is split into); fp32 caches need none but are limited
- * to G*(cap + 1) <= 36864.  The workspace is shared with the prefill calls of the context.
+ * results of the two kernels the step is split into) and are limited to caches whose
+ * per-head merge tables fit 64 KiB of LDS (cap up to about 43 000 rows at G > 8, 87 000 at
+ * G > 4, 349 000 at G <= 4 when the launch uses 256-row parts, half of that with 128-row
+ * parts; beyond it UNCOMP_ERR_UNSUPPORTED, before anything is launched); fp32 caches need no
+ * workspace but are limited to G*(cap + 1) <= 36864.  The workspace is shared with the prefill
+ * calls of the context.
  */
 size_t uncomp_decode_workspace_bytes(int n_heads, int G, int cap);
 uncomp_status uncomp_decode_step(uncomp_ctx* ctx, const void* q, const void* k_new,

@@ -22,6 +22,9 @@ Parity status of each function (what pins it lives in tests/test_oracle_*.py):
 * window_score      pinned: uniform-attention closed form (causal harmonic sums),
                     single-row reduction to a library softmax, probability-mass
                     conservation, spike -> plateau behaviour of the max-pool.
+* window_lse        pinned: zero queries give ln(P+i+1), a library logsumexp per causal
+                    row, and exp(logit - lse) summed over the window reproduces window_score
+                    with pool 1.
 * select_gather     pinned: exhaustive subset search on tiny inputs, structural
                     invariants, byte compare of gathered rows.
 * decode_init /     pinned: without eviction the cumulative scores of T decode steps
@@ -207,6 +210,28 @@ def window_score(Qwin: np.ndarray, K: np.ndarray, G: int, pool: int) -> np.ndarr
                 pooled[j] = vote[max(0, j - half): min(P, j + half + 1)].max()
             score[b, h] += pooled
     return score
+
+
+def window_lse(Qwin: np.ndarray, K: np.ndarray, G: int) -> np.ndarray:
+    """Natural-log normaliser of every window row of window_score: for row i of
+    query head q at position P+i, ln sum_{j <= P+i} exp(q_i . k_j / sqrt(D)).  It is
+    what an attention kernel keeps per row beside its output; the library accepts
+    it in place of its own statistics pass.  Returns [B, Hq, w] float64."""
+    Qwin = np.asarray(Qwin, dtype=np.float64)
+    K = np.asarray(K, dtype=np.float64)
+    B, Hq, w, D = Qwin.shape
+    _, H, N, _ = K.shape
+    assert Hq == G * H and 0 < w < N
+    P = N - w
+    out = np.empty((B, Hq, w))
+    for b in range(B):
+        for q in range(Hq):
+            logits = (Qwin[b, q] @ K[b, q // G].T) / np.sqrt(D)      # [w, N]
+            for i in range(w):
+                row = logits[i, : P + i + 1]
+                m = row.max()
+                out[b, q, i] = m + np.log(np.exp(row - m).sum())
+    return out
 
 
 # --------------------------------------------------------------------------

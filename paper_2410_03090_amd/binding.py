@@ -76,7 +76,7 @@ def load_library() -> ctypes.CDLL:
                                           vp, vp, vp, vp, vp]
     lib.uncomp_assign_budgets.restype = i32
     lib.uncomp_window_score.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, i32,
-                                        c.POINTER(i64), vp, vp]
+                                        c.POINTER(i64), vp, vp, vp]
     lib.uncomp_window_score.restype = i32
     lib.uncomp_select_gather.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32,
                                          c.POINTER(i64), i32, vp, vp, vp, vp, vp]
@@ -180,7 +180,7 @@ class Context:
     def set_kernel_path(self, plain_alu: bool):
         self._check(self.lib.uncomp_set_kernel_path(self.handle, 1 if plain_alu else 0))
 
-    def profile_read(self, max_records: int = 256):
+    def profile_read(self, max_records: int = 1024):
         """(kernel name, ms) of every launch since the last read; synchronise the stream first."""
         names = (ctypes.c_char_p * max_records)()
         ms = (ctypes.c_float * max_records)()
@@ -219,17 +219,21 @@ class Context:
             float(eps), int(delta_n), int(flags), _ptr(hb), _ptr(hg), _ptr(lg), _ptr(lt), _stream()))
         return hb, hg, lg, lt
 
-    def window_score(self, Qwin: torch.Tensor, K: torch.Tensor, G: int, pool: int = 7, out=None):
-        """Qwin [B, H*G, w, D] contiguous, K [B, H, N, D] (last dim contiguous).  Returns score [B,H,N-w]."""
+    def window_score(self, Qwin: torch.Tensor, K: torch.Tensor, G: int, pool: int = 7, out=None, lse=None):
+        """Qwin [B, H*G, w, D] contiguous, K [B, H, N, D] (last dim contiguous).  Returns score [B,H,N-w].
+        lse: optional [B, H*G, w] float32 natural-log normalisers of the window rows (skips the library's own
+        statistics pass)."""
         B, Hq, w, D = Qwin.shape
         _, H, N, _ = K.shape
         assert Qwin.is_contiguous() and K.stride(3) == 1 and Hq == H * G and Qwin.dtype == K.dtype
+        if lse is not None:
+            assert lse.shape == (B, Hq, w) and lse.dtype == torch.float32 and lse.is_contiguous()
         if out is None:
             out = torch.empty(B, H, N - w, dtype=torch.float32, device=K.device)
         strides = (ctypes.c_int64 * 3)(K.stride(0), K.stride(1), K.stride(2))
         self._check(self.lib.uncomp_window_score(
             self.handle, Qwin.data_ptr(), K.data_ptr(), _dtype_code(K), B, H, int(G), N, D, w, int(pool),
-            strides, out.data_ptr(), _stream()))
+            strides, _ptr(lse), out.data_ptr(), _stream()))
         return out
 
     def select_gather(self, score: torch.Tensor, budget: torch.Tensor, K, V, w: int, cap: int, out=None,

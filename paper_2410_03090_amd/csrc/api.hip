@@ -57,6 +57,12 @@ uncomp_status uncomp_create(uncomp_ctx** ctx_out, int device, size_t workspace_b
         ctx->num_cu = prop.multiProcessorCount;
         e = hipMalloc(reinterpret_cast<void**>(&ctx->ws), ctx->ws_bytes);
     }
+    // kernels with more than 64 KiB of dynamic LDS get their limit raised here, not in the hot calls
+    if (e == hipSuccess) e = init_gram_kernels();
+    if (e == hipSuccess) e = init_score_kernels();
+    if (e == hipSuccess) e = init_jacobi_kernels();
+    if (e == hipSuccess) e = init_decode_kernels();
+    if (e == hipSuccess) e = init_subspace_kernels();
     if (e == hipSuccess) e = hipStreamCreateWithFlags(&ctx->side, hipStreamNonBlocking);
     if (e == hipSuccess) e = hipEventCreateWithFlags(&ctx->ev_fork, hipEventDisableTiming);
     if (e == hipSuccess) e = hipEventCreateWithFlags(&ctx->ev_join, hipEventDisableTiming);
@@ -102,6 +108,23 @@ size_t uncomp_workspace_bytes(int n_mat, int N, int D, int B, int H, int G, int 
 
 uncomp_status uncomp_profile(uncomp_ctx* ctx, int on) {
     if (ctx == nullptr) return UNCOMP_ERR_INVALID_ARG;
+    if (on != 0 && ctx->prof.n_events < Profiler::kMax) {
+        // every event pair a profiled region may use is created here, outside any timed call
+        int prev = 0;
+        (void)hipGetDevice(&prev);
+        hipError_t e = hipSetDevice(ctx->device);
+        while (e == hipSuccess && ctx->prof.n_events < Profiler::kMax) {
+            const int i = ctx->prof.n_events;
+            e = hipEventCreate(&ctx->prof.start[i]);
+            if (e == hipSuccess) {
+                e = hipEventCreate(&ctx->prof.stop[i]);
+                if (e != hipSuccess) (void)hipEventDestroy(ctx->prof.start[i]);
+            }
+            if (e == hipSuccess) ctx->prof.n_events = i + 1;
+        }
+        (void)hipSetDevice(prev);
+        if (e != hipSuccess) return hip_fail(ctx, e, "profile: hipEventCreate");
+    }
     ctx->prof.on = on != 0;
     ctx->prof.n = 0;
     return UNCOMP_OK;
@@ -163,6 +186,9 @@ uncomp_status uncomp_head_entropy(uncomp_ctx* ctx, const void* X, uncomp_dtype d
     if (kBudgetScratch + p.bytes > ctx->ws_bytes)
         return fail(ctx, UNCOMP_ERR_WORKSPACE, "head_entropy: needs %zu workspace bytes, context has %zu",
                     kBudgetScratch + p.bytes, ctx->ws_bytes);
+    // an eigen stage of an earlier call may still be reading the Gram partials on the side stream
+    uncomp_status js = uncomp_join(ctx, stream);
+    if (js != UNCOMP_OK) return js;
     char* ws = ctx->ws + kBudgetScratch;
     ctx->score_ws_off = kBudgetScratch + p.bytes;
     Env env{static_cast<hipStream_t>(stream), &ctx->prof, ctx->force_alu};
@@ -213,7 +239,8 @@ uncomp_status uncomp_assign_budgets(uncomp_ctx* ctx, const float* entropy, int n
 
 uncomp_status uncomp_window_score(uncomp_ctx* ctx, const void* Qwin, const void* K, uncomp_dtype dtype,
                                   int B, int H, int G, int N, int D, int w, int pool,
-                                  const int64_t k_strides[3], float* score_out, void* stream) {
+                                  const int64_t k_strides[3], const float* lse_opt, float* score_out,
+                                  void* stream) {
     if (ctx == nullptr) return UNCOMP_ERR_INVALID_ARG;
     if (Qwin == nullptr || K == nullptr || score_out == nullptr || k_strides == nullptr)
         return fail(ctx, UNCOMP_ERR_INVALID_ARG, "window_score: null pointer");
@@ -234,7 +261,7 @@ uncomp_status uncomp_window_score(uncomp_ctx* ctx, const void* Qwin, const void*
         return fail(ctx, UNCOMP_ERR_WORKSPACE, "window_score: needs %zu workspace bytes, context has %zu",
                     off + p.bytes, ctx->ws_bytes);
     hipError_t e = launch_window_score(Qwin, K, dtype, B, H, G, N, w, pool, k_strides, p, ctx->ws + off, score_out,
-                                       Env{static_cast<hipStream_t>(stream), &ctx->prof, ctx->force_alu});
+                                       Env{static_cast<hipStream_t>(stream), &ctx->prof, ctx->force_alu}, lse_opt);
     if (e != hipSuccess) return hip_fail(ctx, e, "window_score: launch");
     return UNCOMP_OK;
 }
@@ -254,6 +281,7 @@ uncomp_status uncomp_select_gather(uncomp_ctx* ctx, const float* score, const in
     if (D != kD) return fail(ctx, UNCOMP_ERR_UNSUPPORTED, "select_gather: D must be 128");
     if (w <= 0 || w >= N) return fail(ctx, UNCOMP_ERR_UNSUPPORTED, "select_gather: need 0 < w < N");
     if (cap < w) return fail(ctx, UNCOMP_ERR_INVALID_ARG, "select_gather: cap must be >= w");
+    if (!aligned16(score)) return fail(ctx, UNCOMP_ERR_INVALID_ARG, "select_gather: score must be 16-byte aligned");
     if (all_kv) {
         if (kv_strides == nullptr) return fail(ctx, UNCOMP_ERR_INVALID_ARG, "select_gather: null strides");
         if (kv_strides[2] < D || (kv_strides[0] & 7) || (kv_strides[1] & 7) || (kv_strides[2] & 7) ||
@@ -491,10 +519,16 @@ uncomp_status uncomp_decode_step(uncomp_ctx* ctx, const void* q, const void* k_n
     const bool wave_path = dtype == UNCOMP_BF16 && !ctx->force_alu;
     if (!wave_path && (int64_t)G * ((int64_t)cap + 1) > 36864)
         return fail(ctx, UNCOMP_ERR_UNSUPPORTED, "decode_step: fp32 caches need G*(cap+1) <= 36864");
+    if (wave_path && decode_update_lds_bytes(p) > kLdsDefaultLimit)
+        return fail(ctx, UNCOMP_ERR_UNSUPPORTED, "decode_step: cap %d at G %d needs %zu bytes of LDS per head, limit %zu",
+                    cap, G, decode_update_lds_bytes(p), kLdsDefaultLimit);
     const size_t need = wave_path ? p.bytes : (out == nullptr ? p.p_off : 0);
     if (need > ctx->ws_bytes)
         return fail(ctx, UNCOMP_ERR_WORKSPACE, "decode_step: needs %zu workspace bytes, context has %zu", need,
                     ctx->ws_bytes);
+    // the workspace starts at offset 0: side-stream work of an earlier entropy call may still use it
+    uncomp_status js = uncomp_join(ctx, stream);
+    if (js != UNCOMP_OK) return js;
     // the kernels always form the output; without a destination it lands in the workspace
     float* out_p = out != nullptr ? out : reinterpret_cast<float*>(ctx->ws + p.out_off);
     const Env env{static_cast<hipStream_t>(stream), &ctx->prof, ctx->force_alu};

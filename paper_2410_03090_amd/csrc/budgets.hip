@@ -22,11 +22,11 @@ __global__ __launch_bounds__(256) void head_budget_kernel(const float* __restric
             rank += (v > mine || (v == mine && o < h)) ? 1 : 0;
         }
         const int g = rank / per;
-        int b = n_max - g * step;
-        const int lo = w < N ? w : N;
+        long long b = (long long)n_max - (long long)g * step;      // g*step may exceed 32 bits
+        const long long lo = w < N ? w : N;
         b = b < lo ? lo : b;
         b = b > N ? N : b;
-        head_budget[e] = b;
+        head_budget[e] = (int32_t)b;
         head_group[e] = g;
     }
 }

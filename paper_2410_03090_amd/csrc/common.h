@@ -13,7 +13,7 @@ namespace uncomp {
 // Optional per-kernel timing: when switched on, each kernel launch of a hot call is put
 // between two HIP events recorded on the caller's stream.
 struct Profiler {
-    static constexpr int kMax = 256;
+    static constexpr int kMax = 1024;
     bool on = false;
     int n = 0;                       // records used since the last reset
     int n_events = 0;                // event pairs created so far
@@ -76,11 +76,7 @@ struct Env {
     void begin(const char* kernel_name) const {
         if (prof == nullptr || !prof->on || prof->n >= Profiler::kMax) return;
         int i = prof->n;
-        if (i >= prof->n_events) {
-            if (hipEventCreate(&prof->start[i]) != hipSuccess) return;
-            if (hipEventCreate(&prof->stop[i]) != hipSuccess) return;
-            prof->n_events = i + 1;
-        }
+        if (i >= prof->n_events) return;             // events are created by uncomp_profile, never here
         prof->name[i] = kernel_name;
         (void)hipEventRecord(prof->start[i], s);
     }
@@ -107,9 +103,11 @@ hipError_t launch_budgets(const float* entropy, int L, int B, int H, int M, int 
                           int N, int w, float eps, int delta_n, unsigned flags,
                           int32_t* head_budget, int32_t* head_group, int32_t* layer_group,
                           int32_t* layer_tokens, char* ws, const Env& env);
+// lse_nat: optional DEVICE [B*H*G*w] natural-log normalisers of the window rows; when given the
+// softmax-statistics pass is skipped.
 hipError_t launch_window_score(const void* Q, const void* K, uncomp_dtype dt, int B, int H, int G,
                                int N, int w, int pool, const int64_t ks[3], const ScorePlan& p,
-                               char* ws, float* score_out, const Env& env);
+                               char* ws, float* score_out, const Env& env, const float* lse_nat = nullptr);
 hipError_t launch_select_gather(const float* score, const int32_t* budget, const void* K,
                                 const void* V, uncomp_dtype dt, int B, int H, int N, int w,
                                 const int64_t ks[3], int cap, void* K_out, void* V_out,
@@ -183,5 +181,22 @@ hipError_t launch_decode_step(const void* q, const void* k_new, const void* v_ne
                               int32_t* evicted, const Env& env);
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// LDS a workgroup may use on gfx950 (160 KiB) and what a kernel gets without asking (64 KiB).
+constexpr size_t kLdsPerWorkgroup = 160 * 1024;
+constexpr size_t kLdsDefaultLimit = 64 * 1024;
+
+// Kernels that take more than 64 KiB of dynamic LDS have their limit raised here, once per context
+// at creation (device current), so that no hot call changes function attributes.
+inline hipError_t allow_dynamic_lds(const void* kernel, size_t bytes) {
+    return hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+}
+hipError_t init_gram_kernels();
+hipError_t init_score_kernels();
+hipError_t init_jacobi_kernels();
+hipError_t init_decode_kernels();
+hipError_t init_subspace_kernels();
+// Largest dynamic LDS request of the bf16 decode update kernel (three tables of [np_max][GT] floats).
+size_t decode_update_lds_bytes(const DecodePlan& p);
 
 }  // namespace uncomp

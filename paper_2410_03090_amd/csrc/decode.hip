@@ -724,6 +724,11 @@ hipError_t launch_decode_init(const float* score, const int32_t* idx, const int3
     return hipGetLastError();
 }
 
+// dynamic LDS the one-kernel decode path may ask for: G*(cap+1) <= 36864 floats plus rounding of cap
+constexpr size_t kDecodeStepLdsMax = (36864 + 64) * sizeof(float);
+
+size_t decode_update_lds_bytes(const DecodePlan& p) { return (size_t)3 * p.np_max * p.GT * sizeof(float); }
+
 size_t decode_step_lds_bytes(int G, int cap) {
     const size_t S = ((size_t)cap + 1 + 3) / 4 * 4;
     size_t prob = (size_t)G * S;
@@ -739,13 +744,7 @@ static hipError_t launch_decode_step_t(const void* q, const void* k_new, const v
     const int S = (cap + 1 + 3) / 4 * 4;
     const size_t lds = decode_step_lds_bytes(G, cap);
     auto kern = decode_step_kernel<T, GT>;
-    static size_t lds_allowed = 0;                  // per instantiation: raise the kernel's LDS limit only when needed
-    if (lds > lds_allowed) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        lds_allowed = lds;
-    }
+    if (lds > kDecodeStepLdsMax) return hipErrorInvalidValue;      // the interface checks G*(cap+1) before
     env.begin("decode_step");
     kern<<<n_heads, kDecodeThreads, lds, env.s>>>(static_cast<const T*>(q), static_cast<const T*>(k_new),
                                                   static_cast<const T*>(v_new), G, pos, budget, w, cap,
@@ -771,6 +770,21 @@ hipError_t launch_decode_step(const void* q, const void* k_new, const void* v_ne
     if (G <= 8) UNCOMP_DECODE_CASE(float, 8);
     UNCOMP_DECODE_CASE(float, 16);
 #undef UNCOMP_DECODE_CASE
+}
+
+template <typename T, int GT>
+static hipError_t allow_decode_step() {
+    return allow_dynamic_lds(reinterpret_cast<const void*>(decode_step_kernel<T, GT>), kDecodeStepLdsMax);
+}
+
+hipError_t init_decode_kernels() {
+    hipError_t e = allow_decode_step<bf16_bits, 4>();
+    if (e == hipSuccess) e = allow_decode_step<bf16_bits, 8>();
+    if (e == hipSuccess) e = allow_decode_step<bf16_bits, 16>();
+    if (e == hipSuccess) e = allow_decode_step<float, 4>();
+    if (e == hipSuccess) e = allow_decode_step<float, 8>();
+    if (e == hipSuccess) e = allow_decode_step<float, 16>();
+    return e;
 }
 
 }  // namespace uncomp

@@ -137,9 +137,6 @@ hipError_t launch_gram(const void* X, uncomp_dtype dt, int n_mat, int N, int64_t
     dim3 grid((unsigned)(p.n_chunks * n_mat)), block(256);
     if (dt == UNCOMP_BF16 && !force_alu) {
         constexpr size_t lds = kGramLdsBytes;
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gram_mfma_kernel),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
         env.begin("gram_mfma");
         gram_mfma_kernel<<<grid, dim3(512), lds, s>>>(static_cast<const bf16_bits*>(X), N, mat_stride, ldx,
                                                       p.n_chunks, p.chunk, gram, sums);
@@ -156,6 +153,10 @@ hipError_t launch_gram(const void* X, uncomp_dtype dt, int n_mat, int N, int64_t
     }
     env.end();
     return hipGetLastError();
+}
+
+hipError_t init_gram_kernels() {
+    return allow_dynamic_lds(reinterpret_cast<const void*>(gram_mfma_kernel), kGramLdsBytes);
 }
 
 }  // namespace uncomp

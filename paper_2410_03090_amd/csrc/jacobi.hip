@@ -355,9 +355,6 @@ hipError_t launch_jacobi_entropy(int n_mat, int N, int k_trunc, unsigned flags,
                                  float* eig_out, const Env& env) {
     hipStream_t s = env.s;
     static_assert(sizeof(Smem) <= 160 * 1024, "LDS budget");
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(jacobi_entropy_kernel),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)sizeof(Smem));
-    if (e != hipSuccess) return e;
     const float* gram = reinterpret_cast<const float*>(ws + p.gram_off);
     const float* sums = reinterpret_cast<const float*>(ws + p.sum_off);
     env.begin("jacobi_entropy");
@@ -365,6 +362,10 @@ hipError_t launch_jacobi_entropy(int n_mat, int N, int k_trunc, unsigned flags,
         gram, sums, p.n_chunks, N, k_trunc, flags, entropy_out, eig_out);
     env.end();
     return hipGetLastError();
+}
+
+hipError_t init_jacobi_kernels() {
+    return allow_dynamic_lds(reinterpret_cast<const void*>(jacobi_entropy_kernel), sizeof(Smem));
 }
 
 }  // namespace uncomp

@@ -240,7 +240,7 @@ __global__ __launch_bounds__(256) void score_vote_wave_kernel(
 
     float* vote_h = vote + (int64_t)bh * G * P;
     uint4 ka[4][4], kb[4][4];                        // [sub-tile][k-step] B operands of two tiles
-    auto load_tile = [&](uint4 dst[4][4], int tile) {            // clamped, never predicated (see ktile_load)
+    auto load_tile = [&](uint4 dst[4][4], int tile) {            // clamped, never predicated
         const int t0 = t_begin + tile * kTile;
 #pragma unroll
         for (int st = 0; st < 4; ++st) {
@@ -321,6 +321,13 @@ __global__ __launch_bounds__(256) void score_vote_wave_kernel(
         process(ka, kb, tile);
         if (tile + 4 < n_tiles) process(kb, ka, tile + 4);
     }
+}
+
+// normalisers handed in by the caller (natural log) -> the base-2 ones the vote pass reads
+__global__ __launch_bounds__(256) void score_lse_import_kernel(const float* __restrict__ lse_nat, int n,
+                                                               float* __restrict__ lse) {
+    const int e = blockIdx.x * blockDim.x + threadIdx.x;
+    if (e < n) lse[e] = lse_nat[e] * kLog2e;
 }
 
 // merge: one thread per (head, row)
@@ -451,6 +458,19 @@ __global__ __launch_bounds__(256) void score_pool_kernel(const float* __restrict
     }
 }
 
+// staged query rows of the MFMA kernels: up to 128 / 256 rows per KV head
+constexpr int kScoreLds8 = 16 * 8 * kRowBytes, kScoreLds16 = 16 * 16 * kRowBytes;
+
+hipError_t init_score_kernels() {
+    hipError_t e = allow_dynamic_lds(reinterpret_cast<const void*>(score_stats_wave_kernel<8>), kScoreLds8);
+    if (e == hipSuccess) e = allow_dynamic_lds(reinterpret_cast<const void*>(score_stats_wave_kernel<16>), kScoreLds16);
+    if (e == hipSuccess) e = allow_dynamic_lds(reinterpret_cast<const void*>(score_vote_wave_kernel<8, true>), kScoreLds8 + 16 * 8 * 4);
+    if (e == hipSuccess) e = allow_dynamic_lds(reinterpret_cast<const void*>(score_vote_wave_kernel<8, false>), kScoreLds8 + 16 * 8 * 4);
+    if (e == hipSuccess) e = allow_dynamic_lds(reinterpret_cast<const void*>(score_vote_wave_kernel<16, true>), kScoreLds16 + 16 * 16 * 4);
+    if (e == hipSuccess) e = allow_dynamic_lds(reinterpret_cast<const void*>(score_vote_wave_kernel<16, false>), kScoreLds16 + 16 * 16 * 4);
+    return e;
+}
+
 ScorePlan plan_score(int B, int H, int G, int N, int w) {
     ScorePlan p;
     const int BH = B * H;
@@ -475,7 +495,7 @@ ScorePlan plan_score(int B, int H, int G, int N, int w) {
 template <typename T>
 static hipError_t run_score(const T* Q, const T* K, int B, int H, int G, int N, int w, int pool,
                             const int64_t ks[3], const ScorePlan& p, char* ws, float* score_out,
-                            const Env& env, bool mfma) {
+                            const Env& env, bool mfma, const float* lse_nat) {
     hipStream_t s = env.s;
     const int BH = B * H, P = N - w;
     float2* stats = reinterpret_cast<float2*>(ws + p.stats_off);
@@ -483,21 +503,22 @@ static hipError_t run_score(const T* Q, const T* K, int B, int H, int G, int N, 
     float* vote = reinterpret_cast<float*>(ws + p.vote_off);
     const dim3 grid1((unsigned)(BH * p.n_chunks));
     int n_parts = p.n_chunks;            // partial statistics per query row
+    const int rows = BH * p.R;
+    const bool own_stats = lse_nat == nullptr;
+    if (!own_stats) {
+        env.begin("score_lse_import");
+        score_lse_import_kernel<<<dim3((rows + 255) / 256), dim3(256), 0, s>>>(lse_nat, rows, lse);
+        env.end();
+    }
     if constexpr (sizeof(T) == 2) {
-        if (mfma) {
+        if (mfma && own_stats) {
             env.begin("score_stats_wave");
             if (p.R <= 128) {
-                constexpr int lds_bytes = 16 * 8 * kRowBytes;
-                hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(score_stats_wave_kernel<8>),
-                                                   hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
-                if (e != hipSuccess) return e;
+                constexpr int lds_bytes = kScoreLds8;
                 score_stats_wave_kernel<8><<<grid1, dim3(256), lds_bytes, s>>>(Q, K, H, p.R, N, w, ks[0], ks[1], ks[2],
                                                                                p.n_chunks, p.chunk, stats);
             } else {
-                constexpr int lds_bytes = 16 * 16 * kRowBytes;
-                hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(score_stats_wave_kernel<16>),
-                                                   hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
-                if (e != hipSuccess) return e;
+                constexpr int lds_bytes = kScoreLds16;
                 score_stats_wave_kernel<16><<<grid1, dim3(256), lds_bytes, s>>>(Q, K, H, p.R, N, w, ks[0], ks[1], ks[2],
                                                                                 p.n_chunks, p.chunk, stats);
             }
@@ -505,7 +526,9 @@ static hipError_t run_score(const T* Q, const T* K, int B, int H, int G, int N, 
             n_parts = p.n_chunks * 4;
         }
     }
-    if (!mfma && w == 1 && G <= 16) {
+    if (!own_stats) {
+        // normalisers already in place
+    } else if (!mfma && w == 1 && G <= 16) {
         env.begin("score_stats_lastrow");
         if (G <= 4)
             score_stats_lastrow_kernel<T, 4><<<grid1, dim3(256), 0, s>>>(Q, K, H, G, N, ks[0], ks[1], ks[2], p.n_chunks,
@@ -524,23 +547,21 @@ static hipError_t run_score(const T* Q, const T* K, int B, int H, int G, int N, 
                                                                    p.n_chunks, p.chunk, stats);
         env.end();
     }
-    const int rows = BH * p.R;
-    env.begin("score_lse");
-    score_lse_kernel<<<dim3((rows + 255) / 256), dim3(256), 0, s>>>(stats, rows, p.R, n_parts, lse);
-    env.end();
+    if (own_stats) {
+        env.begin("score_lse");
+        score_lse_kernel<<<dim3((rows + 255) / 256), dim3(256), 0, s>>>(stats, rows, p.R, n_parts, lse);
+        env.end();
+    }
     const int n_tiles = (P + 255) / 256;
     const int n_pool_tiles = (P + kPoolTile - 1) / kPoolTile;
     if constexpr (sizeof(T) == 2) {
         if (mfma) {
             env.begin("score_vote_wave");
             auto launch_vote = [&](auto kern, int lds_bytes) -> hipError_t {
-                hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                                   hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
-                if (e != hipSuccess) return e;
                 kern<<<grid1, dim3(256), lds_bytes, s>>>(Q, K, lse, H, G, N, w, ks[0], ks[1], ks[2], p.n_chunks, p.chunk, vote);
                 return hipSuccess;
             };
-            constexpr int lds8 = 16 * 8 * kRowBytes + 16 * 8 * 4, lds16 = 16 * 16 * kRowBytes + 16 * 16 * 4;
+            constexpr int lds8 = kScoreLds8 + 16 * 8 * 4, lds16 = kScoreLds16 + 16 * 16 * 4;
             hipError_t ve;
             if (w == 8) ve = p.R <= 128 ? launch_vote(score_vote_wave_kernel<8, true>, lds8) : launch_vote(score_vote_wave_kernel<16, true>, lds16);
             else ve = p.R <= 128 ? launch_vote(score_vote_wave_kernel<8, false>, lds8) : launch_vote(score_vote_wave_kernel<16, false>, lds16);
@@ -574,16 +595,16 @@ static hipError_t run_score(const T* Q, const T* K, int B, int H, int G, int N, 
 
 hipError_t launch_window_score(const void* Q, const void* K, uncomp_dtype dt, int B, int H, int G,
                                int N, int w, int pool, const int64_t ks[3], const ScorePlan& p,
-                               char* ws, float* score_out, const Env& env) {
+                               char* ws, float* score_out, const Env& env, const float* lse_nat) {
     if (dt == UNCOMP_BF16) {
         // the MFMA kernels need whole 16-row blocks per KV head, a window of 8 (the paper's l) or a multiple of 16,
         // and at most 256 rows per KV head
         const bool mfma = !env.force_alu && (w % 16 == 0 || w == 8) && p.R <= 256 && p.R % 16 == 0;
         return run_score<bf16_bits>(static_cast<const bf16_bits*>(Q), static_cast<const bf16_bits*>(K), B, H,
-                                    G, N, w, pool, ks, p, ws, score_out, env, mfma);
+                                    G, N, w, pool, ks, p, ws, score_out, env, mfma, lse_nat);
     }
     return run_score<float>(static_cast<const float*>(Q), static_cast<const float*>(K), B, H, G, N, w,
-                            pool, ks, p, ws, score_out, env, false);
+                            pool, ks, p, ws, score_out, env, false, lse_nat);
 }
 
 }  // namespace uncomp

@@ -30,7 +30,7 @@ __device__ __forceinline__ void score_stats_wave_body(const unsigned char* qs, c
         sum[rb] = 0.f;
     }
     uint4 ka[4][4], kb[4][4];          // [sub-tile][k-step] key operands of two tiles
-    auto load_tile = [&](uint4 dst[4][4], int tile) {            // clamped, never predicated (see ktile_load)
+    auto load_tile = [&](uint4 dst[4][4], int tile) {            // clamped, never predicated
         const int t0 = t_begin + tile * kTile;
 #pragma unroll
         for (int st = 0; st < 4; ++st) {

@@ -399,13 +399,6 @@ static hipError_t run_matrix_entropy(const T* X, int n_mat, int N, int D, int64_
     double* gsum = gpart + (size_t)p.gram_slices * kP * kP;
     float* Rinv = reinterpret_cast<float*>(ws + p.rinv_off);
     const size_t chol_lds = (size_t)kP * (kP + 1) * sizeof(double);
-    static bool chol_attr = false;
-    if (!chol_attr) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(sub_chol_kernel),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)chol_lds);
-        if (e != hipSuccess) return e;
-        chol_attr = true;
-    }
     const unsigned dp_blocks = (unsigned)(((int64_t)D * kP + 255) / 256);
     // Q = orth(W): Cholesky QR with the Gram in fp64
     auto orth = [&]() {
@@ -496,6 +489,10 @@ hipError_t launch_matrix_entropy(const void* X, uncomp_dtype dt, int n_mat, int 
                                   p, ws, entropy_out, eig_out, env);
     return run_matrix_entropy(static_cast<const float*>(X), n_mat, N, D, mat_stride, ldx, k_trunc, flags, n_iter, p, ws,
                               entropy_out, eig_out, env);
+}
+
+hipError_t init_subspace_kernels() {
+    return allow_dynamic_lds(reinterpret_cast<const void*>(sub_chol_kernel), (size_t)kP * (kP + 1) * sizeof(double));
 }
 
 }  // namespace uncomp

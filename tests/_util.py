@@ -40,3 +40,40 @@ def check_index_sets(idx_gpu, len_gpu, idx_ref, len_ref, score_ref, w, rel_band=
         assert abs(score_ref[j] - kth) <= band, (
             f"position {j}: score {score_ref[j]!r} differs from k-th {kth!r} by more than the tie band")
     return len(only_gpu)
+
+
+def tie_band_count(idx_ref, n, score_ref, w, rel_band=1e-5):
+    """How many of the kept prefix positions of one head have an oracle score within rel_band
+    (relative) of the oracle's k-th largest score, i.e. could legitimately be swapped for a
+    rejected position of (almost) the same score.  idx_ref: the oracle's kept positions."""
+    k = int(n) - w
+    if k <= 0 or k >= len(score_ref):
+        return 0
+    kth = np.sort(score_ref)[::-1][k - 1]
+    kept = np.asarray(idx_ref[:k]).astype(np.int64)
+    return int(np.sum(np.abs(score_ref[kept] - kth) <= rel_band * abs(kth)))
+
+
+def check_budgets_against_oracle_entropy(budget_gpu, ent_ref, budget_ref, rel_gap=2e-4):
+    """Budgets of the H heads of one (layer, batch) against the budgets the oracle derives from its
+    OWN entropies (rounded to fp32 before ranking).  They must be equal, except that two heads whose
+    oracle entropies differ by less than rel_gap (relative) may have traded places: every pair that
+    the GPU orders against the oracle's entropies must be such a near-tie, and the multiset of
+    budgets must be the oracle's.  Returns the number of heads whose budget differs (0 or more,
+    all of them inside near-ties)."""
+    bg = np.asarray(budget_gpu).astype(np.int64)
+    br = np.asarray(budget_ref).astype(np.int64)
+    e = np.asarray(ent_ref, dtype=np.float64)
+    assert np.array_equal(np.sort(bg), np.sort(br)), (bg, br)
+    if np.array_equal(bg, br):
+        return 0
+    H = len(bg)
+    for a in range(H):
+        for b in range(H):
+            if bg[a] > bg[b] and not (e[a] > e[b] or (e[a] == e[b] and a < b)):
+                # the GPU ranked a above b although the oracle's entropies say otherwise
+                gap = abs(e[a] - e[b]) / max(abs(e[a]), abs(e[b]), 1e-300)
+                assert gap < rel_gap, (
+                    f"heads {a},{b}: budgets {bg[a]},{bg[b]} against oracle entropies {e[a]!r},{e[b]!r} "
+                    f"(relative gap {gap:.3e} is no near-tie)")
+    return int(np.sum(bg != br))

@@ -1,31 +1,38 @@
 """Full-size parity: benchmark configurations 1-4 at their real shapes, in the launch configuration the
 bench times (all layers handed to each call at once, every kernel on one stream; the 128K case also
-with the entropy stage on the side stream).  The oracle checks a sample
-of (layer, batch, head) units element by element; properties that hold at any size are checked on
-every head."""
+with the entropy stage on the side stream, which must give the same bits).
+
+Against the oracle, element by element: one (batch, head) unit of EVERY layer through entropy, score,
+selection and gather, and the budgets of whole (layer, batch) groups against the budgets the oracle
+derives from its own entropies (near-ties of two heads counted, never ignored).  Properties that hold
+at any size are checked on every head."""
 import numpy as np
 import pytest
 import torch
 
 from oracle import uncomp_oracle as O
 from paper_2410_03090_amd import synth
-from tests._util import check_index_sets, raw_bits, to_f64
+from tests._util import (check_budgets_against_oracle_entropy, check_index_sets, raw_bits, tie_band_count, to_f64)
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
+EPS, DELTA_N = 0.4, 512
 
 
-def _sample_units(cfg, n, seed):
-    rng = np.random.default_rng(seed)
-    units = {(0, 0, 0), (cfg.L - 1, cfg.B - 1, cfg.H - 1)}
-    while len(units) < n:
-        units.add((int(rng.integers(cfg.L)), int(rng.integers(cfg.B)), int(rng.integers(cfg.H))))
-    return sorted(units)
+def _run(ctx, cfg, K, V, Q):
+    L, B, H, N, D, G, w = cfg.L, cfg.B, cfg.H, cfg.N, cfg.D, cfg.G, cfg.w
+    LB = L * B
+    Kf, Vf, Qf = K.reshape(LB, H, N, D), V.reshape(LB, H, N, D), Q.reshape(LB, H * G, w, D)
+    ent = ctx.head_entropy(K.reshape(LB * H, N, D), k_trunc=cfg.k_trunc).reshape(L, B, H)
+    hb, hg, lg, lt = ctx.assign_budgets(ent, cfg.M, cfg.n_max, cfg.step, N, w, EPS, DELTA_N)
+    score = ctx.window_score(Qf, Kf, G, cfg.pool)
+    Ko, Vo, idx, ln = ctx.select_gather(score, hb.reshape(LB, H), Kf, Vf, w, cfg.cap)
+    torch.cuda.synchronize()
+    return ent, hb, hg, lg, lt, score, Ko, Vo, idx, ln
 
 
-@pytest.mark.parametrize("ci,n_ent,n_score,overlap", [(1, 24, 6, False), (2, 16, 4, False), (3, 12, 3, False),
-                                                      (3, 4, 1, True), (4, 24, 6, False)])
-def test_full_config(ci, n_ent, n_score, overlap):
+@pytest.mark.parametrize("ci", [1, 2, 3, 4])
+def test_full_config(ci):
     from paper_2410_03090_amd import binding
     cfg = synth.CONFIGS[ci]
     L, B, H, N, D, G, w = cfg.L, cfg.B, cfg.H, cfg.N, cfg.D, cfg.G, cfg.w
@@ -33,18 +40,21 @@ def test_full_config(ci, n_ent, n_score, overlap):
     print(f"\n[{cfg.name}] generating {L}x{B}x{H} heads of {N} tokens", flush=True)
     K, V, Q = synth.gen_all(cfg, seed0=1000 + ci, device=DEV)
     ctx = binding.Context(0, binding.Context.workspace_bytes(LB * H, N, D, LB, H, G, w))
-    ctx.set_overlap(overlap)
-    Kf, Vf, Qf = K.reshape(LB, H, N, D), V.reshape(LB, H, N, D), Q.reshape(LB, H * G, w, D)
-    ent = ctx.head_entropy(K.reshape(LB * H, N, D), k_trunc=cfg.k_trunc).reshape(L, B, H)
-    hb, hg, lg, lt = ctx.assign_budgets(ent, cfg.M, cfg.n_max, cfg.step, N, w, 0.4, 512)
-    score = ctx.window_score(Qf, Kf, G, cfg.pool)
-    Ko, Vo, idx, ln = ctx.select_gather(score, hb.reshape(LB, H), Kf, Vf, w, cfg.cap)
-    torch.cuda.synchronize()
+    out = _run(ctx, cfg, K, V, Q)
+    if ci == 3:
+        # the same step with the eigen stage and the budgets on the side stream: identical bits
+        ctx.set_overlap(True)
+        for _ in range(2):
+            for a, b in zip(out, _run(ctx, cfg, K, V, Q)):
+                assert torch.equal(a, b)
+        ctx.set_overlap(False)
+        print(f"[{cfg.name}] overlap mode: identical results", flush=True)
+    ent, hb, hg, lg, lt, score, Ko, Vo, idx, ln = out
     print(f"[{cfg.name}] GPU path done", flush=True)
 
     ent_h = ent.cpu().numpy()
     # budgets: exact for the entropies the GPU produced, on every (layer, batch)
-    rb = O.assign_budgets(ent_h, cfg.M, cfg.n_max, cfg.step, N, w, 0.4, 512)
+    rb = O.assign_budgets(ent_h, cfg.M, cfg.n_max, cfg.step, N, w, EPS, DELTA_N)
     for got, ref in zip((hb, hg, lg, lt), rb):
         assert np.array_equal(got.cpu().numpy(), ref)
     assert hb.float().mean().item() == pytest.approx(cfg.avg_budget, abs=1e-3)
@@ -60,22 +70,40 @@ def test_full_config(ci, n_ent, n_score, overlap):
     assert np.array_equal(tail, np.broadcast_to(np.arange(P, N), tail.shape))   # window suffix
     assert torch.isfinite(score).all() and (score >= 0).all()
 
-    # entropy on sampled units
-    worst = 0.0
-    for (l, b, h) in _sample_units(cfg, n_ent, ci):
-        Href, _ = O.head_entropy(to_f64(K[l, b, h])[None], k_trunc=cfg.k_trunc)
-        rel = abs(ent_h[l, b, h] - Href[0]) / abs(Href[0])
-        worst = max(worst, rel)
-        assert rel < 1e-4, (l, b, h, ent_h[l, b, h], Href[0])
-    print(f"[{cfg.name}] entropy: worst relative error {worst:.2e} over {n_ent} units", flush=True)
+    # budgets of whole (layer, batch) groups against the oracle's own entropies
+    rng = np.random.default_rng(ci)
+    groups = {(0, 0), (L - 1, B - 1), (int(rng.integers(L)), int(rng.integers(B)))}
+    ent_ref = {}                      # (l, b, h) -> oracle entropy, shared with the per-layer units below
+    differing = 0
+    min_gap = np.inf
+    for (l, b) in sorted(groups):
+        e = np.array([O.head_entropy(to_f64(K[l, b, h])[None], k_trunc=cfg.k_trunc)[0][0] for h in range(H)])
+        for h in range(H):
+            ent_ref[(l, b, h)] = e[h]
+        np.testing.assert_allclose(ent_h[l, b], e, rtol=1e-4)
+        e32 = e.astype(np.float32)              # the oracle ranks the value the interface carries (fp32)
+        ref = O.assign_budgets(e32[None, None], cfg.M, cfg.n_max, cfg.step, N, w, EPS, DELTA_N)[0][0, 0]
+        differing += check_budgets_against_oracle_entropy(hb_h[l * B + b], e32, ref)
+        es = np.sort(e)
+        min_gap = min(min_gap, float(np.min(np.diff(es) / es[1:])))
+        print(f"[{cfg.name}] budgets of (layer {l}, batch {b}) against the oracle's entropies ok", flush=True)
+    print(f"[{cfg.name}] budget groups checked: {len(groups)}, heads inside a near-tie whose budget differs: "
+          f"{differing}, smallest relative entropy gap {min_gap:.2e}", flush=True)
 
-    # score, selection and gather on sampled units
-    swaps = 0
-    for (l, b, h) in _sample_units(cfg, n_score, 100 + ci):
+    # one unit of every layer: entropy, score, selection, gather
+    worst_ent, worst_score, swaps, band = 0.0, 0.0, 0, 0
+    for l in range(L):
+        b, h = int(rng.integers(B)), int(rng.integers(H))
         lb = l * B + b
+        if (l, b, h) not in ent_ref:
+            ent_ref[(l, b, h)] = O.head_entropy(to_f64(K[l, b, h])[None], k_trunc=cfg.k_trunc)[0][0]
+        rel = abs(ent_h[l, b, h] - ent_ref[(l, b, h)]) / abs(ent_ref[(l, b, h)])
+        worst_ent = max(worst_ent, rel)
+        assert rel < 1e-4, (l, b, h, ent_h[l, b, h], ent_ref[(l, b, h)])
         sref = O.window_score(to_f64(Q[l, b, h * G:(h + 1) * G])[None], to_f64(K[l, b, h])[None, None], G, cfg.pool)[0, 0]
         s_gpu = score[lb, h].cpu().numpy()
         np.testing.assert_allclose(s_gpu, sref, rtol=2e-5)
+        worst_score = max(worst_score, float(np.max(np.abs(s_gpu / sref - 1))))
         n = int(ln_h[lb, h])
         # exact given the GPU's own scores
         ref_same = O.select_indices(s_gpu.astype(np.float64), hb_h[lb, h], N, w)
@@ -83,12 +111,15 @@ def test_full_config(ci, n_ent, n_score, overlap):
         # against the oracle's scores: exact up to the 1e-5 tie band
         ref_idx = O.select_indices(sref, hb_h[lb, h], N, w)
         swaps += check_index_sets(idx_h[lb, h], n, ref_idx, len(ref_idx), sref, w)
+        band += tie_band_count(ref_idx, len(ref_idx), sref, w)
         kb, vb = raw_bits(K[l, b, h]), raw_bits(V[l, b, h])
         assert np.array_equal(raw_bits(Ko[lb, h, :n]), kb[idx_h[lb, h, :n]])
         assert np.array_equal(raw_bits(Vo[lb, h, :n]), vb[idx_h[lb, h, :n]])
         assert not raw_bits(Ko[lb, h, n:]).any()
-        print(f"[{cfg.name}] unit {(l, b, h)}: score/select/gather ok", flush=True)
-    print(f"[{cfg.name}] near-tie swaps on sampled heads: {swaps}", flush=True)
+        if l % 8 == 0 or l == L - 1:
+            print(f"[{cfg.name}] layer {l}: unit (batch {b}, head {h}) entropy/score/select/gather ok", flush=True)
+    print(f"[{cfg.name}] {L} units (one per layer): worst relative error entropy {worst_ent:.2e}, score {worst_score:.2e}; "
+          f"kept positions inside the 1e-5 tie band {band}, of which the GPU chose the other side {swaps}", flush=True)
     ctx.close()
-    del K, V, Q, Kf, Vf, Qf, Ko, Vo, score
+    del K, V, Q, Ko, Vo, score, out
     torch.cuda.empty_cache()

@@ -64,3 +64,55 @@ def test_many_short_matrices_and_widest_budget_call():
     for a, b in zip((hb, hg, lg, lt), rb):
         assert np.array_equal(a.cpu().numpy(), b)
     ctx.close()
+
+
+def test_decode_cache_beyond_the_merge_tables_is_refused_before_any_launch():
+    """bf16 decode: the per-head merge tables of the update kernel live in 64 KiB of LDS.  A cache beyond that is
+    UNSUPPORTED (status code, nothing launched, state untouched); one just inside works and matches the oracle."""
+    from paper_2410_03090_amd import binding
+    G, w = 16, 8
+    g = torch.Generator(device=DEV).manual_seed(3)
+    for cap, ok in ((50_000, False), (40_000, True)):
+        n = cap - 5
+        Kc = torch.randn(1, cap, D, generator=g, device=DEV).to(torch.bfloat16)
+        Vc = torch.randn(1, cap, D, generator=g, device=DEV).to(torch.bfloat16)
+        idx = torch.arange(cap, dtype=torch.int32, device=DEV).view(1, cap).contiguous()
+        cum = torch.rand(1, cap, generator=g, device=DEV)
+        ln = torch.tensor([n], dtype=torch.int32, device=DEV)
+        q = (0.3 * torch.randn(1, G, D, generator=g, device=DEV)).to(torch.bfloat16)
+        kn = torch.randn(1, D, generator=g, device=DEV).to(torch.bfloat16)
+        vn = torch.randn(1, D, generator=g, device=DEV).to(torch.bfloat16)
+        pos = torch.tensor([n], dtype=torch.int32, device=DEV)
+        bud = torch.tensor([n], dtype=torch.int32, device=DEV)          # full: the step evicts
+        ctx = binding.Context(0, binding.Context.decode_workspace_bytes(1, G, cap))
+        before = [t.clone() for t in (Kc, Vc, idx, cum, ln)]
+        if not ok:
+            with pytest.raises(binding.UncompError) as e:
+                ctx.decode_step(q, kn, vn, pos, bud, w, Kc, Vc, idx, cum, ln)
+            assert e.value.status == binding.ERR_UNSUPPORTED
+            torch.cuda.synchronize()
+            for a, b in zip(before, (Kc, Vc, idx, cum, ln)):
+                assert torch.equal(a, b)
+        else:
+            out, ev = ctx.decode_step(q, kn, vn, pos, bud, w, Kc, Vc, idx, cum, ln)
+            torch.cuda.synchronize()
+            r = O.decode_step(to_f64(before[0][0, :n]), to_f64(before[1][0, :n]), before[2][0, :n].cpu().numpy(),
+                              before[3][0, :n].cpu().numpy().astype(np.float64), to_f64(q[0]), to_f64(kn[0]), to_f64(vn[0]),
+                              n, n, w)
+            np.testing.assert_allclose(out[0].cpu().numpy(), r[4], atol=2e-5)
+            assert int(ev[0]) == r[5] and int(ln[0]) == len(r[2])
+        ctx.close()
+
+
+def test_budget_arithmetic_beyond_32_bits():
+    """group index times step may exceed 2^31: the budget is still the clamped arithmetic value."""
+    from paper_2410_03090_amd import binding
+    ctx = binding.Context(0, 1 << 20)
+    ent = torch.tensor([[[3.0, 2.5, 2.0, 1.5, 1.0, 0.9, 0.8, 0.1]]], device=DEV)
+    n_max, step, N, w = 2_000_000_000, 1_000_000_000, 2_100_000_000, 8
+    hb, hg, _, _ = ctx.assign_budgets(ent, 8, n_max, step, N, w)
+    torch.cuda.synchronize()
+    ref = O.assign_budgets(ent.cpu().numpy(), 8, n_max, step, N, w, 0.4, 512)
+    assert np.array_equal(hb.cpu().numpy(), ref[0]) and np.array_equal(hg.cpu().numpy(), ref[1])
+    assert hb.cpu().numpy().ravel().tolist() == [2_000_000_000, 1_000_000_000] + [8] * 6
+    ctx.close()

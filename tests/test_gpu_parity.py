@@ -12,7 +12,7 @@ import torch
 
 from oracle import uncomp_oracle as O
 from paper_2410_03090_amd import synth
-from tests._util import check_index_sets, raw_bits, to_f64
+from tests._util import check_budgets_against_oracle_entropy, check_index_sets, raw_bits, to_f64
 
 pytestmark = pytest.mark.gpu
 
@@ -181,6 +181,28 @@ def test_score_mfma_and_alu_paths_agree(ctx, G, N, w):
     np.testing.assert_allclose(a.cpu().numpy(), ref, rtol=2e-5)
 
 
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("G,N,w", [(4, 3000, 8), (4, 2500, 32), (4, 4100, 64), (3, 500, 5)])
+def test_score_with_normalisers_from_the_caller(ctx, dtype, G, N, w):
+    """lse_opt: the natural-log normalisers of the window rows, here the oracle's, replace the library's own
+    statistics pass; the score must equal the oracle's and the one computed without them."""
+    cfg = synth.tiny_config(dtype="f32" if dtype == torch.float32 else "bf16", B=2, H=2, G=G, N=N, w=w, rank_lo=2, rank_hi=48)
+    K, V, Q = synth.gen_all(cfg, seed0=7 * N + w)
+    lse = O.window_lse(to_f64(Q[0]), to_f64(K[0]), G)
+    Qd, Kd = Q[0].to(DEV), K[0].to(DEV)
+    ctx.profile(True)
+    a = ctx.window_score(Qd, Kd, G=G, pool=7, lse=torch.from_numpy(lse.astype(np.float32)).to(DEV))
+    torch.cuda.synchronize()
+    names = [n for n, _ in ctx.profile_read()]
+    ctx.profile(False)
+    assert not any("stats" in n or n == "score_lse" for n in names), names      # the statistics pass really is skipped
+    b = ctx.window_score(Qd, Kd, G=G, pool=7)
+    torch.cuda.synchronize()
+    ref = O.window_score(to_f64(Q[0]), to_f64(K[0]), G=G, pool=7)
+    np.testing.assert_allclose(a.cpu().numpy(), ref, rtol=2e-5, atol=1e-12)
+    np.testing.assert_allclose(a.cpu().numpy(), b.cpu().numpy(), rtol=2e-5, atol=1e-12)
+
+
 def test_score_strided_keys(ctx):
     cfg = synth.tiny_config(dtype="bf16", B=2, H=2, G=2, N=200, w=8)
     K, V, Q = synth.gen_all(cfg, seed0=3)
@@ -259,10 +281,13 @@ def test_end_to_end_config0(ctx):
     # oracle's own entropies wherever those are not within 2e-4 of each other
     rb = O.assign_budgets(ent.cpu().numpy(), cfg.M, cfg.n_max, cfg.step, N, cfg.w, 0.4, 512)
     assert np.array_equal(hb.cpu().numpy(), rb[0]) and np.array_equal(hg.cpu().numpy(), rb[1])
-    rb64 = O.assign_budgets(Href.reshape(nl, B, H).astype(np.float32), cfg.M, cfg.n_max, cfg.step, N, cfg.w, 0.4, 512)
-    gaps = np.abs(np.diff(np.sort(Href.reshape(nl * B, H), axis=1), axis=1)) / np.abs(Href).max()
-    if gaps.min() > 2e-4:
-        assert np.array_equal(hb.cpu().numpy(), rb64[0])
+    e32 = Href.reshape(nl, B, H).astype(np.float32)          # the oracle ranks the fp32 value the interface carries
+    rb64 = O.assign_budgets(e32, cfg.M, cfg.n_max, cfg.step, N, cfg.w, 0.4, 512)
+    differing = 0
+    for l in range(nl):
+        for b in range(B):
+            differing += check_budgets_against_oracle_entropy(hb.cpu().numpy()[l, b], e32[l, b], rb64[0][l, b])
+    print(f"config 0: heads inside a near-tie whose budget differs from the oracle's: {differing}")
     sref = O.window_score(to_f64(Q[0]), to_f64(K[0]), cfg.G, cfg.pool)
     np.testing.assert_allclose(score.cpu().numpy(), sref, rtol=2e-5)
     rKo, rVo, ridx, rln = O.select_gather(sref, hb.cpu().numpy()[0], raw_bits(K[0]), raw_bits(V[0]), cfg.w, cfg.cap)
@@ -311,6 +336,26 @@ def test_overlap_mode_gives_identical_results(ctx):
     torch.cuda.synchronize()
     assert torch.equal(ent.reshape(a[0].shape), a[0])
     c2.close()
+
+
+def test_overlap_mode_back_to_back_entropy_calls():
+    """Two entropy calls in a row with overlap on: the second one's Gram kernel must not overwrite the partial
+    sums the first one's eigen stage is still reading on the side stream."""
+    from paper_2410_03090_amd import binding
+    n_mat, N = 512, 4000
+    Xa = _rand_lowrank(n_mat, N, 128, 24, torch.bfloat16, seed=41).to(DEV)
+    Xb = _rand_lowrank(n_mat, N, 128, 6, torch.bfloat16, seed=42).to(DEV)
+    c = binding.Context(0, binding.Context.workspace_bytes(n_mat, N, 128, 0, 0, 0, 0))
+    ra, rb = c.head_entropy(Xa).clone(), c.head_entropy(Xb).clone()
+    torch.cuda.synchronize()
+    c.set_overlap(True)
+    for _ in range(5):
+        a = c.head_entropy(Xa)
+        b = c.head_entropy(Xb)
+        c.join()
+        torch.cuda.synchronize()
+        assert torch.equal(a, ra) and torch.equal(b, rb)
+    c.close()
 
 
 # ------------------------------------------------------------------------- error paths

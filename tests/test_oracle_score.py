@@ -108,3 +108,29 @@ def test_scale_is_one_over_sqrt_d():
     Q[0, 0, 0, 0] = 8.0
     s = O.window_score(Q, K, G=1, pool=1)[0, 0]
     assert s[0] / s[1] == pytest.approx(math.exp(8.0 / 4.0), rel=1e-12)
+
+
+def test_window_lse_closed_form_library_and_consistency():
+    # zero queries: every logit is 0, the normaliser of row i is ln(number of causal keys)
+    B, H, G, N, D, w = 1, 2, 2, 37, 8, 4
+    P = N - w
+    K = RNG.standard_normal((B, H, N, D))
+    lse0 = O.window_lse(np.zeros((B, H * G, w, D)), K, G)
+    for i in range(w):
+        assert np.allclose(lse0[:, :, i], math.log(P + i + 1), rtol=0, atol=1e-13)
+    # random queries: a library logsumexp over each causal row, with the query head -> KV head map
+    from scipy.special import logsumexp
+    Q = RNG.standard_normal((B, H * G, w, D)) * 3.0
+    lse = O.window_lse(Q, K, G)
+    for q in range(H * G):
+        for i in range(w):
+            row = (K[0, q // G, : P + i + 1] @ Q[0, q, i]) / math.sqrt(D)
+            assert lse[0, q, i] == pytest.approx(logsumexp(row), rel=1e-13)
+    # exp(logit - lse) summed over the window rows and the query heads is the unpooled score
+    s = O.window_score(Q, K, G=G, pool=1)
+    for h in range(H):
+        want = np.zeros(P)
+        for q in range(h * G, (h + 1) * G):
+            for i in range(w):
+                want += np.exp((K[0, h, :P] @ Q[0, q, i]) / math.sqrt(D) - lse[0, q, i])
+        assert np.allclose(s[0, h], want, rtol=1e-12)
