@@ -18,21 +18,43 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
 
-# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, scaled by what the same
-# counters read for a plain 1 GiB device copy (profiles/hbm_traffic_<workload>.txt has the raw
-# figures and the commands).  Keyed by workload, then kernel.
-MEASURED_TRAFFIC_BYTES = {
-    "llama3-8b-128k": {
-        "gram_mfma": int((8.000 + 0.031) * 2**30),
-        "score_stats_wave": int((8.133 + 0.016) * 2**30),
-        "score_vote_wave": int((8.123 + 0.500) * 2**30),
-        "score_pool": int((0.531 + 0.125) * 2**30),
-        "select": int((0.532 + 0.002) * 2**30),
-        "gather": int((0.256 + 0.250) * 2**30),
-        "decode_attend_wave": int((0.252 + 0.012) * 2**30),
-        "gather_rows": int((1.000 + 0.996) * 2**30),
-    },
-}
+PROFILES = os.path.join(ROOT, "profiles")
+CSRC = os.path.join(ROOT, "paper_2410_03090_amd", "csrc")
+
+
+def kernel_sources_hash():
+    """sha256 over the kernel sources, in name order: identifies the kernels a stored measurement belongs to."""
+    import hashlib
+    h = hashlib.sha256()
+    for name in sorted(os.listdir(CSRC)):
+        if name.endswith((".hip", ".h")):
+            h.update(name.encode())
+            with open(os.path.join(CSRC, name), "rb") as f:
+                h.update(f.read())
+    return h.hexdigest()[:16]
+
+
+def measured_traffic(workload):
+    """HBM bytes per launch of each kernel from the stored rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE summary of
+    this workload (profiles/hbm_traffic_<workload>.txt: lines `traffic_bytes <kernel> <fetched> <written>`,
+    already scaled by what the counters read for a plain copy of known size).  Returns ({kernel: bytes},
+    commit, stale): stale is True when the kernel sources have changed since the counters were read, and
+    then no figure is reported."""
+    path = os.path.join(PROFILES, f"hbm_traffic_{workload}.txt")
+    if not os.path.exists(path):
+        return {}, None, None
+    table, commit, src_hash = {}, None, None
+    with open(path) as f:
+        for line in f:
+            t = line.split()
+            if len(t) == 4 and t[0] == "traffic_bytes":
+                table[t[1]] = int(t[2]) + int(t[3])
+            elif len(t) == 2 and t[0] == "measured_at_commit":
+                commit = t[1]
+            elif len(t) == 2 and t[0] == "kernel_sources_sha256":
+                src_hash = t[1]
+    stale = src_hash != kernel_sources_hash()
+    return ({} if stale else table), commit, stale
 
 
 def algorithmic_work(cfg, name):
@@ -72,6 +94,7 @@ def main():
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="also run one plain device copy of this many MiB (reference for HBM byte counters)")
     ap.add_argument("--cpu-heads", type=int, default=0, help="heads in the oracle sample (0 = auto)")
+    ap.add_argument("--no-with-lse", action="store_true", help="skip the leg that hands the row normalisers to uncomp_window_score")
     ap.add_argument("--no-prepare", action="store_true", help="skip the offline-preparation leg")
     ap.add_argument("--no-matrix-entropy", action="store_true", help="skip the wide-matrix (hidden-state) entropy leg")
     ap.add_argument("--no-hidden-evict", action="store_true", help="skip the stage-1 hidden-state eviction leg")
@@ -153,6 +176,20 @@ def main():
         kernels[name] = {"ms": round(avg, 4), "launches": len(v),
                          "GBps": round(byt / avg / 1e6, 1) if byt else None,
                          "TFLOPs": round(flops / avg / 1e9, 1) if flops else None}
+    # what this machine sustains: a plain streaming read and the bf16 MFMA loop (live and zero operands)
+    read_peak, mfma_live, mfma_zero = ctx.measure_peaks(Kf)
+    peaks = {"stream_read_GBps": round(read_peak, 1), "mfma_bf16_loop_TFLOPs_live_operands": round(mfma_live, 1),
+             "mfma_bf16_loop_TFLOPs_zero_operands": round(mfma_zero, 1),
+             "note": "measured by uncomp_measure_peaks on this device; the data-sheet peaks are 8000 GB/s and 2500 TFLOP/s"}
+    traffic, traffic_commit, traffic_stale = measured_traffic(cfg.name)
+    for name, k in kernels.items():
+        if k["GBps"]:
+            k["hbm_frac"] = round(k["GBps"] / HBM_PEAK_GBS, 4)
+            k["hbm_frac_of_measured"] = round(k["GBps"] / read_peak, 4)
+        if k["TFLOPs"]:
+            issued = 36.0 / 64.0 if name == "gram_mfma" else 1.0          # the Gram kernel computes 36 of 64 symmetric blocks
+            k["mfma_frac_issued"] = round(k["TFLOPs"] * issued / MFMA_BF16_PEAK_TFLOPS, 4)
+            k["mfma_frac_issued_of_measured"] = round(k["TFLOPs"] * issued / mfma_live, 4)
     dominant = max(kernels, key=lambda n: kernels[n]["ms"]) if kernels else None
     roofline = None
     if dominant is not None:
@@ -162,14 +199,18 @@ def main():
             ach = byt / avg_ms / 1e6
             roofline = {"kernel": dominant, "bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBS,
                         "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBS, 4),
-                        "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name, {}).get(dominant),
+                        "traffic": traffic.get(dominant),
+                        "traffic_measured_at_commit": traffic_commit, "traffic_stale": traffic_stale,
                         "algorithmic_bytes": int(byt),
+                        "peak_measured": round(read_peak, 1), "frac_of_measured": round(ach / read_peak, 4),
                         "mfma_TFLOPs": round(flops / avg_ms / 1e9, 1) if flops else None,
-                        "mfma_frac": round(flops / avg_ms / 1e9 / MFMA_BF16_PEAK_TFLOPS, 4) if flops else None}
+                        "mfma_frac": round(flops / avg_ms / 1e9 / MFMA_BF16_PEAK_TFLOPS, 4) if flops else None,
+                        "mfma_frac_of_measured": round(flops / avg_ms / 1e9 / mfma_live, 4) if flops else None}
         else:
             roofline = {"kernel": dominant, "bound": "alu", "achieved": None, "peak": None, "unit": "TFLOP/s",
                         "frac": None, "traffic": None}
 
+    with_lse = None if args.no_with_lse else with_lse_leg(cfg, ctx, Kf, Vf, Qf, ent, bud, score, outs, args)
     gram_resident = gram_resident_leg(cfg, ctx, Kf) if cfg.dtype == "bf16" else None
     decode = decode_leg(cfg, ctx, score, bud[0], outs, args) if args.decode_steps > 0 else None
     hidden = None if args.no_hidden_evict else hidden_leg(cfg, ctx, K, Q, args)
@@ -190,10 +231,51 @@ def main():
                    "head_dim": D, "window": w, "pool": cfg.pool, "k_trunc": cfg.k_trunc,
                    "avg_budget": cfg.avg_budget, "mean_kept": round(kept, 1), "rho": round(kept / N, 5),
                    "head_tokens_per_s": round(value * L * H, 1)},
-        "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels, "gram_cache_resident": gram_resident, "decode": decode, "hidden_evict": hidden, "prepare": prepare, "matrix_entropy": matrix,
+        "roofline": roofline, "cpu_baseline": cpu, "peaks": peaks, "kernels": kernels, "with_lse": with_lse, "gram_cache_resident": gram_resident, "decode": decode, "hidden_evict": hidden, "prepare": prepare, "matrix_entropy": matrix,
         "gen_seconds": round(t_gen, 1),
     }
     print(json.dumps(out))
+
+
+def with_lse_leg(cfg, ctx, Kf, Vf, Qf, ent, bud, score, outs, args):
+    """Not part of `value`: the same step when the caller hands uncomp_window_score the row normalisers its
+    attention kernel already has (lse_opt), so the library's statistics pass over the keys is skipped.  The
+    normalisers are formed here once, outside the timed region, with library fp32 matrix products (they stand
+    in for the model's attention kernel)."""
+    import math
+
+    import torch
+    L, B, H, N, D, G, w = cfg.L, cfg.B, cfg.H, cfg.N, cfg.D, cfg.G, cfg.w
+    LB, P = L * B, N - w
+    lse = torch.empty(LB, H * G, w, dtype=torch.float32, device=Kf.device)
+    causal = torch.arange(N, device=Kf.device)[None, :] > (P + torch.arange(w, device=Kf.device))[:, None]      # [w, N]
+    for lb in range(LB):
+        for h in range(H):
+            q = Qf[lb, h * G:(h + 1) * G].reshape(G * w, D).float()
+            logits = (q @ Kf[lb, h].float().T) * (1.0 / math.sqrt(D))
+            logits.view(G, w, N).masked_fill_(causal[None], float("-inf"))
+            lse[lb, h * G:(h + 1) * G] = torch.logsumexp(logits, dim=1).view(G, w)
+    del logits
+
+    def step():
+        ctx.head_entropy(Kf.reshape(LB * H, N, D), k_trunc=cfg.k_trunc, entropy_out=ent.reshape(-1))
+        ctx.assign_budgets(ent, cfg.M, cfg.n_max, cfg.step, N, w, 0.4, 512, out=bud)
+        ctx.window_score(Qf, Kf, G, cfg.pool, out=score, lse=lse)
+        ctx.select_gather(score, bud[0].reshape(LB, H), Kf, Vf, w, cfg.cap, out=outs)
+
+    ref = score.clone()
+    for _ in range(2):
+        step()
+    torch.cuda.synchronize()
+    dev = float(((score - ref).abs() / ref.abs().clamp_min(1e-30)).max().item())
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / args.steps
+    return {"ms_per_step": round(dt * 1e3, 4), "tokens_per_s": round(B * N / dt, 1),
+            "max_rel_dev_of_score_from_the_full_step": float(f"{dev:.3e}"),
+            "note": "uncomp_window_score given lse_opt: no statistics pass; not the headline"}
 
 
 def gram_resident_leg(cfg, ctx, Kf):
@@ -391,26 +473,28 @@ def decode_leg(cfg, ctx, score, head_budget, outs, args):
 
 
 def cpu_baseline(cfg, K, V, Q, args):
-    """Times the float64 oracle on a few (layer, batch, head) units of the same inputs and
-    scales to the whole job.  Baseline only."""
+    """Times the float64 oracle, as it stands, on a few (layer, batch, head) units of the same inputs and
+    scales to the whole job: once with every host thread the numerical library takes, once limited to one
+    thread (a quarter of the sample).  Also counts, on the sampled heads, how many kept positions lie within
+    1e-5 (relative) of the k-th largest score: the band inside which two correct selections may differ.
+    Baseline only."""
     import numpy as np
     import torch
+    from threadpoolctl import threadpool_info, threadpool_limits
 
     from oracle import uncomp_oracle as O
-    try:
-        from threadpoolctl import threadpool_info
-        threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
-    except Exception:
-        threads = os.cpu_count() or 1
+    threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
     L, B, H, N, D, G, w = cfg.L, cfg.B, cfg.H, cfg.N, cfg.D, cfg.G, cfg.w
     units = L * B * H
-    # one head of the 128K config costs the oracle a few seconds: take enough heads for ~20 s
-    est = 0.65 * (N / 131072.0) * (G * w / 256.0)             # seconds per unit, measured once on a 16-core box
-    n_heads = args.cpu_heads or int(max(1, min(units, 64, round(20.0 / est))))
+    # one head of the 128K config costs the oracle about 0.65 s: take enough heads for ~15 s
+    est = 0.65 * (N / 131072.0) * (G * w / 256.0)
+    n_heads = args.cpu_heads or int(max(1, min(units, 64, round(15.0 / est))))
+    n_single = max(1, n_heads // 4)
     f64 = lambda t: t.detach().cpu().to(torch.float64).numpy()
     bits = lambda t: t.detach().cpu().contiguous().view(torch.int16 if t.dtype == torch.bfloat16 else torch.int32).numpy()
-    t_total = 0.0
-    for u in range(n_heads):
+    band = {"kept_prefix_positions": 0, "within_1e-5_of_kth_score": 0}
+
+    def run_unit(u, count_band):
         l, b, h = (u * 7) % L, u % B, (u * 3) % H
         Kh, Vh = K[l, b, h], V[l, b, h]
         Qh = Q[l, b, h * G:(h + 1) * G]
@@ -418,15 +502,30 @@ def cpu_baseline(cfg, K, V, Q, args):
         Kb, Vb = bits(Kh)[None, None], bits(Vh)[None, None]
         t0 = time.perf_counter()
         Hh, _ = O.head_entropy(Kn[0], k_trunc=cfg.k_trunc)
-        ent = np.repeat(Hh.astype(np.float32)[None, None], 1, axis=2)
-        hb, _, _, _ = O.assign_budgets(ent.reshape(1, 1, 1), 1, cfg.avg_budget, 0, N, w, 0.4, 512)
+        e = np.repeat(Hh.astype(np.float32)[None, None], 1, axis=2)
+        hb, _, _, _ = O.assign_budgets(e.reshape(1, 1, 1), 1, cfg.avg_budget, 0, N, w, 0.4, 512)
         s = O.window_score(Qn, Kn, G, cfg.pool)
-        O.select_gather(s, hb[0], Kb, Vb, w, cfg.cap)
-        t_total += time.perf_counter() - t0
-    t_job = t_total / n_heads * units
+        _, _, idx, ln = O.select_gather(s, hb[0], Kb, Vb, w, cfg.cap)
+        dt = time.perf_counter() - t0
+        if count_band:
+            k = int(ln[0, 0]) - w
+            if 0 < k < N - w:
+                row = s[0, 0]
+                kth = np.sort(row)[::-1][k - 1]
+                band["kept_prefix_positions"] += k
+                band["within_1e-5_of_kth_score"] += int(np.sum(np.abs(row[idx[0, 0, :k]] - kth) <= 1e-5 * abs(kth)))
+        return dt
+
+    t_all = sum(run_unit(u, True) for u in range(n_heads))
+    with threadpool_limits(limits=1):
+        t_one = sum(run_unit(u, False) for u in range(n_single))
+    t_job, t_job1 = t_all / n_heads * units, t_one / n_single * units
     return {"value": round(B * N / t_job, 2), "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+            "value_1_thread": round(B * N / t_job1, 2),
             "sample": f"{n_heads} of {units} (layer,batch,head) units of {cfg.name}, all four stages, "
-                      f"{t_total:.1f} s measured, scaled linearly to the whole job"}
+                      f"{t_all:.1f} s measured with {threads} threads; {n_single} units, {t_one:.1f} s, with one thread; "
+                      f"both scaled linearly to the whole job",
+            "tie_band": dict(band, units=n_heads)}
 
 
 if __name__ == "__main__":

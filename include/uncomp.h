@@ -100,6 +100,16 @@ const char* uncomp_last_error(const uncomp_ctx* ctx);
 uncomp_status uncomp_profile(uncomp_ctx* ctx, int on);
 int uncomp_profile_read(uncomp_ctx* ctx, int max_records, const char** names, float* ms);
 
+/* What the device sustains, measured on the spot (not a paper operation; the one call here that
+ * WAITS for its kernels): read_GBps, the rate of a plain streaming read of `bytes` (>= 64 MiB) of
+ * the caller's DEVICE memory at buf (16-byte aligned, contents irrelevant, not written);
+ * mfma_TFLOPs_live / mfma_TFLOPs_zero, the rate of a loop of v_mfma_f32_32x32x16_bf16 at two waves per
+ * SIMD on pseudo-random operands and on zeros (the chip lowers its clock under the switching
+ * activity of live data, so kernels with real operands are bound by the first figure).  The three
+ * results are HOST doubles.  Takes a few tens of milliseconds. */
+uncomp_status uncomp_measure_peaks(uncomp_ctx* ctx, const void* buf, size_t bytes, double* read_GBps,
+                                   double* mfma_TFLOPs_live, double* mfma_TFLOPs_zero, void* stream);
+
 /* Overlap mode (default off).  With on != 0, uncomp_head_entropy runs only its Gram kernel on
  * the caller's stream and moves the eigen stage to a stream owned by the context (ordered
  * after the Gram kernel by an event); a following uncomp_assign_budgets goes to that stream

@@ -23,7 +23,7 @@ DEFAULT_FLAGS = CENTER | TRUNC_RENORM
 
 EXPORTS = (
     "uncomp_create", "uncomp_destroy", "uncomp_workspace_bytes", "uncomp_last_error",
-    "uncomp_profile", "uncomp_profile_read", "uncomp_set_kernel_path", "uncomp_set_overlap", "uncomp_join",
+    "uncomp_profile", "uncomp_profile_read", "uncomp_measure_peaks", "uncomp_set_kernel_path", "uncomp_set_overlap", "uncomp_join",
     "uncomp_head_entropy", "uncomp_assign_budgets", "uncomp_window_score", "uncomp_select_gather",
     "uncomp_decode_init", "uncomp_decode_step", "uncomp_decode_workspace_bytes",
     "uncomp_hidden_evict", "uncomp_hidden_workspace_bytes",
@@ -70,6 +70,9 @@ def load_library() -> ctypes.CDLL:
     lib.uncomp_set_kernel_path.restype = i32
     lib.uncomp_profile_read.argtypes = [vp, i32, c.POINTER(c.c_char_p), c.POINTER(f32)]
     lib.uncomp_profile_read.restype = i32
+    lib.uncomp_measure_peaks.argtypes = [vp, vp, c.c_size_t, c.POINTER(c.c_double), c.POINTER(c.c_double),
+                                         c.POINTER(c.c_double), vp]
+    lib.uncomp_measure_peaks.restype = i32
     lib.uncomp_head_entropy.argtypes = [vp, vp, i32, i32, i32, i32, i64, i64, i32, u32, vp, vp, vp]
     lib.uncomp_head_entropy.restype = i32
     lib.uncomp_assign_budgets.argtypes = [vp, vp, i32, i32, i32, i32, i32, i32, i32, i32, f32, i32, u32,
@@ -179,6 +182,14 @@ class Context:
 
     def set_kernel_path(self, plain_alu: bool):
         self._check(self.lib.uncomp_set_kernel_path(self.handle, 1 if plain_alu else 0))
+
+    def measure_peaks(self, buf: torch.Tensor):
+        """Streaming-read GB/s over `buf` (any device tensor of at least 64 MiB) and the bf16 MFMA loop's TFLOP/s
+        on live and on zero operands.  Synchronises."""
+        r, a, z = ctypes.c_double(), ctypes.c_double(), ctypes.c_double()
+        self._check(self.lib.uncomp_measure_peaks(self.handle, buf.data_ptr(), buf.numel() * buf.element_size(),
+                                                  ctypes.byref(r), ctypes.byref(a), ctypes.byref(z), _stream()))
+        return r.value, a.value, z.value
 
     def profile_read(self, max_records: int = 1024):
         """(kernel name, ms) of every launch since the last read; synchronise the stream first."""

@@ -60,6 +60,7 @@ uncomp_status uncomp_create(uncomp_ctx** ctx_out, int device, size_t workspace_b
     // kernels with more than 64 KiB of dynamic LDS get their limit raised here, not in the hot calls
     if (e == hipSuccess) e = init_gram_kernels();
     if (e == hipSuccess) e = init_score_kernels();
+    if (e == hipSuccess) e = init_select_kernels();
     if (e == hipSuccess) e = init_jacobi_kernels();
     if (e == hipSuccess) e = init_decode_kernels();
     if (e == hipSuccess) e = init_subspace_kernels();
@@ -166,6 +167,25 @@ int uncomp_profile_read(uncomp_ctx* ctx, int max_records, const char** names, fl
     return n;
 }
 
+uncomp_status uncomp_measure_peaks(uncomp_ctx* ctx, const void* buf, size_t bytes, double* read_GBps,
+                                   double* mfma_TFLOPs_live, double* mfma_TFLOPs_zero, void* stream) {
+    if (ctx == nullptr) return UNCOMP_ERR_INVALID_ARG;
+    if (buf == nullptr || read_GBps == nullptr || mfma_TFLOPs_live == nullptr || mfma_TFLOPs_zero == nullptr)
+        return fail(ctx, UNCOMP_ERR_INVALID_ARG, "measure_peaks: null pointer");
+    if (bytes < (64u << 20) || !aligned16(buf))
+        return fail(ctx, UNCOMP_ERR_INVALID_ARG, "measure_peaks: need at least 64 MiB of 16-byte aligned device memory");
+    uncomp_status js = uncomp_join(ctx, stream);                 // the sink word is the start of the workspace
+    if (js != UNCOMP_OK) return js;
+    double out[3] = {0.0, 0.0, 0.0};
+    hipError_t e = measure_peaks(buf, bytes / 16, ctx->num_cu, reinterpret_cast<uint32_t*>(ctx->ws),
+                                 static_cast<hipStream_t>(stream), out);
+    if (e != hipSuccess) return hip_fail(ctx, e, "measure_peaks");
+    *read_GBps = out[0];
+    *mfma_TFLOPs_live = out[1];
+    *mfma_TFLOPs_zero = out[2];
+    return UNCOMP_OK;
+}
+
 const char* uncomp_last_error(const uncomp_ctx* ctx) { return ctx != nullptr ? ctx->err : "null context"; }
 
 uncomp_status uncomp_head_entropy(uncomp_ctx* ctx, const void* X, uncomp_dtype dtype, int n_mat,
@@ -186,6 +206,7 @@ uncomp_status uncomp_head_entropy(uncomp_ctx* ctx, const void* X, uncomp_dtype d
     if (kBudgetScratch + p.bytes > ctx->ws_bytes)
         return fail(ctx, UNCOMP_ERR_WORKSPACE, "head_entropy: needs %zu workspace bytes, context has %zu",
                     kBudgetScratch + p.bytes, ctx->ws_bytes);
+    ctx->key_range.ptr = nullptr;
     // an eigen stage of an earlier call may still be reading the Gram partials on the side stream
     uncomp_status js = uncomp_join(ctx, stream);
     if (js != UNCOMP_OK) return js;
@@ -260,9 +281,15 @@ uncomp_status uncomp_window_score(uncomp_ctx* ctx, const void* Qwin, const void*
     if (off + p.bytes > ctx->ws_bytes)
         return fail(ctx, UNCOMP_ERR_WORKSPACE, "window_score: needs %zu workspace bytes, context has %zu",
                     off + p.bytes, ctx->ws_bytes);
+    ctx->key_range.ptr = nullptr;
     hipError_t e = launch_window_score(Qwin, K, dtype, B, H, G, N, w, pool, k_strides, p, ctx->ws + off, score_out,
                                        Env{static_cast<hipStream_t>(stream), &ctx->prof, ctx->force_alu}, lse_opt);
     if (e != hipSuccess) return hip_fail(ctx, e, "window_score: launch");
+    ctx->key_range.ptr = reinterpret_cast<const uint32_t*>(ctx->ws + off + p.range_off);
+    ctx->key_range.score = score_out;
+    ctx->key_range.groups = B * H;
+    ctx->key_range.P = N - w;
+    ctx->key_range.n_tiles = p.n_range_tiles;
     return UNCOMP_OK;
 }
 
@@ -293,9 +320,13 @@ uncomp_status uncomp_select_gather(uncomp_ctx* ctx, const float* score, const in
     static const int64_t zero_strides[3] = {0, 0, 0};
     uncomp_status js = uncomp_join(ctx, stream);
     if (js != UNCOMP_OK) return js;
+    // key ranges of these very scores, if uncomp_window_score has just left them in the workspace
+    const bool ranged = ctx->key_range.ptr != nullptr && ctx->key_range.score == score &&
+                        ctx->key_range.groups == B * H && ctx->key_range.P == N - w;
     hipError_t e = launch_select_gather(score, budget, all_kv ? K : nullptr, V, dtype, B, H, N, w,
                                         all_kv ? kv_strides : zero_strides, cap, K_out, V_out, idx_out, len_out,
-                                        Env{static_cast<hipStream_t>(stream), &ctx->prof, ctx->force_alu});
+                                        Env{static_cast<hipStream_t>(stream), &ctx->prof, ctx->force_alu},
+                                        ranged ? ctx->key_range.ptr : nullptr, ranged ? ctx->key_range.n_tiles : 0);
     if (e != hipSuccess) return hip_fail(ctx, e, "select_gather: launch");
     return UNCOMP_OK;
 }
@@ -342,6 +373,7 @@ uncomp_status uncomp_matrix_entropy(uncomp_ctx* ctx, const void* X, uncomp_dtype
     if (kBudgetScratch + p.bytes > ctx->ws_bytes)
         return fail(ctx, UNCOMP_ERR_WORKSPACE, "matrix_entropy: needs %zu workspace bytes, context has %zu",
                     kBudgetScratch + p.bytes, ctx->ws_bytes);
+    ctx->key_range.ptr = nullptr;
     uncomp_status js = uncomp_join(ctx, stream);
     if (js != UNCOMP_OK) return js;
     hipError_t e = launch_matrix_entropy(X, dtype, n_mat, N, D, mat_stride, ldx, k_trunc, flags, n_iter, p,
@@ -388,6 +420,7 @@ uncomp_status uncomp_hidden_evict(uncomp_ctx* ctx, const void* q_last, const voi
     if (p.bytes > ctx->ws_bytes)
         return fail(ctx, UNCOMP_ERR_WORKSPACE, "hidden_evict: needs %zu workspace bytes, context has %zu", p.bytes,
                     ctx->ws_bytes);
+    ctx->key_range.ptr = nullptr;
     uncomp_status js = uncomp_join(ctx, stream);          // the whole workspace is used: wait for side-stream work
     if (js != UNCOMP_OK) return js;
     const Env env{static_cast<hipStream_t>(stream), &ctx->prof, ctx->force_alu};
@@ -405,8 +438,8 @@ uncomp_status uncomp_hidden_evict(uncomp_ctx* ctx, const void* q_last, const voi
     }
     if (e == hipSuccess) e = launch_select_rows(sum, n_keep, 0, B, N, w, cap, idx_out, len_out, env);
     if (e == hipSuccess && Hs != nullptr)
-        e = launch_gather_rows(Hs, idx_out, len_out, B, cap, Dm * esz, hs_strides[0] * esz, hs_strides[1] * esz, Hs_out,
-                               env);
+        e = launch_gather_rows(Hs, idx_out, len_out, B, cap, N, Dm * esz, hs_strides[0] * esz, hs_strides[1] * esz,
+                               Hs_out, env);
     if (e != hipSuccess) return hip_fail(ctx, e, "hidden_evict: launch");
     return UNCOMP_OK;
 }
@@ -527,6 +560,7 @@ uncomp_status uncomp_decode_step(uncomp_ctx* ctx, const void* q, const void* k_n
         return fail(ctx, UNCOMP_ERR_WORKSPACE, "decode_step: needs %zu workspace bytes, context has %zu", need,
                     ctx->ws_bytes);
     // the workspace starts at offset 0: side-stream work of an earlier entropy call may still use it
+    ctx->key_range.ptr = nullptr;
     uncomp_status js = uncomp_join(ctx, stream);
     if (js != UNCOMP_OK) return js;
     // the kernels always form the output; without a destination it lands in the workspace

@@ -37,6 +37,14 @@ struct uncomp_ctx {
     hipStream_t side = nullptr;
     hipEvent_t ev_fork = nullptr, ev_join = nullptr;
     size_t score_ws_off = 0;         // where the scoring workspace starts (after the entropy region)
+    // Key ranges left in the workspace by the last uncomp_window_score, for the selection that follows it.
+    // Cleared by every call that may overwrite that part of the workspace; the selection kernel checks the
+    // range against every score anyway, so a range that does not belong to the scores costs time, not results.
+    struct {
+        const uint32_t* ptr = nullptr;
+        const float* score = nullptr;
+        int groups = 0, P = 0, n_tiles = 0;
+    } key_range;
 };
 
 namespace uncomp {
@@ -63,6 +71,8 @@ struct ScorePlan {
     size_t stats_off;    // float2 [BH][n_chunks][R]   (running max, running sum)
     size_t lse_off;      // float  [BH][R]
     size_t vote_off;     // float  [BH][G][P]
+    size_t range_off;    // uint32 [BH][n_range_tiles][2]: smallest / largest selection key of every 1024 scores
+    int n_range_tiles;
     size_t bytes;
 };
 ScorePlan plan_score(int B, int H, int G, int N, int w);
@@ -111,12 +121,13 @@ hipError_t launch_window_score(const void* Q, const void* K, uncomp_dtype dt, in
 hipError_t launch_select_gather(const float* score, const int32_t* budget, const void* K,
                                 const void* V, uncomp_dtype dt, int B, int H, int N, int w,
                                 const int64_t ks[3], int cap, void* K_out, void* V_out,
-                                int32_t* idx_out, int32_t* len_out, const Env& env);
+                                int32_t* idx_out, int32_t* len_out, const Env& env,
+                                const uint32_t* tile_range = nullptr, int n_range_tiles = 0);
 hipError_t launch_select_rows(const float* score, const int32_t* budget, int budget_stride, int n_groups,
                               int N, int w, int cap, int32_t* idx_out, int32_t* len_out, const Env& env);
 hipError_t launch_gather_rows(const void* src, const int32_t* idx, const int32_t* len, int n_groups, int cap,
-                              int row_bytes, int64_t group_stride_bytes, int64_t row_stride_bytes, void* dst,
-                              const Env& env);
+                              int n_src_rows, int row_bytes, int64_t group_stride_bytes, int64_t row_stride_bytes,
+                              void* dst, const Env& env);
 // Workspace of the bf16 last-token attention of the hidden-state eviction.
 struct LastTokenPlan {
     int GT, wave_rows, s_rows, np;
@@ -191,7 +202,9 @@ constexpr size_t kLdsDefaultLimit = 64 * 1024;
 inline hipError_t allow_dynamic_lds(const void* kernel, size_t bytes) {
     return hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
 }
+hipError_t measure_peaks(const void* buf, size_t n16, int num_cu, uint32_t* sink, hipStream_t s, double out[3]);
 hipError_t init_gram_kernels();
+hipError_t init_select_kernels();
 hipError_t init_score_kernels();
 hipError_t init_jacobi_kernels();
 hipError_t init_decode_kernels();

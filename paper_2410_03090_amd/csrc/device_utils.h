@@ -50,6 +50,13 @@ __device__ __forceinline__ float reduce4_over_rows(float x, float y, float z, fl
     return __uint_as_float(s3[0]) + __uint_as_float(s3[1]);
 }
 
+// float -> uint32 whose unsigned order equals the float order (negative values included; -0.0 and +0.0
+// get the same key).  The selection kernels rank scores by this key.
+__device__ __forceinline__ uint32_t order_key(float f) {
+    uint32_t u = __float_as_uint(f + 0.0f);
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
 __device__ __forceinline__ float wave_max(float v) {
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));

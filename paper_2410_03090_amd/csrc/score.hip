@@ -407,8 +407,10 @@ constexpr int kPoolTile = 1024;
 
 template <int HALF>
 __global__ __launch_bounds__(256) void score_pool_kernel(const float* __restrict__ vote, int G, int P,
-                                                         int n_tiles, float* __restrict__ score) {
+                                                         int n_tiles, float* __restrict__ score,
+                                                         uint32_t* __restrict__ tile_range) {
     __shared__ float sh[4][kPoolTile + 2 * HALF + 4];
+    __shared__ uint32_t wave_range[4][2];
     const int bh = blockIdx.x / n_tiles, tile = blockIdx.x % n_tiles;
     const int tile0 = tile * kPoolTile;
     const int tid = threadIdx.x;
@@ -451,10 +453,37 @@ __global__ __launch_bounds__(256) void score_pool_kernel(const float* __restrict
         }
         __syncthreads();
     }
+    // the tile's smallest and largest selection key ride along: the top-k kernel starts from them instead of
+    // reading every score once more to find their range
+    uint32_t kmin = 0xffffffffu, kmax = 0u;
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
         const int j = tile0 + 4 * tid + e;
-        if (j < P) score[(int64_t)bh * P + j] = total[e];
+        if (j < P) {
+            score[(int64_t)bh * P + j] = total[e];
+            const uint32_t key = order_key(total[e]);
+            kmin = key < kmin ? key : kmin;
+            kmax = key > kmax ? key : kmax;
+        }
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        const uint32_t a = __shfl_xor(kmin, o, 64), c = __shfl_xor(kmax, o, 64);
+        kmin = a < kmin ? a : kmin;
+        kmax = c > kmax ? c : kmax;
+    }
+    if ((tid & 63) == 0) {
+        wave_range[tid >> 6][0] = kmin;
+        wave_range[tid >> 6][1] = kmax;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        for (int i = 1; i < 4; ++i) {
+            kmin = wave_range[i][0] < kmin ? wave_range[i][0] : kmin;
+            kmax = wave_range[i][1] > kmax ? wave_range[i][1] : kmax;
+        }
+        tile_range[((int64_t)bh * n_tiles + tile) * 2] = kmin;
+        tile_range[((int64_t)bh * n_tiles + tile) * 2 + 1] = kmax;
     }
 }
 
@@ -488,7 +517,9 @@ ScorePlan plan_score(int B, int H, int G, int N, int w) {
     p.stats_off = 0;
     p.lse_off = align_up((size_t)BH * nc * 4 * p.R * sizeof(float2), 256);   // up to 4 partials per chunk
     p.vote_off = p.lse_off + align_up((size_t)BH * p.R * sizeof(float), 256);
-    p.bytes = p.vote_off + align_up((size_t)BH * G * P * sizeof(float), 256);
+    p.range_off = p.vote_off + align_up((size_t)BH * G * P * sizeof(float), 256);
+    p.n_range_tiles = (int)((P + kPoolTile - 1) / kPoolTile);
+    p.bytes = p.range_off + align_up((size_t)BH * p.n_range_tiles * 2 * sizeof(uint32_t), 256);
     return p;
 }
 
@@ -501,6 +532,7 @@ static hipError_t run_score(const T* Q, const T* K, int B, int H, int G, int N, 
     float2* stats = reinterpret_cast<float2*>(ws + p.stats_off);
     float* lse = reinterpret_cast<float*>(ws + p.lse_off);
     float* vote = reinterpret_cast<float*>(ws + p.vote_off);
+    uint32_t* tile_range = reinterpret_cast<uint32_t*>(ws + p.range_off);
     const dim3 grid1((unsigned)(BH * p.n_chunks));
     int n_parts = p.n_chunks;            // partial statistics per query row
     const int rows = BH * p.R;
@@ -579,14 +611,14 @@ static hipError_t run_score(const T* Q, const T* K, int B, int H, int G, int N, 
     {
         const dim3 pg((unsigned)(BH * n_pool_tiles)), pb(256);
         switch (pool / 2) {
-            case 0: score_pool_kernel<0><<<pg, pb, 0, s>>>(vote, G, P, n_pool_tiles, score_out); break;
-            case 1: score_pool_kernel<1><<<pg, pb, 0, s>>>(vote, G, P, n_pool_tiles, score_out); break;
-            case 2: score_pool_kernel<2><<<pg, pb, 0, s>>>(vote, G, P, n_pool_tiles, score_out); break;
-            case 3: score_pool_kernel<3><<<pg, pb, 0, s>>>(vote, G, P, n_pool_tiles, score_out); break;
-            case 4: score_pool_kernel<4><<<pg, pb, 0, s>>>(vote, G, P, n_pool_tiles, score_out); break;
-            case 5: score_pool_kernel<5><<<pg, pb, 0, s>>>(vote, G, P, n_pool_tiles, score_out); break;
-            case 6: score_pool_kernel<6><<<pg, pb, 0, s>>>(vote, G, P, n_pool_tiles, score_out); break;
-            default: score_pool_kernel<7><<<pg, pb, 0, s>>>(vote, G, P, n_pool_tiles, score_out); break;
+            case 0: score_pool_kernel<0><<<pg, pb, 0, s>>>(vote, G, P, n_pool_tiles, score_out, tile_range); break;
+            case 1: score_pool_kernel<1><<<pg, pb, 0, s>>>(vote, G, P, n_pool_tiles, score_out, tile_range); break;
+            case 2: score_pool_kernel<2><<<pg, pb, 0, s>>>(vote, G, P, n_pool_tiles, score_out, tile_range); break;
+            case 3: score_pool_kernel<3><<<pg, pb, 0, s>>>(vote, G, P, n_pool_tiles, score_out, tile_range); break;
+            case 4: score_pool_kernel<4><<<pg, pb, 0, s>>>(vote, G, P, n_pool_tiles, score_out, tile_range); break;
+            case 5: score_pool_kernel<5><<<pg, pb, 0, s>>>(vote, G, P, n_pool_tiles, score_out, tile_range); break;
+            case 6: score_pool_kernel<6><<<pg, pb, 0, s>>>(vote, G, P, n_pool_tiles, score_out, tile_range); break;
+            default: score_pool_kernel<7><<<pg, pb, 0, s>>>(vote, G, P, n_pool_tiles, score_out, tile_range); break;
         }
     }
     env.end();

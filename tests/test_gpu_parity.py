@@ -245,6 +245,54 @@ def test_select_gather_exact(ctx, dtype, N, w, cap):
     assert np.array_equal(raw_bits(Vo), rVo)
 
 
+@pytest.mark.parametrize("case", ["many_equal_candidates", "long_lists", "narrow_spread", "tiny_budget"])
+def test_select_paths(ctx, case):
+    """The routes through the selection kernel: candidate lists in LDS, candidate keys that overflow them
+    (thousands of equal scores around the threshold), kept lists that overflow them (budgets of tens of
+    thousands), scores that differ only in their last mantissa bits."""
+    rng = np.random.default_rng(len(case))
+    B, H, w = 1, 3, 16
+    N = 120_016
+    P = N - w
+    score = rng.random((B, H, P)).astype(np.float32)
+    budget = np.array([[3000, 5000, 900]], dtype=np.int32)
+    if case == "many_equal_candidates":
+        score[0, 0] = np.round(score[0, 0] * 6) / 6            # ~20 000 scores per level
+        score[0, 1] = np.where(score[0, 1] < 0.9, 0.5, score[0, 1])
+    elif case == "long_lists":
+        budget = np.array([[40_000, 100_000, 17_000]], dtype=np.int32)
+    elif case == "narrow_spread":
+        score = (1.0 + score * 1e-5).astype(np.float32)         # a few hundred distinct neighbouring floats
+        score[0, 2] = np.float32(0.75) + (rng.integers(0, 3, P) * np.float32(2 ** -24)).astype(np.float32)
+    else:
+        budget = np.array([[w + 1, w + 2, w]], dtype=np.int32)
+    cap = int(budget.max())
+    _, _, idx, ln = ctx.select_gather(torch.from_numpy(score).to(DEV), torch.from_numpy(budget).to(DEV),
+                                      None, None, w, cap, N=N)
+    torch.cuda.synchronize()
+    for h in range(H):
+        ref = O.select_indices(score[0, h].astype(np.float64), budget[0, h], N, w)
+        assert int(ln[0, h]) == len(ref)
+        assert np.array_equal(idx[0, h, : len(ref)].cpu().numpy(), ref), (case, h)
+
+
+def test_select_after_scores_changed_in_place(ctx):
+    """uncomp_window_score leaves the range of its scores for the selection that follows; if the caller changes
+    the scores in between, the selection must notice that the range no longer holds and still be exact."""
+    cfg = synth.tiny_config(dtype="bf16", B=1, H=2, G=2, N=6000, w=32, rank_lo=2, rank_hi=24)
+    K, V, Q = synth.gen_all(cfg, seed0=99)
+    score = ctx.window_score(Q[0].to(DEV), K[0].to(DEV), G=2, pool=7)
+    g = torch.Generator(device=DEV).manual_seed(5)
+    score.copy_(torch.randn(score.shape, generator=g, device=DEV) * 7.0)        # same buffer, other values, wider range
+    budget = torch.tensor([[500, 77]], dtype=torch.int32, device=DEV)
+    _, _, idx, ln = ctx.select_gather(score, budget, None, None, 32, 512, N=6000)
+    torch.cuda.synchronize()
+    sc = score.cpu().numpy().astype(np.float64)
+    for h in range(2):
+        ref = O.select_indices(sc[0, h], int(budget[0, h]), 6000, 32)
+        assert np.array_equal(idx[0, h, : len(ref)].cpu().numpy(), ref)
+
+
 def test_select_indices_only(ctx):
     rng = np.random.default_rng(8)
     N, w, cap = 3000, 32, 256
