@@ -86,7 +86,8 @@ uncomp_status uncomp_destroy(uncomp_ctx* ctx);
 size_t uncomp_workspace_bytes(int n_mat, int N, int D, int B, int H, int G, int w);
 
 /* Host string describing the last failing call on this context (never NULL, owned by
- * the context, valid until the next call on it). */
+ * the context, valid until the next call on it).  With ctx == NULL: the calling thread's last
+ * failing context-free call (uncomp_head_entropy_noalloc), "null context" if there was none. */
 const char* uncomp_last_error(const uncomp_ctx* ctx);
 
 /* Per-kernel timing for benchmarks (not a paper operation).  uncomp_profile(ctx, 1) makes
@@ -166,6 +167,27 @@ uncomp_status uncomp_matrix_entropy(uncomp_ctx* ctx, const void* X, uncomp_dtype
                                     int n_mat, int N, int D, int64_t mat_stride, int64_t ldx,
                                     int k_trunc, unsigned flags, int n_iter,
                                     float* entropy_out, float* eig_out, void* stream);
+
+/*
+ * uncomp_head_entropy for callers that cannot allocate device memory: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  It takes no context and calls no hipMalloc,
+ * hipFree or other allocating routine: the partial second-moment sums that uncomp_head_entropy keeps
+ * in the context's workspace live in a fixed array of 32.3 MiB inside the library's code object (each
+ * GPU the library runs on holds its copy from the loading of the library to the end of the process).
+ * Arguments, results and the kernels are those of uncomp_head_entropy (eigen stage: the fp64
+ * tridiagonalisation; no profiling, no overlap mode); the call works on the CURRENT device.
+ * Limits: the partial sums of one call must fit the array: at most 512 matrices per call (beyond:
+ * UNCOMP_ERR_WORKSPACE, nothing launched); between 1 and 512 matrices the token axis is split into
+ * fewer, longer chunks than uncomp_head_entropy would use, which changes the order of the fp32
+ * partial sums but not what is computed.  All calls on one GPU share the array: calls that overlap
+ * in time on one GPU (different streams, different threads) race; calls on one stream are ordered.
+ * The first call on a device looks up the array's address and raises one kernel's LDS limit
+ * (no allocation either, but not to be done under stream capture: make one call beforehand).
+ * uncomp_last_error(NULL) gives the reason of the calling thread's last failing call.
+ */
+uncomp_status uncomp_head_entropy_noalloc(const void* X, uncomp_dtype dtype, int n_mat, int N, int D,
+                                          int64_t mat_stride, int64_t ldx, int k_trunc, unsigned flags,
+                                          float* entropy_out, float* eig_out, void* stream);
 
 /*
  * Budgets from entropies (Sec. 3.3.3 "Design", Eq. 11; Sec. 3.3.2 Eq. 8-10).

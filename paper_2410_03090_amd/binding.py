@@ -24,7 +24,7 @@ DEFAULT_FLAGS = CENTER | TRUNC_RENORM
 EXPORTS = (
     "uncomp_create", "uncomp_destroy", "uncomp_workspace_bytes", "uncomp_last_error",
     "uncomp_profile", "uncomp_profile_read", "uncomp_measure_peaks", "uncomp_set_kernel_path", "uncomp_set_overlap", "uncomp_join",
-    "uncomp_head_entropy", "uncomp_assign_budgets", "uncomp_window_score", "uncomp_select_gather",
+    "uncomp_head_entropy", "uncomp_head_entropy_noalloc", "uncomp_assign_budgets", "uncomp_window_score", "uncomp_select_gather",
     "uncomp_decode_init", "uncomp_decode_step", "uncomp_decode_workspace_bytes",
     "uncomp_hidden_evict", "uncomp_hidden_workspace_bytes",
     "uncomp_matrix_entropy", "uncomp_matrix_workspace_bytes",
@@ -75,6 +75,8 @@ def load_library() -> ctypes.CDLL:
     lib.uncomp_measure_peaks.restype = i32
     lib.uncomp_head_entropy.argtypes = [vp, vp, i32, i32, i32, i32, i64, i64, i32, u32, vp, vp, vp]
     lib.uncomp_head_entropy.restype = i32
+    lib.uncomp_head_entropy_noalloc.argtypes = [vp, i32, i32, i32, i32, i64, i64, i32, u32, vp, vp, vp]
+    lib.uncomp_head_entropy_noalloc.restype = i32
     lib.uncomp_assign_budgets.argtypes = [vp, vp, i32, i32, i32, i32, i32, i32, i32, i32, f32, i32, u32,
                                           vp, vp, vp, vp, vp]
     lib.uncomp_assign_budgets.restype = i32
@@ -126,6 +128,21 @@ def _stream() -> int:
 
 def _ptr(t):
     return None if t is None else t.data_ptr()
+
+
+def head_entropy_noalloc(X: torch.Tensor, k_trunc: int = 32, flags: int = DEFAULT_FLAGS, entropy_out=None, eig_out=None):
+    """uncomp_head_entropy_noalloc: X [n_mat, N, D] (last dim contiguous), outputs given by the caller (the call
+    itself allocates nothing; without outputs this wrapper makes them first).  Returns (entropy, eig or None)."""
+    lib = load_library()
+    n_mat, N, D = X.shape
+    assert X.stride(2) == 1
+    if entropy_out is None:
+        entropy_out = torch.empty(n_mat, dtype=torch.float32, device=X.device)
+    st = lib.uncomp_head_entropy_noalloc(X.data_ptr(), _dtype_code(X), n_mat, N, D, X.stride(0), X.stride(1), int(k_trunc),
+                                         int(flags), entropy_out.data_ptr(), _ptr(eig_out), _stream())
+    if st != OK:
+        raise UncompError(st, lib.uncomp_last_error(None).decode())
+    return entropy_out, eig_out
 
 
 class Context:

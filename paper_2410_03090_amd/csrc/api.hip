@@ -186,7 +186,7 @@ uncomp_status uncomp_measure_peaks(uncomp_ctx* ctx, const void* buf, size_t byte
     return UNCOMP_OK;
 }
 
-const char* uncomp_last_error(const uncomp_ctx* ctx) { return ctx != nullptr ? ctx->err : "null context"; }
+const char* uncomp_last_error(const uncomp_ctx* ctx) { return ctx != nullptr ? ctx->err : noalloc_last_error(); }
 
 uncomp_status uncomp_head_entropy(uncomp_ctx* ctx, const void* X, uncomp_dtype dtype, int n_mat,
                                   int N, int D, int64_t mat_stride, int64_t ldx, int k_trunc,

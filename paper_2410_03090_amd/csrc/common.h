@@ -62,7 +62,7 @@ struct EntropyPlan {
     size_t sum_off;      // float [n_mat][n_chunks][D]
     size_t bytes;
 };
-EntropyPlan plan_entropy(int n_mat, int N);
+EntropyPlan plan_entropy(int n_mat, int N, size_t max_bytes = 0);
 
 struct ScorePlan {
     int R;               // query rows per KV head = G*w
@@ -203,6 +203,7 @@ inline hipError_t allow_dynamic_lds(const void* kernel, size_t bytes) {
     return hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
 }
 hipError_t measure_peaks(const void* buf, size_t n16, int num_cu, uint32_t* sink, hipStream_t s, double out[3]);
+const char* noalloc_last_error();
 hipError_t init_gram_kernels();
 hipError_t init_select_kernels();
 hipError_t init_score_kernels();

@@ -107,24 +107,29 @@ __global__ __launch_bounds__(512, 1) void gram_mfma_kernel(const bf16_bits* __re
                       sum_part + ((int64_t)m_idx * n_chunks + c) * kD);
 }
 
-EntropyPlan plan_entropy(int n_mat, int N) {
+EntropyPlan plan_entropy(int n_mat, int N, size_t max_bytes) {
     EntropyPlan p;
     // Two workgroups of eight waves per CU cover the chip; fewer, longer chunks mean fewer 64 KiB
     // partials to write and to add up again (128K workload: 8 chunks per matrix 1.54 ms, 2 chunks
-    // 1.46 ms), and chunks stay above 4096 tokens.
+    // 1.46 ms), and chunks stay above 4096 tokens.  A byte limit (max_bytes > 0) lowers the chunk
+    // count until the partials fit; p.bytes still exceeds it if even one chunk per matrix does not.
     int max_chunks = N / 4096 > 0 ? N / 4096 : 1;
     int want = (512 + n_mat - 1) / (n_mat > 0 ? n_mat : 1);
     int nc = want < 1 ? 1 : want;
     if (nc > max_chunks) nc = max_chunks;
-    int chunk = (N + nc - 1) / nc;
-    chunk = (chunk + kGramTile - 1) / kGramTile * kGramTile;
-    nc = (N + chunk - 1) / chunk;
-    if (nc < 1) nc = 1;
-    p.n_chunks = nc;
-    p.chunk = chunk;
-    p.gram_off = 0;
-    p.sum_off = align_up((size_t)n_mat * nc * kD * kD * sizeof(float), 256);
-    p.bytes = p.sum_off + align_up((size_t)n_mat * nc * kD * sizeof(float), 256);
+    for (;;) {
+        int chunk = (N + nc - 1) / nc;
+        chunk = (chunk + kGramTile - 1) / kGramTile * kGramTile;
+        int n = (N + chunk - 1) / chunk;
+        if (n < 1) n = 1;
+        p.n_chunks = n;
+        p.chunk = chunk;
+        p.gram_off = 0;
+        p.sum_off = align_up((size_t)n_mat * n * kD * kD * sizeof(float), 256);
+        p.bytes = p.sum_off + align_up((size_t)n_mat * n * kD * sizeof(float), 256);
+        if (max_bytes == 0 || p.bytes <= max_bytes || nc <= 1) break;
+        nc = n > 1 ? n - 1 : 1;
+    }
     return p;
 }
 

@@ -37,6 +37,9 @@ def test_null_context_is_rejected_without_a_device():
     assert lib.uncomp_head_entropy(None, None, 0, 1, 1, 128, 0, 128, 32, 3, None, None, None) == binding.ERR_INVALID_ARG
     assert lib.uncomp_destroy(None) == binding.ERR_INVALID_ARG
     assert lib.uncomp_last_error(None) == b"null context"
+    # the context-free entry point validates on the host before it touches a device, and leaves its reason
+    assert lib.uncomp_head_entropy_noalloc(None, 0, 1, 1, 128, 0, 128, 32, 3, None, None, None) == binding.ERR_INVALID_ARG
+    assert b"null pointer" in lib.uncomp_last_error(None)
 
 
 def test_product_package_does_not_import_the_oracle():
