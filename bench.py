@@ -94,6 +94,9 @@ def main():
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="also run one plain device copy of this many MiB (reference for HBM byte counters)")
     ap.add_argument("--cpu-heads", type=int, default=0, help="heads in the oracle sample (0 = auto)")
+    ap.add_argument("--zero-keys", action="store_true",
+                    help="all keys zero: same instructions, no switching activity in the matrix operands (shows what the "
+                         "chip's clock management costs the kernels on live data); results are degenerate, timing only")
     ap.add_argument("--no-with-lse", action="store_true", help="skip the leg that hands the row normalisers to uncomp_window_score")
     ap.add_argument("--no-prepare", action="store_true", help="skip the offline-preparation leg")
     ap.add_argument("--no-matrix-entropy", action="store_true", help="skip the wide-matrix (hidden-state) entropy leg")
@@ -115,6 +118,8 @@ def main():
     torch.cuda.set_device(0)
     t_gen = time.time()
     K, V, Q = synth.gen_all(cfg, args.seed, device=dev)
+    if args.zero_keys:
+        K.zero_()
     torch.cuda.synchronize()
     t_gen = time.time() - t_gen
     L, B, H, N, D, G, w = cfg.L, cfg.B, cfg.H, cfg.N, cfg.D, cfg.G, cfg.w
@@ -226,7 +231,7 @@ def main():
         "metric": "kv_tokens_compressed_per_sec", "value": round(value, 1), "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": cfg.dtype,
-        "data": "synthetic",
+        "data": "synthetic" if not args.zero_keys else "all-zero keys (timing experiment, not a result)",
         "config": {"workload": cfg.name, "layers": L, "batch": B, "kv_heads": H, "q_per_kv": G, "seq_len": N,
                    "head_dim": D, "window": w, "pool": cfg.pool, "k_trunc": cfg.k_trunc,
                    "avg_budget": cfg.avg_budget, "mean_kept": round(kept, 1), "rho": round(kept / N, 5),
