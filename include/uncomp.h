@@ -35,7 +35,9 @@
  *   - Arguments are validated on the host before anything is launched; a failing call
  *     returns a negative status, launches nothing and leaves outputs untouched.
  *     uncomp_last_error gives a one-line reason.
- *   - Supported: D == 128; dtype bf16 or fp32; 1 <= k_trunc; pool odd, 1 <= pool <= 15;
+ *   - Supported: D == 128, and D == 64 in the four hot calls (64-wide heads run on the plain
+ *     arithmetic units, not the matrix cores: correct, several times slower; every other call
+ *     takes D == 128 only); dtype bf16 or fp32; 1 <= k_trunc; pool odd, 1 <= pool <= 15;
  *     0 < w < N; M >= 1 dividing H.  Anything else is UNCOMP_ERR_UNSUPPORTED.
  */
 #ifndef UNCOMP_H

@@ -195,7 +195,7 @@ uncomp_status uncomp_head_entropy(uncomp_ctx* ctx, const void* X, uncomp_dtype d
     if (X == nullptr || entropy_out == nullptr) return fail(ctx, UNCOMP_ERR_INVALID_ARG, "head_entropy: null pointer");
     if (n_mat <= 0 || N <= 0) return fail(ctx, UNCOMP_ERR_INVALID_ARG, "head_entropy: n_mat and N must be positive");
     if (dtype != UNCOMP_BF16 && dtype != UNCOMP_F32) return fail(ctx, UNCOMP_ERR_UNSUPPORTED, "head_entropy: dtype");
-    if (D != kD) return fail(ctx, UNCOMP_ERR_UNSUPPORTED, "head_entropy: D must be 128");
+    if (D != kD && D != 64) return fail(ctx, UNCOMP_ERR_UNSUPPORTED, "head_entropy: D must be 64 or 128");
     if (k_trunc < 1) return fail(ctx, UNCOMP_ERR_UNSUPPORTED, "head_entropy: k_trunc must be >= 1");
     if (flags & ~(UNCOMP_CENTER | UNCOMP_TRUNC_RENORM | UNCOMP_LAYER_DELTA_INCREASE))
         return fail(ctx, UNCOMP_ERR_UNSUPPORTED, "head_entropy: unknown flag bits");
@@ -213,7 +213,7 @@ uncomp_status uncomp_head_entropy(uncomp_ctx* ctx, const void* X, uncomp_dtype d
     char* ws = ctx->ws + kBudgetScratch;
     ctx->score_ws_off = kBudgetScratch + p.bytes;
     Env env{static_cast<hipStream_t>(stream), &ctx->prof, ctx->force_alu};
-    hipError_t e = launch_gram(X, dtype, n_mat, N, mat_stride, ldx, p, ws, env);
+    hipError_t e = launch_gram(X, dtype, n_mat, N, mat_stride, ldx, p, ws, env, D);
     if (e != hipSuccess) return hip_fail(ctx, e, "head_entropy: gram launch");
     if (ctx->overlap) {
         // the eigen stage moves to the side stream, ordered after the Gram kernel
@@ -224,8 +224,8 @@ uncomp_status uncomp_head_entropy(uncomp_ctx* ctx, const void* X, uncomp_dtype d
         ctx->side_pending = true;
     }
     // the plain-ALU switch also selects the fp32 Jacobi eigen stage (an independent cross-check)
-    e = ctx->force_alu ? launch_jacobi_entropy(n_mat, N, k_trunc, flags, p, ws, entropy_out, eig_out, env)
-                       : launch_tridiag_entropy(n_mat, N, k_trunc, flags, p, ws, entropy_out, eig_out, env);
+    e = ctx->force_alu ? launch_jacobi_entropy(n_mat, N, k_trunc, flags, p, ws, entropy_out, eig_out, env, D)
+                       : launch_tridiag_entropy(n_mat, N, k_trunc, flags, p, ws, entropy_out, eig_out, env, nullptr, D);
     if (e != hipSuccess) return hip_fail(ctx, e, "head_entropy: eigen launch");
     return UNCOMP_OK;
 }
@@ -267,7 +267,7 @@ uncomp_status uncomp_window_score(uncomp_ctx* ctx, const void* Qwin, const void*
         return fail(ctx, UNCOMP_ERR_INVALID_ARG, "window_score: null pointer");
     if (B <= 0 || H <= 0 || G <= 0 || N <= 0) return fail(ctx, UNCOMP_ERR_INVALID_ARG, "window_score: sizes must be positive");
     if (dtype != UNCOMP_BF16 && dtype != UNCOMP_F32) return fail(ctx, UNCOMP_ERR_UNSUPPORTED, "window_score: dtype");
-    if (D != kD) return fail(ctx, UNCOMP_ERR_UNSUPPORTED, "window_score: D must be 128");
+    if (D != kD && D != 64) return fail(ctx, UNCOMP_ERR_UNSUPPORTED, "window_score: D must be 64 or 128");
     if (w <= 0 || w >= N) return fail(ctx, UNCOMP_ERR_UNSUPPORTED, "window_score: need 0 < w < N");
     if (pool < 1 || pool > 15 || (pool & 1) == 0) return fail(ctx, UNCOMP_ERR_UNSUPPORTED, "window_score: pool must be odd in [1,15]");
     if ((int64_t)G * w > 512) return fail(ctx, UNCOMP_ERR_UNSUPPORTED, "window_score: G*w must be <= 512");
@@ -283,7 +283,7 @@ uncomp_status uncomp_window_score(uncomp_ctx* ctx, const void* Qwin, const void*
                     off + p.bytes, ctx->ws_bytes);
     ctx->key_range.ptr = nullptr;
     hipError_t e = launch_window_score(Qwin, K, dtype, B, H, G, N, w, pool, k_strides, p, ctx->ws + off, score_out,
-                                       Env{static_cast<hipStream_t>(stream), &ctx->prof, ctx->force_alu}, lse_opt);
+                                       Env{static_cast<hipStream_t>(stream), &ctx->prof, ctx->force_alu}, lse_opt, D);
     if (e != hipSuccess) return hip_fail(ctx, e, "window_score: launch");
     ctx->key_range.ptr = reinterpret_cast<const uint32_t*>(ctx->ws + off + p.range_off);
     ctx->key_range.score = score_out;
@@ -305,7 +305,7 @@ uncomp_status uncomp_select_gather(uncomp_ctx* ctx, const float* score, const in
     if (any_kv && !all_kv) return fail(ctx, UNCOMP_ERR_INVALID_ARG, "select_gather: K, V, K_out, V_out must be given together");
     if (B <= 0 || H <= 0 || N <= 0 || cap <= 0) return fail(ctx, UNCOMP_ERR_INVALID_ARG, "select_gather: sizes must be positive");
     if (dtype != UNCOMP_BF16 && dtype != UNCOMP_F32) return fail(ctx, UNCOMP_ERR_UNSUPPORTED, "select_gather: dtype");
-    if (D != kD) return fail(ctx, UNCOMP_ERR_UNSUPPORTED, "select_gather: D must be 128");
+    if (D != kD && D != 64) return fail(ctx, UNCOMP_ERR_UNSUPPORTED, "select_gather: D must be 64 or 128");
     if (w <= 0 || w >= N) return fail(ctx, UNCOMP_ERR_UNSUPPORTED, "select_gather: need 0 < w < N");
     if (cap < w) return fail(ctx, UNCOMP_ERR_INVALID_ARG, "select_gather: cap must be >= w");
     if (!aligned16(score)) return fail(ctx, UNCOMP_ERR_INVALID_ARG, "select_gather: score must be 16-byte aligned");
@@ -326,7 +326,7 @@ uncomp_status uncomp_select_gather(uncomp_ctx* ctx, const float* score, const in
     hipError_t e = launch_select_gather(score, budget, all_kv ? K : nullptr, V, dtype, B, H, N, w,
                                         all_kv ? kv_strides : zero_strides, cap, K_out, V_out, idx_out, len_out,
                                         Env{static_cast<hipStream_t>(stream), &ctx->prof, ctx->force_alu},
-                                        ranged ? ctx->key_range.ptr : nullptr, ranged ? ctx->key_range.n_tiles : 0);
+                                        ranged ? ctx->key_range.ptr : nullptr, ranged ? ctx->key_range.n_tiles : 0, D);
     if (e != hipSuccess) return hip_fail(ctx, e, "select_gather: launch");
     return UNCOMP_OK;
 }

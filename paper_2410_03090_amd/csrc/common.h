@@ -98,17 +98,20 @@ struct Env {
 };
 
 // ---- launchers (each returns the hipError_t of its launches) ---------------------------
+// D: features per token, 128, or 64 (then the plain-ALU kernel runs and features 64..127 of the 128-wide
+// partial sums are zero, which leaves the non-zero eigenvalues and the entropy as they are).
 hipError_t launch_gram(const void* X, uncomp_dtype dt, int n_mat, int N, int64_t mat_stride,
-                       int64_t ldx, const EntropyPlan& p, char* ws, const Env& env);
+                       int64_t ldx, const EntropyPlan& p, char* ws, const Env& env, int D = kD);
 hipError_t launch_jacobi_entropy(int n_mat, int N, int k_trunc, unsigned flags,
                                  const EntropyPlan& p, char* ws, float* entropy_out,
-                                 float* eig_out, const Env& env);
+                                 float* eig_out, const Env& env, int eig_ld = kD);
 // trace_total: optional DEVICE pointer to two doubles, the raw (unnormalised) centred and
 // uncentred traces of the larger matrix that the one handed in is a projection of: Eq. 5 without
 // renormalisation divides by the one that applies, and a larger matrix without spread gives 0.
 hipError_t launch_tridiag_entropy(int n_mat, int N, int k_trunc, unsigned flags,
                                   const EntropyPlan& p, char* ws, float* entropy_out,
-                                  float* eig_out, const Env& env, const double* trace_total = nullptr);
+                                  float* eig_out, const Env& env, const double* trace_total = nullptr,
+                                  int eig_ld = kD);
 hipError_t launch_budgets(const float* entropy, int L, int B, int H, int M, int n_max, int step,
                           int N, int w, float eps, int delta_n, unsigned flags,
                           int32_t* head_budget, int32_t* head_group, int32_t* layer_group,
@@ -117,12 +120,13 @@ hipError_t launch_budgets(const float* entropy, int L, int B, int H, int M, int 
 // softmax-statistics pass is skipped.
 hipError_t launch_window_score(const void* Q, const void* K, uncomp_dtype dt, int B, int H, int G,
                                int N, int w, int pool, const int64_t ks[3], const ScorePlan& p,
-                               char* ws, float* score_out, const Env& env, const float* lse_nat = nullptr);
+                               char* ws, float* score_out, const Env& env, const float* lse_nat = nullptr,
+                               int D = kD);
 hipError_t launch_select_gather(const float* score, const int32_t* budget, const void* K,
                                 const void* V, uncomp_dtype dt, int B, int H, int N, int w,
                                 const int64_t ks[3], int cap, void* K_out, void* V_out,
                                 int32_t* idx_out, int32_t* len_out, const Env& env,
-                                const uint32_t* tile_range = nullptr, int n_range_tiles = 0);
+                                const uint32_t* tile_range = nullptr, int n_range_tiles = 0, int D = kD);
 hipError_t launch_select_rows(const float* score, const int32_t* budget, int budget_stride, int n_groups,
                               int N, int w, int cap, int32_t* idx_out, int32_t* len_out, const Env& env);
 hipError_t launch_gather_rows(const void* src, const int32_t* idx, const int32_t* len, int n_groups, int cap,

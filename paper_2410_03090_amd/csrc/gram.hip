@@ -14,7 +14,7 @@ namespace uncomp {
 // block of the 128x128 output; tokens are staged through LDS 32 at a time.
 // ---------------------------------------------------------------------------------------
 template <typename T>
-__global__ __launch_bounds__(256) void gram_alu_kernel(const T* __restrict__ X, int N,
+__global__ __launch_bounds__(256) void gram_alu_kernel(const T* __restrict__ X, int N, int D,
                                                        int64_t mat_stride, int64_t ldx,
                                                        int n_chunks, int chunk,
                                                        float* __restrict__ gram_part,
@@ -41,7 +41,7 @@ __global__ __launch_bounds__(256) void gram_alu_kernel(const T* __restrict__ X, 
             int g = tid + rep * 256;
             int tt = g >> 4, f8 = (g & 15) * 8;
             float v[8];
-            if (t0 + tt < t_end) {
+            if (t0 + tt < t_end && f8 < D) {                 // features beyond D (a 64-wide head) count as zeros
                 load8(Xm + (int64_t)(t0 + tt) * ldx + f8, v);
             } else {
 #pragma unroll
@@ -134,9 +134,9 @@ EntropyPlan plan_entropy(int n_mat, int N, size_t max_bytes) {
 }
 
 hipError_t launch_gram(const void* X, uncomp_dtype dt, int n_mat, int N, int64_t mat_stride,
-                       int64_t ldx, const EntropyPlan& p, char* ws, const Env& env) {
+                       int64_t ldx, const EntropyPlan& p, char* ws, const Env& env, int D) {
     hipStream_t s = env.s;
-    const bool force_alu = env.force_alu;
+    const bool force_alu = env.force_alu || D != kD;       // the MFMA kernel is written for 128 features
     float* gram = reinterpret_cast<float*>(ws + p.gram_off);
     float* sums = reinterpret_cast<float*>(ws + p.sum_off);
     dim3 grid((unsigned)(p.n_chunks * n_mat)), block(256);
@@ -151,10 +151,10 @@ hipError_t launch_gram(const void* X, uncomp_dtype dt, int n_mat, int N, int64_t
     env.begin("gram_alu");
     if (dt == UNCOMP_BF16) {
         gram_alu_kernel<bf16_bits><<<grid, block, 0, s>>>(
-            static_cast<const bf16_bits*>(X), N, mat_stride, ldx, p.n_chunks, p.chunk, gram, sums);
+            static_cast<const bf16_bits*>(X), N, D, mat_stride, ldx, p.n_chunks, p.chunk, gram, sums);
     } else {
         gram_alu_kernel<float><<<grid, block, 0, s>>>(
-            static_cast<const float*>(X), N, mat_stride, ldx, p.n_chunks, p.chunk, gram, sums);
+            static_cast<const float*>(X), N, D, mat_stride, ldx, p.n_chunks, p.chunk, gram, sums);
     }
     env.end();
     return hipGetLastError();

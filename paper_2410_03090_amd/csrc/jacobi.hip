@@ -74,7 +74,7 @@ __device__ __forceinline__ float row_rotate(float v) {
 
 __global__ __launch_bounds__(kThreads) void jacobi_entropy_kernel(
     const float* __restrict__ gram_part, const float* __restrict__ sum_part, int n_chunks, int N,
-    int k_trunc, unsigned flags, float* __restrict__ entropy_out, float* __restrict__ eig_out) {
+    int k_trunc, unsigned flags, float* __restrict__ entropy_out, float* __restrict__ eig_out, int eig_ld) {
     extern __shared__ __align__(16) unsigned char smem_raw[];
     Smem& sm = *reinterpret_cast<Smem*>(smem_raw);
     const int m = blockIdx.x;
@@ -106,7 +106,7 @@ __global__ __launch_bounds__(kThreads) void jacobi_entropy_kernel(
     const bool degenerate = !(trace > 0.0) || (center && (N < 2 || trace < trace_u * 0x1p-20));
     if (degenerate) {
         if (tid == 0) entropy_out[m] = 0.f;
-        if (eig_out != nullptr && tid < kD) eig_out[(int64_t)m * kD + tid] = 0.f;
+        if (eig_out != nullptr && tid < eig_ld) eig_out[(int64_t)m * eig_ld + tid] = 0.f;
         return;
     }
     const double inv_tr = 1.0 / trace;
@@ -346,20 +346,20 @@ __global__ __launch_bounds__(kThreads) void jacobi_entropy_kernel(
     }
     const double H = block_sum(term, sm.red, tid);
     if (tid == 0) entropy_out[m] = (float)H;
-    if (eig_out != nullptr && tid < kD)
-        eig_out[(int64_t)m * kD + tid] = total > 0.0 ? (float)(mine / total) : 0.f;
+    if (eig_out != nullptr && tid < eig_ld)        // eig_ld values per matrix: all 128, or the leading 64 of a 64-wide input
+        eig_out[(int64_t)m * eig_ld + tid] = total > 0.0 ? (float)(mine / total) : 0.f;
 }
 
 hipError_t launch_jacobi_entropy(int n_mat, int N, int k_trunc, unsigned flags,
                                  const EntropyPlan& p, char* ws, float* entropy_out,
-                                 float* eig_out, const Env& env) {
+                                 float* eig_out, const Env& env, int eig_ld) {
     hipStream_t s = env.s;
     static_assert(sizeof(Smem) <= 160 * 1024, "LDS budget");
     const float* gram = reinterpret_cast<const float*>(ws + p.gram_off);
     const float* sums = reinterpret_cast<const float*>(ws + p.sum_off);
     env.begin("jacobi_entropy");
     jacobi_entropy_kernel<<<dim3(n_mat), dim3(kThreads), sizeof(Smem), s>>>(
-        gram, sums, p.n_chunks, N, k_trunc, flags, entropy_out, eig_out);
+        gram, sums, p.n_chunks, N, k_trunc, flags, entropy_out, eig_out, eig_ld);
     env.end();
     return hipGetLastError();
 }

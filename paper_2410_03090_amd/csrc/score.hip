@@ -28,7 +28,7 @@ constexpr int kVoteRows = 32;     // query rows staged per step in pass 2 (plain
 // ---------------------------------------------------------------------------------------
 template <typename T>
 __global__ __launch_bounds__(512) void score_stats_alu_kernel(
-    const T* __restrict__ Q, const T* __restrict__ K, int H, int G, int N, int w, int64_t ks_b,
+    const T* __restrict__ Q, const T* __restrict__ K, int H, int G, int N, int D, int w, int64_t ks_b,
     int64_t ks_h, int64_t ks_t, int n_chunks, int chunk, float2* __restrict__ stats) {
     __shared__ float kt[kStatTile][kD];
     const int bh = blockIdx.x / n_chunks, c = blockIdx.x % n_chunks;
@@ -38,16 +38,16 @@ __global__ __launch_bounds__(512) void score_stats_alu_kernel(
     const bool live = row < R;
     const int i = live ? row % w : 0;
     const T* Kh = K + b * ks_b + h * ks_h;
-    const float scale2 = kLog2e * rsqrtf((float)kD);
+    const float scale2 = kLog2e * rsqrtf((float)D);
 
-    float q[kD];
+    float q[kD];                                 // features beyond D (a 64-wide head) are zeros on both sides
+#pragma unroll
+    for (int d = 0; d < kD; ++d) q[d] = 0.f;
     if (live) {
-        const T* qp = Q + ((int64_t)bh * R + row) * kD;
+        const T* qp = Q + ((int64_t)bh * R + row) * D;
 #pragma unroll
-        for (int d = 0; d < kD; d += 8) load8(qp + d, q + d);
-    } else {
-#pragma unroll
-        for (int d = 0; d < kD; ++d) q[d] = 0.f;
+        for (int d = 0; d < kD; d += 8)
+            if (d < D) load8(qp + d, q + d);
     }
 
     float mx = -INFINITY, sum = 0.f;
@@ -57,7 +57,7 @@ __global__ __launch_bounds__(512) void score_stats_alu_kernel(
         for (int g8 = threadIdx.x; g8 < kStatTile * (kD / 8); g8 += blockDim.x) {
             int tt = g8 >> 4, f8 = (g8 & 15) * 8;
             float v[8];
-            if (t0 + tt < t_end) {
+            if (t0 + tt < t_end && f8 < D) {
                 load8(Kh + (int64_t)(t0 + tt) * ks_t + f8, v);
             } else {
 #pragma unroll
@@ -97,19 +97,20 @@ __global__ __launch_bounds__(512) void score_stats_alu_kernel(
 // ---------------------------------------------------------------------------------------
 template <typename T, int GT>
 __global__ __launch_bounds__(256) void score_stats_lastrow_kernel(
-    const T* __restrict__ Q, const T* __restrict__ K, int H, int G, int N, int64_t ks_b, int64_t ks_h,
+    const T* __restrict__ Q, const T* __restrict__ K, int H, int G, int N, int D, int64_t ks_b, int64_t ks_h,
     int64_t ks_t, int n_chunks, int chunk, float2* __restrict__ stats) {
     __shared__ float2 part[16][GT];
     const int bh = blockIdx.x / n_chunks, c = blockIdx.x % n_chunks;
     const int b = bh / H, h = bh % H;
     const int tid = threadIdx.x, sub = tid & 15, rg = tid >> 4;
     const T* Kh = K + b * ks_b + h * ks_h;
-    const float scale2 = kLog2e * rsqrtf((float)kD);
+    const float scale2 = kLog2e * rsqrtf((float)D);
+    const bool has = 8 * sub < D;                 // lanes whose eight features lie beyond D hold zeros
     float qf[GT][8];
 #pragma unroll
     for (int g = 0; g < GT; ++g) {
-        if (g < G) {
-            load8(Q + ((int64_t)bh * G + g) * kD + 8 * sub, qf[g]);
+        if (g < G && has) {
+            load8(Q + ((int64_t)bh * G + g) * D + 8 * sub, qf[g]);
 #pragma unroll
             for (int e = 0; e < 8; ++e) qf[g][e] *= scale2;
         } else {
@@ -130,7 +131,7 @@ __global__ __launch_bounds__(256) void score_stats_lastrow_kernel(
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int t = min(t0 + 16 * u + rg, t_end - 1);          // clamped, never predicated
-            load8(Kh + (int64_t)t * ks_t + 8 * sub, kv[u]);
+            load8(Kh + (int64_t)t * ks_t + (has ? 8 * sub : 0), kv[u]);   // lanes beyond D re-read the first piece; their queries are zero
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
@@ -354,7 +355,7 @@ __global__ __launch_bounds__(256) void score_lse_kernel(const float2* __restrict
 template <typename T>
 __global__ __launch_bounds__(256) void score_vote_alu_kernel(
     const T* __restrict__ Q, const T* __restrict__ K, const float* __restrict__ lse, int H, int G,
-    int N, int w, int64_t ks_b, int64_t ks_h, int64_t ks_t, int n_tiles, float* __restrict__ vote) {
+    int N, int D, int w, int64_t ks_b, int64_t ks_h, int64_t ks_t, int n_tiles, float* __restrict__ vote) {
     __shared__ float qs[kVoteRows][kD];
     __shared__ float ls[kVoteRows];
     const int bh = blockIdx.x / n_tiles, tile = blockIdx.x % n_tiles;
@@ -362,16 +363,16 @@ __global__ __launch_bounds__(256) void score_vote_alu_kernel(
     const int R = G * w, P = N - w;
     const int j = tile * 256 + threadIdx.x;
     const bool live = j < P;
-    const float scale2 = kLog2e * rsqrtf((float)kD);
+    const float scale2 = kLog2e * rsqrtf((float)D);
 
-    float k[kD];
+    float k[kD];                                 // features beyond D (a 64-wide head) are zeros on both sides
+#pragma unroll
+    for (int d = 0; d < kD; ++d) k[d] = 0.f;
     if (live) {
         const T* kp = K + b * ks_b + h * ks_h + (int64_t)j * ks_t;
 #pragma unroll
-        for (int d = 0; d < kD; d += 8) load8(kp + d, k + d);
-    } else {
-#pragma unroll
-        for (int d = 0; d < kD; ++d) k[d] = 0.f;
+        for (int d = 0; d < kD; d += 8)
+            if (d < D) load8(kp + d, k + d);
     }
 
     for (int g = 0; g < G; ++g) {
@@ -380,8 +381,8 @@ __global__ __launch_bounds__(256) void score_vote_alu_kernel(
             const int nr = min(kVoteRows, w - r0);
             for (int g8 = threadIdx.x; g8 < nr * (kD / 8); g8 += 256) {
                 int rr = g8 >> 4, f8 = (g8 & 15) * 8;
-                float tmp[8];
-                load8(Q + ((int64_t)bh * R + g * w + r0 + rr) * kD + f8, tmp);
+                float tmp[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+                if (f8 < D) load8(Q + ((int64_t)bh * R + g * w + r0 + rr) * D + f8, tmp);
 #pragma unroll
                 for (int e = 0; e < 8; ++e) qs[rr][f8 + e] = tmp[e];
             }
@@ -526,7 +527,7 @@ ScorePlan plan_score(int B, int H, int G, int N, int w) {
 template <typename T>
 static hipError_t run_score(const T* Q, const T* K, int B, int H, int G, int N, int w, int pool,
                             const int64_t ks[3], const ScorePlan& p, char* ws, float* score_out,
-                            const Env& env, bool mfma, const float* lse_nat) {
+                            const Env& env, bool mfma, const float* lse_nat, int D) {
     hipStream_t s = env.s;
     const int BH = B * H, P = N - w;
     float2* stats = reinterpret_cast<float2*>(ws + p.stats_off);
@@ -563,19 +564,19 @@ static hipError_t run_score(const T* Q, const T* K, int B, int H, int G, int N, 
     } else if (!mfma && w == 1 && G <= 16) {
         env.begin("score_stats_lastrow");
         if (G <= 4)
-            score_stats_lastrow_kernel<T, 4><<<grid1, dim3(256), 0, s>>>(Q, K, H, G, N, ks[0], ks[1], ks[2], p.n_chunks,
+            score_stats_lastrow_kernel<T, 4><<<grid1, dim3(256), 0, s>>>(Q, K, H, G, N, D, ks[0], ks[1], ks[2], p.n_chunks,
                                                                          p.chunk, stats);
         else if (G <= 8)
-            score_stats_lastrow_kernel<T, 8><<<grid1, dim3(256), 0, s>>>(Q, K, H, G, N, ks[0], ks[1], ks[2], p.n_chunks,
+            score_stats_lastrow_kernel<T, 8><<<grid1, dim3(256), 0, s>>>(Q, K, H, G, N, D, ks[0], ks[1], ks[2], p.n_chunks,
                                                                          p.chunk, stats);
         else
-            score_stats_lastrow_kernel<T, 16><<<grid1, dim3(256), 0, s>>>(Q, K, H, G, N, ks[0], ks[1], ks[2], p.n_chunks,
+            score_stats_lastrow_kernel<T, 16><<<grid1, dim3(256), 0, s>>>(Q, K, H, G, N, D, ks[0], ks[1], ks[2], p.n_chunks,
                                                                           p.chunk, stats);
         env.end();
     } else if (!mfma) {
         const int threads1 = (p.R + 63) / 64 * 64;
         env.begin("score_stats_alu");
-        score_stats_alu_kernel<T><<<grid1, dim3(threads1), 0, s>>>(Q, K, H, G, N, w, ks[0], ks[1], ks[2],
+        score_stats_alu_kernel<T><<<grid1, dim3(threads1), 0, s>>>(Q, K, H, G, N, D, w, ks[0], ks[1], ks[2],
                                                                    p.n_chunks, p.chunk, stats);
         env.end();
     }
@@ -604,7 +605,7 @@ static hipError_t run_score(const T* Q, const T* K, int B, int H, int G, int N, 
     if (!mfma) {
         env.begin("score_vote_alu");
         score_vote_alu_kernel<T><<<dim3((unsigned)(BH * n_tiles)), dim3(256), 0, s>>>(
-            Q, K, lse, H, G, N, w, ks[0], ks[1], ks[2], n_tiles, vote);
+            Q, K, lse, H, G, N, D, w, ks[0], ks[1], ks[2], n_tiles, vote);
         env.end();
     }
     env.begin("score_pool");
@@ -627,16 +628,16 @@ static hipError_t run_score(const T* Q, const T* K, int B, int H, int G, int N, 
 
 hipError_t launch_window_score(const void* Q, const void* K, uncomp_dtype dt, int B, int H, int G,
                                int N, int w, int pool, const int64_t ks[3], const ScorePlan& p,
-                               char* ws, float* score_out, const Env& env, const float* lse_nat) {
+                               char* ws, float* score_out, const Env& env, const float* lse_nat, int D) {
     if (dt == UNCOMP_BF16) {
         // the MFMA kernels need whole 16-row blocks per KV head, a window of 8 (the paper's l) or a multiple of 16,
         // and at most 256 rows per KV head
-        const bool mfma = !env.force_alu && (w % 16 == 0 || w == 8) && p.R <= 256 && p.R % 16 == 0;
+        const bool mfma = !env.force_alu && D == kD && (w % 16 == 0 || w == 8) && p.R <= 256 && p.R % 16 == 0;
         return run_score<bf16_bits>(static_cast<const bf16_bits*>(Q), static_cast<const bf16_bits*>(K), B, H,
-                                    G, N, w, pool, ks, p, ws, score_out, env, mfma, lse_nat);
+                                    G, N, w, pool, ks, p, ws, score_out, env, mfma, lse_nat, D);
     }
     return run_score<float>(static_cast<const float*>(Q), static_cast<const float*>(K), B, H, G, N, w,
-                            pool, ks, p, ws, score_out, env, false, lse_nat);
+                            pool, ks, p, ws, score_out, env, false, lse_nat, D);
 }
 
 }  // namespace uncomp

@@ -464,7 +464,7 @@ hipError_t launch_select_gather(const float* score, const int32_t* budget, const
                                 const void* V, uncomp_dtype dt, int B, int H, int N, int w,
                                 const int64_t ks[3], int cap, void* K_out, void* V_out,
                                 int32_t* idx_out, int32_t* len_out, const Env& env, const uint32_t* tile_range,
-                                int n_range_tiles) {
+                                int n_range_tiles, int D) {
     hipStream_t s = env.s;
     const int BH = B * H;
     env.begin("select");
@@ -475,7 +475,7 @@ hipError_t launch_select_gather(const float* score, const int32_t* budget, const
     if (e != hipSuccess || K == nullptr) return e;
     const int esz = dt == UNCOMP_BF16 ? 2 : 4;
     const int per16 = 16 / esz;                       // elements per 16-byte unit
-    const int lanes = kD / per16;                     // 16 (bf16) or 32 (fp32)
+    const int lanes = D / per16;                      // 16-byte units per row: 16 (bf16) or 32 (fp32) at D = 128
     const int rows_per_block = 256 / lanes;
     const int n_row_tiles = (cap + rows_per_block - 1) / rows_per_block;
     env.begin("gather");

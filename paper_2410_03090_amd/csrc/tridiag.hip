@@ -130,7 +130,7 @@ __device__ __forceinline__ int sturm_count(const double2* de, double x) {
 template <int kParts>
 __global__ __launch_bounds__(kD * kParts, kParts == 2 ? 2 : 1) void tridiag_entropy_kernel(
     const float* __restrict__ gram_part, const float* __restrict__ sum_part, int n_chunks, int N,
-    int k_trunc, unsigned flags, float* __restrict__ entropy_out, float* __restrict__ eig_out,
+    int k_trunc, unsigned flags, float* __restrict__ entropy_out, float* __restrict__ eig_out, int eig_ld,
     const double* __restrict__ trace_total) {
     constexpr int kThreads = kD * kParts, kWaves = kThreads / 64;
     constexpr int kHalf = kD / kParts;                           // rows of a column per thread
@@ -173,7 +173,7 @@ __global__ __launch_bounds__(kD * kParts, kParts == 2 ? 2 : 1) void tridiag_entr
     }
     if (degenerate) {
         if (tid == 0) entropy_out[m] = 0.f;
-        if (eig_out != nullptr && tid < kD) eig_out[(int64_t)m * kD + tid] = 0.f;
+        if (eig_out != nullptr && tid < eig_ld) eig_out[(int64_t)m * eig_ld + tid] = 0.f;
         return;
     }
     double a[kHalf];                                             // a[k] = A[64 hf + k][c]
@@ -340,22 +340,22 @@ __global__ __launch_bounds__(kD * kParts, kParts == 2 ? 2 : 1) void tridiag_entr
     }
     const double H = block_sum<kWaves>(term, sm.red, tid);
     if (tid == 0) entropy_out[m] = (float)H;
-    if (eig_out != nullptr && tid < kD)
-        eig_out[(int64_t)m * kD + tid] = whole > 0.0 ? (float)(mine / whole) : 0.f;
+    if (eig_out != nullptr && tid < eig_ld)        // eig_ld values per matrix: all 128, or the leading 64 of a 64-wide input
+        eig_out[(int64_t)m * eig_ld + tid] = whole > 0.0 ? (float)(mine / whole) : 0.f;
 }
 
 hipError_t launch_tridiag_entropy(int n_mat, int N, int k_trunc, unsigned flags, const EntropyPlan& p,
                                   char* ws, float* entropy_out, float* eig_out, const Env& env,
-                                  const double* trace_total) {
+                                  const double* trace_total, int eig_ld) {
     const float* gram = reinterpret_cast<const float*>(ws + p.gram_off);
     const float* sums = reinterpret_cast<const float*>(ws + p.sum_off);
     env.begin("tridiag_entropy");
     if (n_mat < 512)
         tridiag_entropy_kernel<4><<<dim3(n_mat), dim3(4 * kD), 0, env.s>>>(gram, sums, p.n_chunks, N, k_trunc, flags,
-                                                                         entropy_out, eig_out, trace_total);
+                                                                         entropy_out, eig_out, eig_ld, trace_total);
     else
         tridiag_entropy_kernel<2><<<dim3(n_mat), dim3(2 * kD), 0, env.s>>>(gram, sums, p.n_chunks, N, k_trunc, flags,
-                                                                         entropy_out, eig_out, trace_total);
+                                                                         entropy_out, eig_out, eig_ld, trace_total);
     env.end();
     return hipGetLastError();
 }

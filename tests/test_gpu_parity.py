@@ -305,6 +305,46 @@ def test_select_indices_only(ctx):
         assert idx[0, h, : len(ref)].cpu().tolist() == ref.tolist()
 
 
+# ------------------------------------------------------------------------- 64-wide heads
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_head_dim_64_all_four_calls(ctx, dtype):
+    """D = 64: the four hot calls against the oracle (entropy with both truncation readings and the spectrum,
+    budgets, scores, selection, gathered rows)."""
+    cfg = synth.tiny_config(dtype="f32" if dtype == torch.float32 else "bf16", B=2, H=3, G=4, N=1500, D=64, w=32,
+                            avg_budget=200, M=3, rank_lo=3, rank_hi=40)
+    K, V, Q = synth.gen_all(cfg, seed0=64)
+    Kd, Vd, Qd = K[0].to(DEV), V[0].to(DEV), Q[0].to(DEV)
+    X = Kd.reshape(cfg.B * cfg.H, cfg.N, 64)
+    for flags in (O.DEFAULT_FLAGS, O.FLAG_CENTER, 0):
+        for k in (16, 32, 64, 100):
+            ent, eig = ctx.head_entropy(X, k_trunc=k, flags=flags, want_eig=True)
+            torch.cuda.synchronize()
+            Href, eref = O.head_entropy(to_f64(K[0]).reshape(-1, cfg.N, 64), k_trunc=k, flags=flags)
+            np.testing.assert_allclose(ent.cpu().numpy(), Href, rtol=1e-4)
+            assert eig.shape == (cfg.B * cfg.H, 64)
+            np.testing.assert_allclose(eig.cpu().numpy(), eref, rtol=0, atol=2e-5)
+    ent = ctx.head_entropy(X, k_trunc=32).reshape(1, cfg.B, cfg.H)
+    hb, hg, lg, lt = ctx.assign_budgets(ent, cfg.M, cfg.n_max, cfg.step, cfg.N, cfg.w)
+    score = ctx.window_score(Qd, Kd, cfg.G, cfg.pool)
+    Ko, Vo, idx, ln = ctx.select_gather(score, hb[0], Kd, Vd, cfg.w, cfg.cap)
+    torch.cuda.synchronize()
+    rb = O.assign_budgets(ent.cpu().numpy(), cfg.M, cfg.n_max, cfg.step, cfg.N, cfg.w, 0.4, 512)
+    assert np.array_equal(hb.cpu().numpy(), rb[0])
+    sref = O.window_score(to_f64(Q[0]), to_f64(K[0]), cfg.G, cfg.pool)
+    np.testing.assert_allclose(score.cpu().numpy(), sref, rtol=2e-5)
+    lse = O.window_lse(to_f64(Q[0]), to_f64(K[0]), cfg.G)
+    s2 = ctx.window_score(Qd, Kd, cfg.G, cfg.pool, lse=torch.from_numpy(lse.astype(np.float32)).to(DEV))
+    np.testing.assert_allclose(s2.cpu().numpy(), sref, rtol=2e-5)
+    rKo, rVo, ridx, rln = O.select_gather(score.cpu().numpy().astype(np.float64), hb[0].cpu().numpy(), raw_bits(K[0]),
+                                          raw_bits(V[0]), cfg.w, cfg.cap)
+    assert np.array_equal(idx.cpu().numpy(), ridx) and np.array_equal(ln.cpu().numpy(), rln)
+    assert Ko.shape[-1] == 64
+    for b in range(cfg.B):
+        for h in range(cfg.H):
+            n = int(rln[b, h])
+            assert np.array_equal(raw_bits(Ko)[b, h, :n], rKo[b, h, :n]) and np.array_equal(raw_bits(Vo)[b, h, :n], rVo[b, h, :n])
+
+
 # ------------------------------------------------------------------------- whole path
 def _run_path(ctx, cfg, K, V, Q):
     """All four calls for the layers held in K/V/Q ([nl,B,H,N,D] / [nl,B,Hq,w,D])."""
@@ -411,7 +451,7 @@ def test_argument_errors(ctx):
     from paper_2410_03090_amd import binding
     X = torch.zeros(2, 64, 128, dtype=torch.bfloat16, device=DEV)
     with pytest.raises(binding.UncompError) as e:
-        ctx.head_entropy(torch.zeros(2, 64, 64, dtype=torch.bfloat16, device=DEV))
+        ctx.head_entropy(torch.zeros(2, 64, 96, dtype=torch.bfloat16, device=DEV))
     assert e.value.status == binding.ERR_UNSUPPORTED
     with pytest.raises(binding.UncompError) as e:
         ctx.head_entropy(X, k_trunc=0)
