@@ -18,8 +18,8 @@ namespace uncomp {
 // 8g..8g+7" (c = 0..7).  v_mfma_f32_16x16x32_bf16 on operands (cA, cB) then accumulates the
 // block G[8i+cA][8j+cB], i,j = 0..15; only cA <= cB is computed (36 of 64 blocks) and
 // mirrored on output.  Column sums come from v_dot2 against (1,1) on the same operands.
-// The four waves of a workgroup take 32-token steps round-robin with three steps of loads
-// in flight each, and combine their accumulators through LDS at the end of the chunk.
+// The eight waves of a workgroup (two per SIMD) take 32-token steps round-robin with kGramStages
+// steps of loads in flight each, and combine their accumulators through LDS at the end of the chunk.
 // ---------------------------------------------------------------------------------------
 typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 
@@ -91,7 +91,7 @@ __device__ __forceinline__ void gram_wave_accumulate(const bf16_bits* __restrict
                     __builtin_amdgcn_mfma_f32_16x16x32_bf16(v[ca], v[cb], acc[tri_index(ca, cb)], 0, 0, 0);
     };
 
-    // this wave's steps: wv, wv+4, ...; three in flight
+    // this wave's steps: wv, wv + kWaves, ...; kGramStages of them in flight
 #pragma unroll
     for (int st = 0; st < kGramStages; ++st) load_step(buf[st], wv + kWaves * st);
     for (int s0 = wv; s0 < n_steps; s0 += kWaves * kGramStages) {
