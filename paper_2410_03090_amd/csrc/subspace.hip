@@ -229,44 +229,49 @@ __global__ __launch_bounds__(256) void sub_reduce_kernel(const float* __restrict
     W[e] = (float)a;
 }
 
-// Partial Gram of W (D x 128, fp32) in fp64 over a slice of rows: gpart[slice][128][128].
-// Thread (ty, tx) owns the 8 x 8 block of entries (8 ty + i, 8 tx + j).
-__global__ __launch_bounds__(256) void sub_gram64_kernel(const float* __restrict__ W, int D, int rows_per_slice,
-                                                         double* __restrict__ gpart) {
-    __shared__ float rowbuf[8][kP];
-    const int tid = threadIdx.x, ty = tid >> 4, tx = tid & 15;
-    const int r0 = blockIdx.x * rows_per_slice, r1 = min(D, r0 + rows_per_slice);
-    double acc[8][8];
+// Partial Gram of W (D x 128, fp32) in fp64 over a slice of kGramRows rows: gpart[slice][128][128], on
+// v_mfma_f64_16x16x4_f64 (operands: lane l holds row / column l%16 and contraction index l/16; result:
+// column l%16, rows 4*(l/16)..+4).  The slice is staged in LDS as fp32 and widened on the way into the
+// operands (exact); wave w owns the output tile rows 2w and 2w+1, all eight tile columns.
+constexpr int kGramRows = 64;
+constexpr int kGramLd = 144;             // floats per staged row: four consecutive rows start 16 banks apart
+
+typedef double f64x4_t __attribute__((ext_vector_type(4)));
+
+__global__ __launch_bounds__(256) void sub_gram64_kernel(const float* __restrict__ W, int D, double* __restrict__ gpart) {
+    __shared__ __align__(16) float rows[kGramRows][kGramLd];
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int c = lane & 15, kk = lane >> 4;
+    const int r0 = blockIdx.x * kGramRows;
+    for (int e = tid; e < kGramRows * (kP / 4); e += 256) {
+        const int rr = e >> 5, q = e & 31;
+        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (r0 + rr < D) v = *reinterpret_cast<const float4*>(W + (int64_t)(r0 + rr) * kP + 4 * q);
+        *reinterpret_cast<float4*>(&rows[rr][4 * q]) = v;
+    }
+    __syncthreads();
+    f64x4_t acc[2][8];
 #pragma unroll
-    for (int i = 0; i < 8; ++i)
+    for (int t = 0; t < 2; ++t)
 #pragma unroll
-        for (int j = 0; j < 8; ++j) acc[i][j] = 0.0;
-    for (int r = r0; r < r1; r += 8) {
-        for (int e = tid; e < 8 * kP; e += 256) {
-            const int rr = e >> 7, j = e & 127;
-            rowbuf[rr][j] = r + rr < r1 ? W[(int64_t)(r + rr) * kP + j] : 0.f;
+        for (int J = 0; J < 8; ++J) acc[t][J] = f64x4_t{0.0, 0.0, 0.0, 0.0};
+    for (int k0 = 0; k0 < kGramRows; k0 += 4) {
+        const float* row = rows[k0 + kk];
+        const double a0 = (double)row[32 * wv + c], a1 = (double)row[32 * wv + 16 + c];
+#pragma unroll
+        for (int J = 0; J < 8; ++J) {
+            const double b = (double)row[16 * J + c];
+            acc[0][J] = __builtin_amdgcn_mfma_f64_16x16x4f64(a0, b, acc[0][J], 0, 0, 0);
+            acc[1][J] = __builtin_amdgcn_mfma_f64_16x16x4f64(a1, b, acc[1][J], 0, 0, 0);
         }
-        __syncthreads();
-#pragma unroll
-        for (int rr = 0; rr < 8; ++rr) {
-            double a[8], b[8];
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                a[i] = (double)rowbuf[rr][8 * ty + i];
-                b[i] = (double)rowbuf[rr][8 * tx + i];
-            }
-#pragma unroll
-            for (int i = 0; i < 8; ++i)
-#pragma unroll
-                for (int j = 0; j < 8; ++j) acc[i][j] = fma(a[i], b[j], acc[i][j]);
-        }
-        __syncthreads();
     }
     double* o = gpart + (int64_t)blockIdx.x * kP * kP;
 #pragma unroll
-    for (int i = 0; i < 8; ++i)
+    for (int t = 0; t < 2; ++t)
 #pragma unroll
-        for (int j = 0; j < 8; ++j) o[(8 * ty + i) * kP + 8 * tx + j] = acc[i][j];
+        for (int J = 0; J < 8; ++J)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) o[(32 * wv + 16 * t + 4 * v + kk) * kP + 16 * J + c] = acc[t][J][v];   // register v of lane group kk holds row 4v + kk
 }
 
 // gsum = sum of the slices (fixed order).
@@ -278,53 +283,151 @@ __global__ __launch_bounds__(256) void sub_gram64_sum_kernel(const double* __res
     gsum[e] = a;
 }
 
-// One workgroup: Cholesky G = L L^T in LDS (fp64), then Rinv = L^-T as fp32
-// so that Q = W Rinv has orthonormal columns.  A pivot below 1e-12 of the largest diagonal entry
-// retires its column (its row and column of Rinv are zero).
+// value of x in lane `src` (a compile-time constant after unrolling) as a wave-uniform double
+__device__ __forceinline__ double lane_value(double x, int src) {
+    const int lo = __builtin_amdgcn_readlane(__double2loint(x), src);
+    const int hi = __builtin_amdgcn_readlane(__double2hiint(x), src);
+    return __hiloint2double(hi, lo);
+}
+
+// One workgroup: Cholesky G = L L^T in LDS (fp64), then Rinv = L^-T as fp32 so that Q = W Rinv has
+// orthonormal columns.  A pivot below 1e-12 of the largest diagonal entry retires its column (its
+// row and column of Rinv are zero).  Both halves work on 16-wide blocks, three workgroup barriers
+// per block instead of two per column:
+//   factor   the 16 x 16 diagonal block in the registers of one wave (lane = row, values of other
+//            rows by v_readlane), the rows below it by forward substitution (one thread per row),
+//            the trailing triangle by a rank-16 update;
+//   invert   X = L^-1 block row by block row: the part that earlier block rows determine is a
+//            product of known blocks (all threads), the 16 x 16 rest a forward substitution (one
+//            thread per column).  X[k][c], k > c, lives at G[c][k] in the unused upper triangle.
 __global__ __launch_bounds__(256) void sub_chol_kernel(const double* __restrict__ gsum, float* __restrict__ Rinv) {
     extern __shared__ __align__(16) double G[];                // [128][129]
     __shared__ double dinv[kP];
     __shared__ double maxdiag;
-    constexpr int LD = kP + 1;
-    const int tid = threadIdx.x;
-    for (int e = tid; e < kP * kP; e += 256) G[(e >> 7) * LD + (e & 127)] = gsum[e];
+    constexpr int LD = kP + 1, B = 16, NB = kP / B;
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const double2* g2 = reinterpret_cast<const double2*>(gsum);
+#pragma unroll 8
+    for (int e = tid; e < kP * kP / 2; e += 256) {                 // 32 loads per thread, eight in flight
+        const double2 v = g2[e];
+        const int row = e >> 6, col = 2 * (e & 63);
+        G[row * LD + col] = v.x;
+        G[row * LD + col + 1] = v.y;
+    }
     __syncthreads();
-    if (tid == 0) {
-        double m = 0.0;
-        for (int i = 0; i < kP; ++i) m = fmax(m, G[i * LD + i]);
-        maxdiag = m;
+    if (wv == 0) {
+        double m = fmax(G[lane * LD + lane], G[(lane + 64) * LD + lane + 64]);
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) m = fmax(m, __shfl_xor(m, o, 64));
+        if (lane == 0) maxdiag = m;
     }
     __syncthreads();
     const double tol = maxdiag * 1e-12;
-    for (int j = 0; j < kP; ++j) {
-        const double piv = G[j * LD + j];
-        const bool live = piv > tol;
-        const double d = live ? sqrt(piv) : 0.0;
-        const double di = live ? 1.0 / d : 0.0;
-        __syncthreads();                                       // everyone has read the pivot
-        for (int i = j + tid; i < kP; i += 256) G[i * LD + j] = (i == j) ? d : G[i * LD + j] * di;
-        if (tid == 0) dinv[j] = di;
+    for (int p = 0; p < NB; ++p) {
+        const int j0 = B * p;
+        if (wv == 0) {
+            // diagonal block: lane i (and its copies in the upper lanes) holds row j0 + i
+            const int i = lane & (B - 1);
+            double a[B];
+#pragma unroll
+            for (int k = 0; k < B; ++k) a[k] = G[(j0 + i) * LD + j0 + k];
+#pragma unroll
+            for (int j = 0; j < B; ++j) {
+                const double piv = lane_value(a[j], j);
+                const bool live = piv > tol;
+                const double di = live ? rsqrt(piv) : 0.0;              // one reciprocal square root instead of a root and a division
+                const double d = piv * di;
+                if (i == j) a[j] = d;
+                else if (i > j) a[j] *= di;
+#pragma unroll
+                for (int k = j + 1; k < B; ++k) {
+                    const double lkj = lane_value(a[j], k);              // L[k][j]
+                    if (i >= k) a[k] -= a[j] * lkj;                      // G[i][k] -= L[i][j] L[k][j], j < k <= i
+                }
+                if (lane == 0) dinv[j0 + j] = di;
+            }
+            if (lane < B) {
+#pragma unroll
+                for (int k = 0; k < B; ++k)
+                    if (k <= i) G[(j0 + i) * LD + j0 + k] = a[k];
+            }
+        }
         __syncthreads();
-        // trailing update of the lower triangle: G[i][k] -= L[i][j] L[k][j], j < k <= i
-        for (int i = j + 1 + (tid >> 4); i < kP; i += 16) {
-            const double lij = G[i * LD + j];
-            for (int k = j + 1 + (tid & 15); k <= i; k += 16) G[i * LD + k] -= lij * G[k * LD + j];
+        {
+            // rows below the block: L[r][j0 + j] = (G[r][j0 + j] - sum_{k<j} L[r][j0 + k] L[j0 + j][j0 + k]) / L[j0 + j][j0 + j]
+            const int r = j0 + B + tid;
+            if (r < kP) {
+                double l[B];
+#pragma unroll
+                for (int j = 0; j < B; ++j) {
+                    double acc = G[r * LD + j0 + j];
+#pragma unroll
+                    for (int k = 0; k < j; ++k) acc -= l[k] * G[(j0 + j) * LD + j0 + k];
+                    l[j] = acc * dinv[j0 + j];
+                }
+#pragma unroll
+                for (int j = 0; j < B; ++j) G[r * LD + j0 + j] = l[j];
+            }
         }
+        __syncthreads();
+        {
+            // trailing lower triangle: G[i][k] -= sum_j L[i][j0 + j] L[k][j0 + j], j0 + B <= k <= i
+            const int ti = tid >> 4, tk = tid & 15;
+            for (int i = j0 + B + ti; i < kP; i += 16) {
+                double li[B];
+#pragma unroll
+                for (int j = 0; j < B; ++j) li[j] = G[i * LD + j0 + j];
+                for (int k = j0 + B + tk; k <= i; k += 16) {
+                    double acc = 0.0;
+#pragma unroll
+                    for (int j = 0; j < B; ++j) acc = fma(li[j], G[k * LD + j0 + j], acc);
+                    G[i * LD + k] -= acc;
+                }
+            }
+        }
+        __syncthreads();
     }
-    __syncthreads();
-    // column c of L^-1 by forward substitution (thread c): x_i = (delta_ic - sum_{k<i} L[i][k] x_k) / L[i][i].
-    // x is kept in row c of the (no longer needed) upper triangle, diagonal included; the reads
-    // of L touch the strict lower triangle only.
-    if (tid < kP) {
-        const int c = tid;
-        for (int i = 0; i < c; ++i) Rinv[(int64_t)c * kP + i] = 0.f;
-        for (int i = c; i < kP; ++i) {
-            double a = (i == c) ? 1.0 : 0.0;
-            for (int k = c; k < i; ++k) a -= G[i * LD + k] * G[c * LD + k];
-            const double x = a * dinv[i];
-            G[c * LD + i] = x;
-            Rinv[(int64_t)c * kP + i] = (float)x;             // Rinv = (L^-1)^T: Rinv[c][i] = Linv[i][c]
+    // X = L^-1, block row I at a time.  X[k][c] (k > c) is kept at G[c][k]; X[c][c] = dinv[c].
+    for (int I = 0; I < NB; ++I) {
+        const int i0 = B * I;
+        // what the earlier block rows contribute: S[i][c] = -sum_{k=c}^{i0-1} L[i][k] X[k][c], c < i0 <= i; parked at G[c][i]
+        for (int e = tid; e < B * i0; e += 256) {
+            const int c = e / B, i = i0 + e % B;
+            double acc = -G[i * LD + c] * dinv[c], acc1 = 0.0, acc2 = 0.0, acc3 = 0.0;
+            int k = c + 1;
+            for (; k + 3 < i0; k += 4) {                             // four independent chains hide the LDS latency
+                acc = fma(-G[i * LD + k], G[c * LD + k], acc);
+                acc1 = fma(-G[i * LD + k + 1], G[c * LD + k + 1], acc1);
+                acc2 = fma(-G[i * LD + k + 2], G[c * LD + k + 2], acc2);
+                acc3 = fma(-G[i * LD + k + 3], G[c * LD + k + 3], acc3);
+            }
+            for (; k < i0; ++k) acc = fma(-G[i * LD + k], G[c * LD + k], acc);
+            G[c * LD + i] = (acc + acc1) + (acc2 + acc3);
         }
+        __syncthreads();
+        // the block itself: x_i = (S_i - sum_{k = max(i0, c)}^{i-1} L[i][k] x_k) / L[i][i], column c by thread c
+        if (tid >= i0 + B && tid < kP) {
+#pragma unroll
+            for (int ii = 0; ii < B; ++ii) Rinv[(int64_t)tid * kP + i0 + ii] = 0.f;      // rows above column tid
+        } else if (tid < i0 + B) {
+            const int c = tid;
+            double x[B];
+#pragma unroll
+            for (int ii = 0; ii < B; ++ii) {
+                const int i = i0 + ii;
+                double acc = c < i0 ? G[c * LD + i] : (i == c ? 1.0 : 0.0);
+#pragma unroll
+                for (int kk = 0; kk < ii; ++kk) acc = fma(-G[i * LD + i0 + kk], x[kk], acc);     // x[kk] is 0 above column c
+                x[ii] = i < c ? 0.0 : acc * dinv[i];
+            }
+#pragma unroll
+            for (int ii = 0; ii < B; ++ii) {
+                const int i = i0 + ii;
+                if (i > c) G[c * LD + i] = x[ii];
+                Rinv[(int64_t)c * kP + i] = (float)x[ii];      // Rinv = (L^-1)^T: Rinv[c][i] = X[i][c], zero for i < c
+            }
+        }
+        __syncthreads();
     }
 }
 
@@ -342,7 +445,7 @@ MatrixPlan plan_matrix(int N, int D) {
     if (kc < 1) kc = 1;
     p.w_chunk = ((N + kc - 1) / kc + 15) / 16 * 16;
     p.w_chunks = (N + p.w_chunk - 1) / p.w_chunk;
-    p.gram_slices = (D + 255) / 256;
+    p.gram_slices = (D + kGramRows - 1) / kGramRows;
     p.ep = plan_entropy(1, N);
     size_t off = 0;
     auto take = [&](size_t bytes) {
@@ -402,7 +505,7 @@ static hipError_t run_matrix_entropy(const T* X, int n_mat, int N, int D, int64_
     const unsigned dp_blocks = (unsigned)(((int64_t)D * kP + 255) / 256);
     // Q = orth(W): Cholesky QR with the Gram in fp64
     auto orth = [&]() {
-        sub_gram64_kernel<<<dim3((unsigned)p.gram_slices), dim3(256), 0, s>>>(W, D, 256, gpart);
+        sub_gram64_kernel<<<dim3((unsigned)p.gram_slices), dim3(256), 0, s>>>(W, D, gpart);
         sub_gram64_sum_kernel<<<dim3(kP * kP / 256), dim3(256), 0, s>>>(gpart, p.gram_slices, gsum);
         sub_chol_kernel<<<dim3(1), dim3(256), chol_lds, s>>>(gsum, Rinv);
         sub_gemm_kernel<float, false><<<dim3((unsigned)((D + 63) / 64), 1), dim3(256), 0, s>>>(W, kP, Rinv, D, kP, kP, Q);
@@ -417,10 +520,15 @@ static hipError_t run_matrix_entropy(const T* X, int n_mat, int N, int D, int64_
     bf16_bits* Zh = reinterpret_cast<bf16_bits*>(ws + p.zsplit_off);
     bf16_bits* Zl = Zh + (size_t)N * kP;
     hipError_t perr = hipSuccess;
-    auto project = [&](const T* Xm) {       // Z = X Q
+    // The early rounds multiply by the high bf16 half of Q and Z only (relative error 2^-9 per product): what
+    // they get wrong is a small tilt of the iterated subspace, which the later rounds remove like any other
+    // component outside the dominant subspace.  The last quarter of the rounds (at least two) and the final
+    // projection use both halves.
+    const int first_precise = n_iter - (n_iter / 4 > 2 ? n_iter / 4 : 2);
+    auto project = [&](const T* Xm, bool precise) {       // Z = X Q
         if constexpr (sizeof(T) == 2) {
             if (mfma) {
-                hipError_t e = launch_xq_mfma(Xm, ldx, Q, N, D, Qt_hi, Qt_lo, p.z_splits, Zpart, Z, s);
+                hipError_t e = launch_xq_mfma(Xm, ldx, Q, N, D, Qt_hi, Qt_lo, p.z_splits, Zpart, Z, s, precise);
                 if (e != hipSuccess) perr = e;
                 return;
             }
@@ -440,7 +548,8 @@ static hipError_t run_matrix_entropy(const T* X, int n_mat, int N, int D, int64_
         sub_start_kernel<<<dim3(dp_blocks), dim3(256), 0, s>>>(W, D);
         orth();
         for (int it = 0; it < n_iter; ++it) {
-            project(Xm);
+            const bool precise = it >= first_precise;
+            project(Xm, precise);
             if (center) {
                 sub_zsum_part_kernel<<<dim3(kZsumParts), dim3(1024), 0, s>>>(sv, Q, D, zsum + kP);
                 sub_zsum_kernel<<<dim3(1), dim3(128), 0, s>>>(zsum + kP, zsum);
@@ -449,7 +558,7 @@ static hipError_t run_matrix_entropy(const T* X, int n_mat, int N, int D, int64_
             bool done = false;
             if constexpr (sizeof(T) == 2) {
                 if (mfma) {
-                    hipError_t e = launch_xtz_mfma(Xm, ldx, Z, N, D, Zh, Zl, p.t_chunk, p.t_chunks, Wpart, s);
+                    hipError_t e = launch_xtz_mfma(Xm, ldx, Z, N, D, Zh, Zl, p.t_chunk, p.t_chunks, Wpart, s, precise);
                     if (e != hipSuccess) return e;
                     w_parts = p.t_chunks;
                     done = true;
@@ -467,7 +576,7 @@ static hipError_t run_matrix_entropy(const T* X, int n_mat, int N, int D, int64_
                 orth();
             }
         }
-        project(Xm);
+        project(Xm, true);
         env.end();
         if (perr != hipSuccess) return perr;
         // the projected tokens go through the 128-wide entropy path; trace(C) replaces its own trace

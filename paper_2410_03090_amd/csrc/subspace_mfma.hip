@@ -43,6 +43,8 @@ __global__ __launch_bounds__(256) void sub_qt_split_kernel(const float* __restri
 // X rows come straight from global memory in MFMA A-operand layout (lane = row%16, 16 bytes), the
 // step's slice of Q^T (128 x 32, both halves) is staged in LDS by the whole workgroup, double
 // buffered, and read as B operands.
+// LO: also multiply by the low halves (off in the early rounds of the iteration, whose errors the later rounds remove).
+template <bool LO>
 __global__ __launch_bounds__(256) void sub_xq_mfma_kernel(const bf16_bits* __restrict__ X, int64_t ldx,
                                                           const bf16_bits* __restrict__ Qt_hi,
                                                           const bf16_bits* __restrict__ Qt_lo, int N, int D,
@@ -68,14 +70,18 @@ __global__ __launch_bounds__(256) void sub_xq_mfma_kernel(const bf16_bits* __res
         const int k0 = k_begin + 32 * step + 8 * s_piece;
         sh0 = *reinterpret_cast<const uint4*>(Qt_hi + (int64_t)s_col0 * D + k0);
         sh1 = *reinterpret_cast<const uint4*>(Qt_hi + (int64_t)(s_col0 + 64) * D + k0);
-        sl0 = *reinterpret_cast<const uint4*>(Qt_lo + (int64_t)s_col0 * D + k0);
-        sl1 = *reinterpret_cast<const uint4*>(Qt_lo + (int64_t)(s_col0 + 64) * D + k0);
+        if (LO) {
+            sl0 = *reinterpret_cast<const uint4*>(Qt_lo + (int64_t)s_col0 * D + k0);
+            sl1 = *reinterpret_cast<const uint4*>(Qt_lo + (int64_t)(s_col0 + 64) * D + k0);
+        }
     };
     auto stage_store = [&](int buf) {
         *reinterpret_cast<uint4*>(&qs[buf][0][s_col0 * kQtRow + 8 * s_piece]) = sh0;
         *reinterpret_cast<uint4*>(&qs[buf][0][(s_col0 + 64) * kQtRow + 8 * s_piece]) = sh1;
-        *reinterpret_cast<uint4*>(&qs[buf][1][s_col0 * kQtRow + 8 * s_piece]) = sl0;
-        *reinterpret_cast<uint4*>(&qs[buf][1][(s_col0 + 64) * kQtRow + 8 * s_piece]) = sl1;
+        if (LO) {
+            *reinterpret_cast<uint4*>(&qs[buf][1][s_col0 * kQtRow + 8 * s_piece]) = sl0;
+            *reinterpret_cast<uint4*>(&qs[buf][1][(s_col0 + 64) * kQtRow + 8 * s_piece]) = sl1;
+        }
     };
     // rows past the end re-read the last row (clamped, never predicated); their results are not stored
     auto load_a_next = [&](int step) {
@@ -103,13 +109,15 @@ __global__ __launch_bounds__(256) void sub_xq_mfma_kernel(const bf16_bits* __res
         for (int cb = 0; cb < 8; ++cb) {
             const bf16x8_t bh = __builtin_bit_cast(
                 bf16x8_t, *reinterpret_cast<const uint4*>(&qs[buf][0][(16 * cb + n) * kQtRow + 8 * kq]));
-            const bf16x8_t bl = __builtin_bit_cast(
-                bf16x8_t, *reinterpret_cast<const uint4*>(&qs[buf][1][(16 * cb + n) * kQtRow + 8 * kq]));
+            bf16x8_t bl = bh;
+            if (LO)
+                bl = __builtin_bit_cast(
+                    bf16x8_t, *reinterpret_cast<const uint4*>(&qs[buf][1][(16 * cb + n) * kQtRow + 8 * kq]));
 #pragma unroll
             for (int rb = 0; rb < 4; ++rb) {
                 const bf16x8_t av = __builtin_bit_cast(bf16x8_t, a_cur[rb]);
                 acc[rb][cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, bh, acc[rb][cb], 0, 0, 0);
-                acc[rb][cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, bl, acc[rb][cb], 0, 0, 0);
+                if (LO) acc[rb][cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, bl, acc[rb][cb], 0, 0, 0);
             }
         }
         if (more) stage_store(buf ^ 1);          // the other buffer: everyone left it at the last barrier
@@ -157,6 +165,7 @@ __global__ __launch_bounds__(256) void sub_z_split_kernel(const float* __restric
 // of 32 tokens and leaves its 8 operands in LDS (double buffered, one barrier per round); then every
 // wave multiplies all four steps with its own 32 columns of Z, whose operands (2 columns per lane)
 // it builds itself.  Accumulator block (c, b): feature 8 i + c, column 32 w + 2 n + b.
+template <bool LO>
 __global__ __launch_bounds__(256) void sub_xtz_mfma_kernel(const bf16_bits* __restrict__ X, int64_t ldx,
                                                            const bf16_bits* __restrict__ Zh,
                                                            const bf16_bits* __restrict__ Zl, int N, int D, int t_chunk,
@@ -226,7 +235,7 @@ __global__ __launch_bounds__(256) void sub_xtz_mfma_kernel(const bf16_bits* __re
             for (int e = 0; e < 8; ++e) {
                 const int t = min(t0 + e, N - 1);                    // clamped: X is zero there anyway
                 zh[e] = *reinterpret_cast<const uint32_t*>(Zh + (int64_t)t * kP + col0);
-                zl[e] = *reinterpret_cast<const uint32_t*>(Zl + (int64_t)t * kP + col0);
+                zl[e] = LO ? *reinterpret_cast<const uint32_t*>(Zl + (int64_t)t * kP + col0) : 0u;
             }
             bf16x8_t bh0, bh1, bl0, bl1;
             {
@@ -247,9 +256,9 @@ __global__ __launch_bounds__(256) void sub_xtz_mfma_kernel(const bf16_bits* __re
             for (int c = 0; c < 8; ++c) {
                 const bf16x8_t av = __builtin_bit_cast(bf16x8_t, xs[buf][st][c][lane]);
                 acc[c][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, bh0, acc[c][0], 0, 0, 0);
-                acc[c][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, bl0, acc[c][0], 0, 0, 0);
+                if (LO) acc[c][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, bl0, acc[c][0], 0, 0, 0);
                 acc[c][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, bh1, acc[c][1], 0, 0, 0);
-                acc[c][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, bl1, acc[c][1], 0, 0, 0);
+                if (LO) acc[c][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, bl1, acc[c][1], 0, 0, 0);
             }
         }
         if (more) store_x(buf ^ 1);
@@ -283,13 +292,14 @@ __global__ __launch_bounds__(256) void sub_sum_parts_kernel(const float* __restr
 }
 
 hipError_t launch_xq_mfma(const bf16_bits* X, int64_t ldx, const float* Q, int N, int D, bf16_bits* Qt_hi,
-                          bf16_bits* Qt_lo, int n_split, float* Zpart, float* Z, hipStream_t s) {
+                          bf16_bits* Qt_lo, int n_split, float* Zpart, float* Z, hipStream_t s, bool precise) {
     sub_qt_split_kernel<<<dim3((unsigned)(D / 32), kP / 32), dim3(256), 0, s>>>(Q, D, Qt_hi, Qt_lo);
     const int k_chunk = ((D + n_split - 1) / n_split + 31) / 32 * 32;
     const int splits = (D + k_chunk - 1) / k_chunk;
     float* dst = splits == 1 ? Z : Zpart;
-    sub_xq_mfma_kernel<<<dim3((unsigned)((N + 255) / 256), (unsigned)splits), dim3(256), 0, s>>>(X, ldx, Qt_hi, Qt_lo, N, D,
-                                                                                              k_chunk, dst);
+    const dim3 grid((unsigned)((N + 255) / 256), (unsigned)splits);
+    if (precise) sub_xq_mfma_kernel<true><<<grid, dim3(256), 0, s>>>(X, ldx, Qt_hi, Qt_lo, N, D, k_chunk, dst);
+    else sub_xq_mfma_kernel<false><<<grid, dim3(256), 0, s>>>(X, ldx, Qt_hi, Qt_lo, N, D, k_chunk, dst);
     if (splits > 1) {
         const int64_t total = (int64_t)N * kP;
         sub_sum_parts_kernel<<<dim3((unsigned)((total / 4 + 255) / 256)), dim3(256), 0, s>>>(Zpart, splits, total, Z);
@@ -299,11 +309,12 @@ hipError_t launch_xq_mfma(const bf16_bits* X, int64_t ldx, const float* Q, int N
 
 // Wpart[tc][D][128] = partial X^T Z over token chunks; Zh / Zl are scratch for the two halves of Z.
 hipError_t launch_xtz_mfma(const bf16_bits* X, int64_t ldx, const float* Z, int N, int D, bf16_bits* Zh, bf16_bits* Zl,
-                           int t_chunk, int n_tchunks, float* Wpart, hipStream_t s) {
+                           int t_chunk, int n_tchunks, float* Wpart, hipStream_t s, bool precise) {
     const int64_t total = (int64_t)N * kP;
     sub_z_split_kernel<<<dim3((unsigned)((total / 4 + 255) / 256)), dim3(256), 0, s>>>(Z, total, Zh, Zl);
-    sub_xtz_mfma_kernel<<<dim3((unsigned)(D / 128), (unsigned)n_tchunks), dim3(256), 0, s>>>(X, ldx, Zh, Zl, N, D, t_chunk,
-                                                                                          Wpart);
+    const dim3 grid((unsigned)(D / 128), (unsigned)n_tchunks);
+    if (precise) sub_xtz_mfma_kernel<true><<<grid, dim3(256), 0, s>>>(X, ldx, Zh, Zl, N, D, t_chunk, Wpart);
+    else sub_xtz_mfma_kernel<false><<<grid, dim3(256), 0, s>>>(X, ldx, Zh, Zl, N, D, t_chunk, Wpart);
     return hipGetLastError();
 }
 
