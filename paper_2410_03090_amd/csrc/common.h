@@ -154,12 +154,13 @@ hipError_t launch_labels_to_budget(const int32_t* labels, int L, int B, int H, i
 struct MatrixPlan {
     int stat_chunks, stat_chunk;     // token chunks of the column statistics
     int w_chunks, w_chunk;           // token chunks of W = X^T Z
-    int gram_slices;                 // row slices of the fp64 Gram of W
+    int gram_slices, gram_rows;      // row slices of the fp64 Gram of W
+    int zgram_slices, zgram_rows;    // token slices of the fp64 Gram of the projected tokens
     int z_splits;                    // split of the sum over d in the MFMA version of Z = X Q
     int t_chunks, t_chunk;           // token chunks of the MFMA version of W = X^T Z
     size_t qt_off, zpart_off, zsplit_off;
     EntropyPlan ep;                  // the 128-wide entropy path on the projected tokens
-    size_t ep_off, statpart_off, s_off, trace_off, zsum_off, q_off, w_off, wpart_off, z_off, gpart_off, rinv_off;
+    size_t ep_off, statpart_off, s_off, trace_off, zsum_off, q_off, w_off, wpart_off, z_off, gpart_off, spart_off, rinv_off;
     size_t bytes;
 };
 MatrixPlan plan_matrix(int N, int D);

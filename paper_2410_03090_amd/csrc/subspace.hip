@@ -229,58 +229,119 @@ __global__ __launch_bounds__(256) void sub_reduce_kernel(const float* __restrict
     W[e] = (float)a;
 }
 
-// Partial Gram of W (D x 128, fp32) in fp64 over a slice of kGramRows rows: gpart[slice][128][128], on
-// v_mfma_f64_16x16x4_f64 (operands: lane l holds row / column l%16 and contraction index l/16; result:
-// column l%16, rows 4*(l/16)..+4).  The slice is staged in LDS as fp32 and widened on the way into the
-// operands (exact); wave w owns the output tile rows 2w and 2w+1, all eight tile columns.
+// Partial Gram of a tall fp32 matrix A (n_rows x 128) in fp64: gpart[slice][128][128] (+ the column sums of
+// the slice in spart[slice][128] when asked for) on v_mfma_f64_16x16x4_f64.  Operands: lane l holds row /
+// column l%16 at contraction index l/16; result register v of lane l: row 4v + l/16, column l%16.  The rows
+// are staged in LDS 64 at a time as fp32 (next tile's loads in flight during the products) and widened on
+// the way into the operands (exact).  Only the 36 tiles on and above the diagonal are computed, nine per
+// wave (tile rows w and 7 - w); the write-out mirrors them.
 constexpr int kGramRows = 64;
 constexpr int kGramLd = 144;             // floats per staged row: four consecutive rows start 16 banks apart
 
 typedef double f64x4_t __attribute__((ext_vector_type(4)));
 
-__global__ __launch_bounds__(256) void sub_gram64_kernel(const float* __restrict__ W, int D, double* __restrict__ gpart) {
+__global__ __launch_bounds__(256) void sub_gram64_kernel(const float* __restrict__ A, int n_rows, int rows_per_wg,
+                                                         double* __restrict__ gpart, double* __restrict__ spart) {
     __shared__ __align__(16) float rows[kGramRows][kGramLd];
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int c = lane & 15, kk = lane >> 4;
-    const int r0 = blockIdx.x * kGramRows;
-    for (int e = tid; e < kGramRows * (kP / 4); e += 256) {
-        const int rr = e >> 5, q = e & 31;
-        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (r0 + rr < D) v = *reinterpret_cast<const float4*>(W + (int64_t)(r0 + rr) * kP + 4 * q);
-        *reinterpret_cast<float4*>(&rows[rr][4 * q]) = v;
-    }
-    __syncthreads();
-    f64x4_t acc[2][8];
+    const int r_begin = blockIdx.x * rows_per_wg;
+    const int r_end = min(n_rows, r_begin + rows_per_wg);
+    const int I1 = wv, I2 = 7 - wv, n1 = 8 - wv;             // slot s < n1: tile (I1, I1 + s); else (I2, I2 + s - n1)
+    f64x4_t acc[9];
 #pragma unroll
-    for (int t = 0; t < 2; ++t)
+    for (int sl = 0; sl < 9; ++sl) acc[sl] = f64x4_t{0.0, 0.0, 0.0, 0.0};
+    double csum = 0.0;
+    float4 pre[8];
+    auto fetch = [&](int r0) {
 #pragma unroll
-        for (int J = 0; J < 8; ++J) acc[t][J] = f64x4_t{0.0, 0.0, 0.0, 0.0};
-    for (int k0 = 0; k0 < kGramRows; k0 += 4) {
-        const float* row = rows[k0 + kk];
-        const double a0 = (double)row[32 * wv + c], a1 = (double)row[32 * wv + 16 + c];
+        for (int i = 0; i < 8; ++i) {
+            const int e = tid + 256 * i, rr = e >> 5, q = e & 31;
+            pre[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (r0 + rr < r_end) pre[i] = *reinterpret_cast<const float4*>(A + (int64_t)(r0 + rr) * kP + 4 * q);
+        }
+    };
+    if (r_begin < r_end) fetch(r_begin);
+    for (int r0 = r_begin; r0 < r_end; r0 += kGramRows) {
+        __syncthreads();                                      // the previous tile has been read
 #pragma unroll
-        for (int J = 0; J < 8; ++J) {
-            const double b = (double)row[16 * J + c];
-            acc[0][J] = __builtin_amdgcn_mfma_f64_16x16x4f64(a0, b, acc[0][J], 0, 0, 0);
-            acc[1][J] = __builtin_amdgcn_mfma_f64_16x16x4f64(a1, b, acc[1][J], 0, 0, 0);
+        for (int i = 0; i < 8; ++i) {
+            const int e = tid + 256 * i;
+            *reinterpret_cast<float4*>(&rows[e >> 5][4 * (e & 31)]) = pre[i];
+        }
+        __syncthreads();
+        if (r0 + kGramRows < r_end) fetch(r0 + kGramRows);
+        if (spart != nullptr && tid < kP) {
+#pragma unroll 8
+            for (int rr = 0; rr < kGramRows; ++rr) csum += (double)rows[rr][tid];
+        }
+        for (int k0 = 0; k0 < kGramRows; k0 += 4) {
+            const float* row = rows[k0 + kk];
+            const double a1 = (double)row[16 * I1 + c], a2 = (double)row[16 * I2 + c];
+#pragma unroll
+            for (int sl = 0; sl < 9; ++sl) {
+                const bool first = sl < n1;
+                const int J = first ? I1 + sl : I2 + sl - n1;
+                const double bv = (double)row[16 * J + c];
+                acc[sl] = __builtin_amdgcn_mfma_f64_16x16x4f64(first ? a1 : a2, bv, acc[sl], 0, 0, 0);
+            }
         }
     }
     double* o = gpart + (int64_t)blockIdx.x * kP * kP;
 #pragma unroll
-    for (int t = 0; t < 2; ++t)
+    for (int sl = 0; sl < 9; ++sl) {
+        const bool first = sl < n1;
+        const int I = first ? I1 : I2, J = first ? I1 + sl : I2 + sl - n1;
 #pragma unroll
-        for (int J = 0; J < 8; ++J)
-#pragma unroll
-            for (int v = 0; v < 4; ++v) o[(32 * wv + 16 * t + 4 * v + kk) * kP + 16 * J + c] = acc[t][J][v];   // register v of lane group kk holds row 4v + kk
+        for (int v = 0; v < 4; ++v) {
+            const int r = 16 * I + 4 * v + kk, col = 16 * J + c;
+            o[r * kP + col] = acc[sl][v];
+            if (I != J) o[col * kP + r] = acc[sl][v];
+        }
+    }
+    if (spart != nullptr && tid < kP) spart[(int64_t)blockIdx.x * kP + tid] = csum;
 }
 
-// gsum = sum of the slices (fixed order).
+// gsum = sum of the slices (fixed order); four loads in flight per thread.
 __global__ __launch_bounds__(256) void sub_gram64_sum_kernel(const double* __restrict__ gpart, int n_slices,
                                                              double* __restrict__ gsum) {
     const int e = blockIdx.x * 256 + threadIdx.x;
+    const double* g = gpart + e;
     double a = 0.0;
-    for (int s = 0; s < n_slices; ++s) a += gpart[(int64_t)s * kP * kP + e];
+    int sl = 0;
+    for (; sl + 3 < n_slices; sl += 4) {
+        const double v0 = g[(int64_t)sl * kP * kP], v1 = g[(int64_t)(sl + 1) * kP * kP];
+        const double v2 = g[(int64_t)(sl + 2) * kP * kP], v3 = g[(int64_t)(sl + 3) * kP * kP];
+        a = (((a + v0) + v1) + v2) + v3;
+    }
+    for (; sl < n_slices; ++sl) a += g[(int64_t)sl * kP * kP];
     gsum[e] = a;
+}
+
+// The same sums for the Gram of the projected tokens, rounded to the fp32 single-chunk layout that the
+// 128-wide eigenvalue kernels read: gram[128*128], then the column sums sums[128] (block 64 of the grid).
+__global__ __launch_bounds__(256) void sub_zgram_finish_kernel(const double* __restrict__ gpart,
+                                                               const double* __restrict__ spart, int n_slices,
+                                                               float* __restrict__ gram, float* __restrict__ sums) {
+    if (blockIdx.x == kP * kP / 256) {
+        if (threadIdx.x < kP) {
+            double a = 0.0;
+            for (int sl = 0; sl < n_slices; ++sl) a += spart[(int64_t)sl * kP + threadIdx.x];
+            sums[threadIdx.x] = (float)a;
+        }
+        return;
+    }
+    const int e = blockIdx.x * 256 + threadIdx.x;
+    const double* g = gpart + e;
+    double a = 0.0;
+    int sl = 0;
+    for (; sl + 3 < n_slices; sl += 4) {
+        const double v0 = g[(int64_t)sl * kP * kP], v1 = g[(int64_t)(sl + 1) * kP * kP];
+        const double v2 = g[(int64_t)(sl + 2) * kP * kP], v3 = g[(int64_t)(sl + 3) * kP * kP];
+        a = (((a + v0) + v1) + v2) + v3;
+    }
+    for (; sl < n_slices; ++sl) a += g[(int64_t)sl * kP * kP];
+    gram[e] = (float)a;
 }
 
 // value of x in lane `src` (a compile-time constant after unrolling) as a wave-uniform double
@@ -445,8 +506,17 @@ MatrixPlan plan_matrix(int N, int D) {
     if (kc < 1) kc = 1;
     p.w_chunk = ((N + kc - 1) / kc + 15) / 16 * 16;
     p.w_chunks = (N + p.w_chunk - 1) / p.w_chunk;
-    p.gram_slices = (D + kGramRows - 1) / kGramRows;
-    p.ep = plan_entropy(1, N);
+    // Gram of W: 128-row slices; Gram of the projected tokens: one workgroup per CU at most, whole 64-row tiles each
+    p.gram_rows = 2 * kGramRows;
+    p.gram_slices = (D + p.gram_rows - 1) / p.gram_rows;
+    p.zgram_rows = ((N + 255) / 256 + kGramRows - 1) / kGramRows * kGramRows;
+    p.zgram_slices = (N + p.zgram_rows - 1) / p.zgram_rows;
+    // the eigenvalue kernel reads one already summed chunk
+    p.ep.n_chunks = 1;
+    p.ep.chunk = N;
+    p.ep.gram_off = 0;
+    p.ep.sum_off = (size_t)kP * kP * sizeof(float);
+    p.ep.bytes = p.ep.sum_off + (size_t)kP * sizeof(float);
     size_t off = 0;
     auto take = [&](size_t bytes) {
         const size_t at = off;
@@ -468,7 +538,9 @@ MatrixPlan plan_matrix(int N, int D) {
     p.t_chunks = (N + p.t_chunk - 1) / p.t_chunk;
     p.wpart_off = take((size_t)(p.w_chunks > p.t_chunks ? p.w_chunks : p.t_chunks) * D * kP * sizeof(float));
     p.z_off = take((size_t)N * kP * sizeof(float));
-    p.gpart_off = take((size_t)(p.gram_slices + 1) * kP * kP * sizeof(double));     // slices, then their sum
+    const int max_slices = p.gram_slices > p.zgram_slices ? p.gram_slices : p.zgram_slices;
+    p.gpart_off = take((size_t)(max_slices + 1) * kP * kP * sizeof(double));     // slices, then their sum
+    p.spart_off = take((size_t)p.zgram_slices * kP * sizeof(double));
     p.rinv_off = take((size_t)kP * kP * sizeof(float));
     // bf16 MFMA products: Q^T as two bf16 halves, partial Z of the split over d
     const int row_wgs = (N + 255) / 256;
@@ -479,7 +551,7 @@ MatrixPlan plan_matrix(int N, int D) {
     p.z_splits = zs;
     p.qt_off = take((size_t)2 * kP * D * sizeof(bf16_bits));
     p.zpart_off = take(zs > 1 ? (size_t)zs * N * kP * sizeof(float) : 0);
-    p.zsplit_off = take((size_t)2 * N * kP * sizeof(bf16_bits));
+    p.zsplit_off = take((size_t)2 * (((size_t)N + 127) / 128 * 128) * kP * sizeof(bf16_bits));
     p.bytes = off;
     return p;
 }
@@ -499,26 +571,29 @@ static hipError_t run_matrix_entropy(const T* X, int n_mat, int N, int D, int64_
     float* Wpart = reinterpret_cast<float*>(ws + p.wpart_off);
     float* Z = reinterpret_cast<float*>(ws + p.z_off);
     double* gpart = reinterpret_cast<double*>(ws + p.gpart_off);
-    double* gsum = gpart + (size_t)p.gram_slices * kP * kP;
+    double* gsum = gpart + (size_t)(p.gram_slices > p.zgram_slices ? p.gram_slices : p.zgram_slices) * kP * kP;
+    double* spart = reinterpret_cast<double*>(ws + p.spart_off);
     float* Rinv = reinterpret_cast<float*>(ws + p.rinv_off);
     const size_t chol_lds = (size_t)kP * (kP + 1) * sizeof(double);
     const unsigned dp_blocks = (unsigned)(((int64_t)D * kP + 255) / 256);
     // Q = orth(W): Cholesky QR with the Gram in fp64
     auto orth = [&]() {
-        sub_gram64_kernel<<<dim3((unsigned)p.gram_slices), dim3(256), 0, s>>>(W, D, gpart);
+        sub_gram64_kernel<<<dim3((unsigned)p.gram_slices), dim3(256), 0, s>>>(W, D, p.gram_rows, gpart, nullptr);
         sub_gram64_sum_kernel<<<dim3(kP * kP / 256), dim3(256), 0, s>>>(gpart, p.gram_slices, gsum);
         sub_chol_kernel<<<dim3(1), dim3(256), chol_lds, s>>>(gsum, Rinv);
         sub_gemm_kernel<float, false><<<dim3((unsigned)((D + 63) / 64), 1), dim3(256), 0, s>>>(W, kP, Rinv, D, kP, kP, Q);
     };
     // bf16 inputs with 16-byte aligned rows take the MFMA products, everything else the fp32 ALUs
+    // (rows at most 2^22 elements apart: those kernels address 256 rows with 32-bit byte offsets)
     bool mfma = false;
     if constexpr (sizeof(T) == 2)
-        mfma = !env.force_alu && (ldx % 8) == 0 && (mat_stride % 8) == 0 && (reinterpret_cast<uintptr_t>(X) & 15u) == 0;
+        mfma = !env.force_alu && (ldx % 8) == 0 && (mat_stride % 8) == 0 && (reinterpret_cast<uintptr_t>(X) & 15u) == 0 &&
+               ldx <= ((int64_t)1 << 22);
     bf16_bits* Qt_hi = reinterpret_cast<bf16_bits*>(ws + p.qt_off);
     bf16_bits* Qt_lo = Qt_hi + (size_t)kP * D;
     float* Zpart = reinterpret_cast<float*>(ws + p.zpart_off);
     bf16_bits* Zh = reinterpret_cast<bf16_bits*>(ws + p.zsplit_off);
-    bf16_bits* Zl = Zh + (size_t)N * kP;
+    bf16_bits* Zl = Zh + (((size_t)N + 127) / 128 * 128) * kP;
     hipError_t perr = hipSuccess;
     // The early rounds multiply by the high bf16 half of Q and Z only (relative error 2^-9 per product): what
     // they get wrong is a small tilt of the iterated subspace, which the later rounds remove like any other
@@ -580,9 +655,13 @@ static hipError_t run_matrix_entropy(const T* X, int n_mat, int N, int D, int64_
         env.end();
         if (perr != hipSuccess) return perr;
         // the projected tokens go through the 128-wide entropy path; trace(C) replaces its own trace
-        hipError_t e = launch_gram(Z, UNCOMP_F32, 1, N, (int64_t)N * kP, kP, p.ep, ws + p.ep_off, env);
-        if (e != hipSuccess) return e;
-        e = launch_tridiag_entropy(1, N, k_trunc, flags, p.ep, ws + p.ep_off, entropy_out + m,
+        env.begin("matrix_gram");
+        sub_gram64_kernel<<<dim3((unsigned)p.zgram_slices), dim3(256), 0, s>>>(Z, N, p.zgram_rows, gpart, spart);
+        sub_zgram_finish_kernel<<<dim3(kP * kP / 256 + 1), dim3(256), 0, s>>>(
+            gpart, spart, p.zgram_slices, reinterpret_cast<float*>(ws + p.ep_off + p.ep.gram_off),
+            reinterpret_cast<float*>(ws + p.ep_off + p.ep.sum_off));
+        env.end();
+        hipError_t e = launch_tridiag_entropy(1, N, k_trunc, flags, p.ep, ws + p.ep_off, entropy_out + m,
                                    eig_out != nullptr ? eig_out + (int64_t)m * kP : nullptr, env,
                                    trace);
         if (e != hipSuccess) return e;
@@ -600,7 +679,11 @@ hipError_t launch_matrix_entropy(const void* X, uncomp_dtype dt, int n_mat, int 
                               entropy_out, eig_out, env);
 }
 
+hipError_t init_subspace_mfma_kernels();
+
 hipError_t init_subspace_kernels() {
+    hipError_t e = init_subspace_mfma_kernels();
+    if (e != hipSuccess) return e;
     return allow_dynamic_lds(reinterpret_cast<const void*>(sub_chol_kernel), (size_t)kP * (kP + 1) * sizeof(double));
 }
 

@@ -10,7 +10,7 @@ namespace uncomp {
 namespace {
 
 constexpr int kP = 128;
-constexpr int kQtRow = 40;               // LDS row of one column of Q^T: 32 elements + 8 of padding (80 bytes:
+constexpr int kQtRow = 72;               // LDS row of one column of Q^T: 64 elements + 8 of padding (144 bytes:
                                          // 16 consecutive rows then start in 16 different 16-byte bank groups)
 
 // round-to-nearest-even bf16 of a finite float
@@ -39,91 +39,138 @@ __global__ __launch_bounds__(256) void sub_qt_split_kernel(const float* __restri
 }
 
 // out[kc][t][j] = sum over the k chunk of X[t][d] (Qt_hi[j][d] + Qt_lo[j][d]).
-// Workgroup: 256 rows of X; wave: 64 rows (four 16-row blocks) x 128 columns.  Per step of 32 d the
-// X rows come straight from global memory in MFMA A-operand layout (lane = row%16, 16 bytes), the
-// step's slice of Q^T (128 x 32, both halves) is staged in LDS by the whole workgroup, double
-// buffered, and read as B operands.
+// Workgroup: 256 rows of X; wave: 64 rows (four 16-row blocks) x 128 columns.  Per step of 64 d (one whole
+// 128-byte line of every row: with half lines a sixth of X came from HBM twice, the other half having left
+// the L2 in between) the X rows come straight from global memory in MFMA A-operand layout (lane = row%16,
+// 16 bytes per 32 d), one step ahead; the step's slice of Q^T (128 x 64, both halves) is staged in LDS by
+// the whole workgroup, double buffered, and read as B operands.  The step loop is unrolled twice so that
+// the two register sets of X rows are addressed by constants and no copy waits for a load in flight.
+// Workgroups start at different steps of the sum over d and wrap around, which spreads the rows that are
+// read at one time over the HBM channels.
 // LO: also multiply by the low halves (off in the early rounds of the iteration, whose errors the later rounds remove).
+template <int V>
+struct phase_t {
+    static constexpr int value = V;
+};
+
+constexpr int kQStep = 64;                                           // d per step
+template <bool LO>
+constexpr size_t xq_lds_bytes() {
+    return (size_t)2 * (LO ? 2 : 1) * kP * kQtRow * sizeof(bf16_bits);
+}
+
 template <bool LO>
 __global__ __launch_bounds__(256) void sub_xq_mfma_kernel(const bf16_bits* __restrict__ X, int64_t ldx,
                                                           const bf16_bits* __restrict__ Qt_hi,
                                                           const bf16_bits* __restrict__ Qt_lo, int N, int D,
                                                           int k_chunk, float* __restrict__ out) {
-    __shared__ __align__(16) bf16_bits qs[2][2][kP * kQtRow];         // [buffer][half][column][d]
+    extern __shared__ __align__(16) bf16_bits qs_raw[];              // [buffer][half][column][kQtRow]
+    constexpr int kHalf = kP * kQtRow, kBuf = (LO ? 2 : 1) * kHalf;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int n = lane & 15, kq = lane >> 4;
     const int row0 = blockIdx.x * 256 + wv * 64;
     const int kc = blockIdx.y;
     const int k_begin = kc * k_chunk, k_end = min(D, k_begin + k_chunk);
-    const int n_steps = (k_end - k_begin) >> 5;
+    const int n_steps = (k_end - k_begin) / kQStep;
     f32x4_t acc[4][8];
 #pragma unroll
     for (int rb = 0; rb < 4; ++rb)
 #pragma unroll
         for (int cb = 0; cb < 8; ++cb) acc[rb][cb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
-    // staging: 128 columns x 4 pieces of 8 d, for both halves: four 16-byte loads per thread
-    const int s_col0 = tid >> 2, s_piece = tid & 3;                    // columns s_col0 and s_col0 + 64
-    uint4 sh0, sh1, sl0, sl1;                                        // staged pieces of Q^T (named: an array here ends up in scratch)
-    uint4 a_cur[4], a_nxt[4];
-    auto stage_load = [&](int step) {
-        const int k0 = k_begin + 32 * step + 8 * s_piece;
-        sh0 = *reinterpret_cast<const uint4*>(Qt_hi + (int64_t)s_col0 * D + k0);
-        sh1 = *reinterpret_cast<const uint4*>(Qt_hi + (int64_t)(s_col0 + 64) * D + k0);
+    // staging: 128 columns x 8 pieces of 8 d per half: four 16-byte loads per thread and half
+    const int s_col0 = tid >> 3, s_piece = tid & 7;                    // columns s_col0 + 32 i
+    uint4 sh0, sh1, sh2, sh3, sl0, sl1, sl2, sl3;                    // (named: an array here ends up in scratch)
+    uint4 a[2][2][4];                                                // X rows: [set][32-d half of the step][row block]
+    // rows past the end re-read the last row (clamped, never predicated); their results are not stored
+    // addresses = a base that is uniform over the workgroup + a 32-bit byte offset per lane (the launcher
+    // checks that 256 rows of X and all of Q^T span less than 4 GiB)
+    const char* xwg = reinterpret_cast<const char*>(X + (int64_t)blockIdx.x * 256 * ldx + k_begin);
+    uint32_t xoff[4];
+#pragma unroll
+    for (int rb = 0; rb < 4; ++rb)
+        xoff[rb] = (uint32_t)(min(row0 + 16 * rb + n, N - 1) - blockIdx.x * 256) * (uint32_t)(ldx * 2) + 16u * kq;
+    const char* qwg = reinterpret_cast<const char*>(Qt_hi + k_begin);
+    const int64_t lo_bytes = reinterpret_cast<const char*>(Qt_lo) - reinterpret_cast<const char*>(Qt_hi);
+    const uint32_t qoff = ((uint32_t)s_col0 * (uint32_t)D + 8u * s_piece) * 2u;
+    const int64_t q32 = (int64_t)32 * D * 2;                         // 32 columns on, in bytes
+    const int rot = (int)(((int64_t)blockIdx.x * n_steps) / gridDim.x);
+    auto at_step = [&](int step) {
+        const int k = step + rot;
+        return k >= n_steps ? k - n_steps : k;
+    };
+    auto stage_load = [&](int step_seq) {
+        const char* qs = qwg + 2 * kQStep * at_step(step_seq);
+        sh0 = *reinterpret_cast<const uint4*>(qs + qoff);
+        sh1 = *reinterpret_cast<const uint4*>(qs + q32 + qoff);
+        sh2 = *reinterpret_cast<const uint4*>(qs + 2 * q32 + qoff);
+        sh3 = *reinterpret_cast<const uint4*>(qs + 3 * q32 + qoff);
         if (LO) {
-            sl0 = *reinterpret_cast<const uint4*>(Qt_lo + (int64_t)s_col0 * D + k0);
-            sl1 = *reinterpret_cast<const uint4*>(Qt_lo + (int64_t)(s_col0 + 64) * D + k0);
+            sl0 = *reinterpret_cast<const uint4*>(qs + lo_bytes + qoff);
+            sl1 = *reinterpret_cast<const uint4*>(qs + lo_bytes + q32 + qoff);
+            sl2 = *reinterpret_cast<const uint4*>(qs + lo_bytes + 2 * q32 + qoff);
+            sl3 = *reinterpret_cast<const uint4*>(qs + lo_bytes + 3 * q32 + qoff);
         }
     };
     auto stage_store = [&](int buf) {
-        *reinterpret_cast<uint4*>(&qs[buf][0][s_col0 * kQtRow + 8 * s_piece]) = sh0;
-        *reinterpret_cast<uint4*>(&qs[buf][0][(s_col0 + 64) * kQtRow + 8 * s_piece]) = sh1;
+        bf16_bits* q = qs_raw + buf * kBuf + s_col0 * kQtRow + 8 * s_piece;
+        *reinterpret_cast<uint4*>(q) = sh0;
+        *reinterpret_cast<uint4*>(q + 32 * kQtRow) = sh1;
+        *reinterpret_cast<uint4*>(q + 64 * kQtRow) = sh2;
+        *reinterpret_cast<uint4*>(q + 96 * kQtRow) = sh3;
         if (LO) {
-            *reinterpret_cast<uint4*>(&qs[buf][1][s_col0 * kQtRow + 8 * s_piece]) = sl0;
-            *reinterpret_cast<uint4*>(&qs[buf][1][(s_col0 + 64) * kQtRow + 8 * s_piece]) = sl1;
+            *reinterpret_cast<uint4*>(q + kHalf) = sl0;
+            *reinterpret_cast<uint4*>(q + kHalf + 32 * kQtRow) = sl1;
+            *reinterpret_cast<uint4*>(q + kHalf + 64 * kQtRow) = sl2;
+            *reinterpret_cast<uint4*>(q + kHalf + 96 * kQtRow) = sl3;
         }
     };
-    // rows past the end re-read the last row (clamped, never predicated); their results are not stored
-    auto load_a_next = [&](int step) {
-        const int k0 = k_begin + 32 * step + 8 * kq;
+    auto load_a = [&](auto set, int step_seq) {
+        constexpr int S = decltype(set)::value;
+        const char* xs = xwg + 2 * kQStep * at_step(step_seq);
 #pragma unroll
-        for (int rb = 0; rb < 4; ++rb) {
-            const int r = min(row0 + 16 * rb + n, N - 1);
-            a_nxt[rb] = *reinterpret_cast<const uint4*>(X + (int64_t)r * ldx + k0);
-        }
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+            for (int rb = 0; rb < 4; ++rb) a[S][h][rb] = *reinterpret_cast<const uint4*>(xs + 64 * h + xoff[rb]);
     };
-    stage_load(0);
-    load_a_next(0);
-    stage_store(0);
-#pragma unroll
-    for (int rb = 0; rb < 4; ++rb) a_cur[rb] = a_nxt[rb];
-    __syncthreads();
-    for (int step = 0; step < n_steps; ++step) {
-        const int buf = step & 1;
+    auto body = [&](auto ph, int step) {
+        constexpr int PH = decltype(ph)::value;
+        if (step >= n_steps) return;                                 // uniform over the workgroup
         const bool more = step + 1 < n_steps;
         if (more) {
             stage_load(step + 1);
-            load_a_next(step + 1);
+            load_a(phase_t<PH ^ 1>{}, step + 1);
         }
+        const bf16_bits* qb = qs_raw + PH * kBuf + n * kQtRow + 8 * kq;
 #pragma unroll
-        for (int cb = 0; cb < 8; ++cb) {
-            const bf16x8_t bh = __builtin_bit_cast(
-                bf16x8_t, *reinterpret_cast<const uint4*>(&qs[buf][0][(16 * cb + n) * kQtRow + 8 * kq]));
-            bf16x8_t bl = bh;
-            if (LO)
-                bl = __builtin_bit_cast(
-                    bf16x8_t, *reinterpret_cast<const uint4*>(&qs[buf][1][(16 * cb + n) * kQtRow + 8 * kq]));
+        for (int h = 0; h < 2; ++h)
 #pragma unroll
-            for (int rb = 0; rb < 4; ++rb) {
-                const bf16x8_t av = __builtin_bit_cast(bf16x8_t, a_cur[rb]);
-                acc[rb][cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, bh, acc[rb][cb], 0, 0, 0);
-                if (LO) acc[rb][cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, bl, acc[rb][cb], 0, 0, 0);
+            for (int cb = 0; cb < 8; ++cb) {
+                const bf16x8_t bh =
+                    __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(qb + 16 * cb * kQtRow + 32 * h));
+                bf16x8_t bl = bh;
+                if (LO)
+                    bl = __builtin_bit_cast(bf16x8_t,
+                                            *reinterpret_cast<const uint4*>(qb + kHalf + 16 * cb * kQtRow + 32 * h));
+#pragma unroll
+                for (int rb = 0; rb < 4; ++rb) {
+                    const bf16x8_t av = __builtin_bit_cast(bf16x8_t, a[PH][h][rb]);
+                    acc[rb][cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, bh, acc[rb][cb], 0, 0, 0);
+                    if (LO) acc[rb][cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, bl, acc[rb][cb], 0, 0, 0);
+                }
             }
-        }
-        if (more) stage_store(buf ^ 1);          // the other buffer: everyone left it at the last barrier
+        if (more) stage_store(PH ^ 1);           // the other buffer: everyone left it at the last barrier
         __syncthreads();
-#pragma unroll
-        for (int rb = 0; rb < 4; ++rb) a_cur[rb] = a_nxt[rb];
+    };
+    if (n_steps > 0) {
+        stage_load(0);
+        load_a(phase_t<0>{}, 0);
+        stage_store(0);
+    }
+    __syncthreads();
+    for (int s0 = 0; s0 < n_steps; s0 += 2) {
+        body(phase_t<0>{}, s0);
+        body(phase_t<1>{}, s0 + 1);
     }
     // accumulator lane: column 16 cb + n, rows 16 rb + 4 kq + v
     float* o = out + (int64_t)kc * N * kP;
@@ -140,44 +187,68 @@ __global__ __launch_bounds__(256) void sub_xq_mfma_kernel(const bf16_bits* __res
 }
 
 
-// Zh / Zl [N][128] bf16 halves of Z [N][128] fp32 (row-major, as the X^T Z kernel streams them).
-__global__ __launch_bounds__(256) void sub_z_split_kernel(const float* __restrict__ Z, int64_t total,
-                                                          bf16_bits* __restrict__ Zh, bf16_bits* __restrict__ Zl) {
-    const int64_t e = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
-    if (e >= total) return;
-    const float4 z = *reinterpret_cast<const float4*>(Z + e);
-    const float v[4] = {z.x, z.y, z.z, z.w};
-    uint32_t h[4], l[4];
+// Zt_hi / Zt_lo [128][n_pad] bf16 from Z [N][128] fp32: the transposed halves that the X^T Z kernel streams
+// (n_pad = N rounded up to 128; the tokens past N are written as zeros).  Tile: 64 tokens x 32 columns.
+template <bool LO>
+__global__ __launch_bounds__(256) void sub_z_split_kernel(const float* __restrict__ Z, int N, int64_t n_pad,
+                                                          bf16_bits* __restrict__ Zt_hi, bf16_bits* __restrict__ Zt_lo) {
+    __shared__ float tile[64][33];
+    const int t0 = blockIdx.x * 64, j0 = blockIdx.y * 32;
+    const int tid = threadIdx.x;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        h[i] = bf16_rne(v[i]);
-        l[i] = bf16_rne(v[i] - __uint_as_float(h[i] << 16));
+    for (int rep = 0; rep < 2; ++rep) {
+        const int r = (tid >> 3) + 32 * rep, q = tid & 7;
+        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (t0 + r < N) v = *reinterpret_cast<const float4*>(Z + (int64_t)(t0 + r) * kP + j0 + 4 * q);
+        tile[r][4 * q] = v.x;
+        tile[r][4 * q + 1] = v.y;
+        tile[r][4 * q + 2] = v.z;
+        tile[r][4 * q + 3] = v.w;
     }
-    *reinterpret_cast<uint2*>(Zh + e) = make_uint2(h[0] | (h[1] << 16), h[2] | (h[3] << 16));
-    *reinterpret_cast<uint2*>(Zl + e) = make_uint2(l[0] | (l[1] << 16), l[2] | (l[3] << 16));
+    __syncthreads();
+    const int col = tid >> 3, piece = tid & 7;                        // 8 tokens of one column: 16 bytes per half
+    uint32_t h[8], l[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const float v = tile[8 * piece + i][col];
+        h[i] = bf16_rne(v);
+        l[i] = bf16_rne(v - __uint_as_float(h[i] << 16));
+    }
+    const int64_t at = (int64_t)(j0 + col) * n_pad + t0 + 8 * piece;
+    *reinterpret_cast<uint4*>(Zt_hi + at) =
+        make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
+    if (LO)
+        *reinterpret_cast<uint4*>(Zt_lo + at) =
+            make_uint4(l[0] | (l[1] << 16), l[2] | (l[3] << 16), l[4] | (l[5] << 16), l[6] | (l[7] << 16));
 }
 
 // out[tc][d][j] = sum over the token chunk of X[t][d] (Zh[t][j] + Zl[t][j]) for the 128 features d of
-// one slab.  The contraction runs over tokens, the slow index of both operands, so operands are
-// transposed in registers: a lane loads 8 tokens x 8 features (16 bytes per token) and byte
-// permutes turn them into 8 operands "feature 8 i + c over 8 tokens".  The four waves of a
-// workgroup share one slab of X: per round of 128 tokens every wave loads and transposes one step
-// of 32 tokens and leaves its 8 operands in LDS (double buffered, one barrier per round); then every
-// wave multiplies all four steps with its own 32 columns of Z, whose operands (2 columns per lane)
-// it builds itself.  Accumulator block (c, b): feature 8 i + c, column 32 w + 2 n + b.
+// one slab.  The contraction runs over tokens, the slow index of X, so X is transposed in registers: a
+// lane loads 8 tokens x 8 features (16 bytes per token) and byte permutes turn them into 8 operands
+// "feature 8 i + c over 8 tokens".  The four waves of a workgroup share one slab of X: per round of 128
+// tokens every wave loads and transposes one step of 32 tokens and leaves its 8 operands in LDS (double
+// buffered, one barrier per round); then every wave multiplies all four steps with its own 32 columns of
+// Z, which arrive transposed (Zt [128][n_pad]: 16 bytes = 8 tokens of one column = one operand), a whole
+// round ahead.  Accumulator block (c, b): feature 8 i + c, column 32 w + 16 b + n.
+// Workgroups that share a token chunk are placed on one XCD (the hardware deals consecutive workgroup ids
+// round-robin over the 8 XCDs), so each L2 fetches only its own chunks of Z.
 template <bool LO>
 __global__ __launch_bounds__(256) void sub_xtz_mfma_kernel(const bf16_bits* __restrict__ X, int64_t ldx,
                                                            const bf16_bits* __restrict__ Zh,
-                                                           const bf16_bits* __restrict__ Zl, int N, int D, int t_chunk,
-                                                           float* __restrict__ out) {
+                                                           const bf16_bits* __restrict__ Zl, int64_t n_pad, int N, int D,
+                                                           int n_slabs, int t_chunk, float* __restrict__ out) {
     __shared__ __align__(16) uint4 xs[2][4][8][64];                   // [buffer][step][operand][lane]: 64 KB
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int m = lane & 15, g = lane >> 4;
-    const int slab = blockIdx.x, tc = blockIdx.y;
+    int vid = blockIdx.x;
+    const int total = gridDim.x;
+    if ((total & 7) == 0) vid = (vid & 7) * (total >> 3) + (vid >> 3);
+    const int slab = vid % n_slabs, tc = vid / n_slabs;
     const int t_begin = tc * t_chunk, t_end = min(N, t_begin + t_chunk);
     const int n_rounds = (t_end - t_begin + 127) >> 7;
     const bf16_bits* xbase = X + (int64_t)slab * 128 + 8 * m;
-    const int col0 = 32 * wv + 2 * m;                                // this lane's two columns of Z
+    const bf16_bits* zh_base = Zh + (int64_t)(32 * wv + m) * n_pad + 8 * g;    // column 32 w + n, then + 16 columns
+    const bf16_bits* zl_base = Zl + (int64_t)(32 * wv + m) * n_pad + 8 * g;
     f32x4_t acc[8][2];
 #pragma unroll
     for (int c = 0; c < 8; ++c) {
@@ -185,6 +256,8 @@ __global__ __launch_bounds__(256) void sub_xtz_mfma_kernel(const bf16_bits* __re
         acc[c][1] = f32x4_t{0.f, 0.f, 0.f, 0.f};
     }
     uint4 x0, x1, x2, x3, x4, x5, x6, x7;                            // this wave's step of the next round (named: no scratch)
+    uint4 zc[4][2], zn[4][2];                                        // Z operands [step][column block]: this round, the next
+    uint4 lc[4][2], ln[4][2];                                        // their low halves
     // tokens past the end contribute nothing: their X rows are taken as zero
     auto row_or_zero = [&](int t) {
         uint4 v = make_uint4(0u, 0u, 0u, 0u);
@@ -201,6 +274,17 @@ __global__ __launch_bounds__(256) void sub_xtz_mfma_kernel(const bf16_bits* __re
         x5 = row_or_zero(t0 + 5);
         x6 = row_or_zero(t0 + 6);
         x7 = row_or_zero(t0 + 7);
+    };
+    // t_begin and the rounds are multiples of 128 and n_pad covers whole rounds: every load stays inside Zt
+    auto load_z = [&](uint4 (&zd)[4][2], uint4 (&ld)[4][2], int round) {
+        const int64_t t0 = t_begin + 128 * round;
+#pragma unroll
+        for (int st = 0; st < 4; ++st)
+#pragma unroll
+            for (int b = 0; b < 2; ++b) {
+                zd[st][b] = *reinterpret_cast<const uint4*>(zh_base + (int64_t)16 * b * n_pad + t0 + 32 * st);
+                if (LO) ld[st][b] = *reinterpret_cast<const uint4*>(zl_base + (int64_t)16 * b * n_pad + t0 + 32 * st);
+            }
     };
     // operand c, dword j = feature 8m + c of tokens (2j, 2j+1) of this lane's 8 tokens
     auto store_x = [&](int buf) {
@@ -219,38 +303,26 @@ __global__ __launch_bounds__(256) void sub_xtz_mfma_kernel(const bf16_bits* __re
 #pragma unroll
         for (int c = 0; c < 8; ++c) xs[buf][wv][c][lane] = make_uint4(r[c][0], r[c][1], r[c][2], r[c][3]);
     };
-    load_x(0);
-    store_x(0);
+    if (n_rounds > 0) {
+        load_x(0);
+        load_z(zc, lc, 0);
+        store_x(0);
+    }
     __syncthreads();
     for (int round = 0; round < n_rounds; ++round) {
         const int buf = round & 1;
         const bool more = round + 1 < n_rounds;
-        if (more) load_x(round + 1);
+        if (more) {
+            load_x(round + 1);
+            load_z(zn, ln, round + 1);
+        }
 #pragma unroll
         for (int st = 0; st < 4; ++st) {
-            // Z operands of this step: tokens t0 + e, columns col0, col0 + 1 (one dword per token and half)
-            const int t0 = t_begin + 128 * round + 32 * st + 8 * g;
-            uint32_t zh[8], zl[8];
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const int t = min(t0 + e, N - 1);                    // clamped: X is zero there anyway
-                zh[e] = *reinterpret_cast<const uint32_t*>(Zh + (int64_t)t * kP + col0);
-                zl[e] = LO ? *reinterpret_cast<const uint32_t*>(Zl + (int64_t)t * kP + col0) : 0u;
-            }
-            bf16x8_t bh0, bh1, bl0, bl1;
-            {
-                uint32_t p0[4], p1[4], q0[4], q1[4];
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    p0[j] = __builtin_amdgcn_perm(zh[2 * j + 1], zh[2 * j], 0x05040100u);
-                    p1[j] = __builtin_amdgcn_perm(zh[2 * j + 1], zh[2 * j], 0x07060302u);
-                    q0[j] = __builtin_amdgcn_perm(zl[2 * j + 1], zl[2 * j], 0x05040100u);
-                    q1[j] = __builtin_amdgcn_perm(zl[2 * j + 1], zl[2 * j], 0x07060302u);
-                }
-                bh0 = __builtin_bit_cast(bf16x8_t, make_uint4(p0[0], p0[1], p0[2], p0[3]));
-                bh1 = __builtin_bit_cast(bf16x8_t, make_uint4(p1[0], p1[1], p1[2], p1[3]));
-                bl0 = __builtin_bit_cast(bf16x8_t, make_uint4(q0[0], q0[1], q0[2], q0[3]));
-                bl1 = __builtin_bit_cast(bf16x8_t, make_uint4(q1[0], q1[1], q1[2], q1[3]));
+            const bf16x8_t bh0 = __builtin_bit_cast(bf16x8_t, zc[st][0]), bh1 = __builtin_bit_cast(bf16x8_t, zc[st][1]);
+            bf16x8_t bl0 = bh0, bl1 = bh1;
+            if (LO) {
+                bl0 = __builtin_bit_cast(bf16x8_t, lc[st][0]);
+                bl1 = __builtin_bit_cast(bf16x8_t, lc[st][1]);
             }
 #pragma unroll
             for (int c = 0; c < 8; ++c) {
@@ -261,17 +333,27 @@ __global__ __launch_bounds__(256) void sub_xtz_mfma_kernel(const bf16_bits* __re
                 if (LO) acc[c][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, bl1, acc[c][1], 0, 0, 0);
             }
         }
-        if (more) store_x(buf ^ 1);
+        if (more) {
+            store_x(buf ^ 1);
+#pragma unroll
+            for (int st = 0; st < 4; ++st)
+#pragma unroll
+                for (int b = 0; b < 2; ++b) {
+                    zc[st][b] = zn[st][b];
+                    if (LO) lc[st][b] = ln[st][b];
+                }
+        }
         __syncthreads();
     }
     // accumulator lane: column index n = lane % 16, rows i = 4 (lane / 16) + v
-    float* o = out + ((int64_t)tc * D + (int64_t)slab * 128) * kP + 32 * wv;
+    float* o = out + ((int64_t)tc * D + (int64_t)slab * 128) * kP + 32 * wv + m;
 #pragma unroll
     for (int c = 0; c < 8; ++c)
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
             const int feat = 8 * (4 * g + v) + c;
-            *reinterpret_cast<float2*>(o + (int64_t)feat * kP + 2 * m) = make_float2(acc[c][0][v], acc[c][1][v]);
+            o[(int64_t)feat * kP] = acc[c][0][v];
+            o[(int64_t)feat * kP + 16] = acc[c][1][v];
         }
 }
 
@@ -294,12 +376,14 @@ __global__ __launch_bounds__(256) void sub_sum_parts_kernel(const float* __restr
 hipError_t launch_xq_mfma(const bf16_bits* X, int64_t ldx, const float* Q, int N, int D, bf16_bits* Qt_hi,
                           bf16_bits* Qt_lo, int n_split, float* Zpart, float* Z, hipStream_t s, bool precise) {
     sub_qt_split_kernel<<<dim3((unsigned)(D / 32), kP / 32), dim3(256), 0, s>>>(Q, D, Qt_hi, Qt_lo);
-    const int k_chunk = ((D + n_split - 1) / n_split + 31) / 32 * 32;
+    const int k_chunk = ((D + n_split - 1) / n_split + kQStep - 1) / kQStep * kQStep;
     const int splits = (D + k_chunk - 1) / k_chunk;
     float* dst = splits == 1 ? Z : Zpart;
     const dim3 grid((unsigned)((N + 255) / 256), (unsigned)splits);
-    if (precise) sub_xq_mfma_kernel<true><<<grid, dim3(256), 0, s>>>(X, ldx, Qt_hi, Qt_lo, N, D, k_chunk, dst);
-    else sub_xq_mfma_kernel<false><<<grid, dim3(256), 0, s>>>(X, ldx, Qt_hi, Qt_lo, N, D, k_chunk, dst);
+    if (precise)
+        sub_xq_mfma_kernel<true><<<grid, dim3(256), xq_lds_bytes<true>(), s>>>(X, ldx, Qt_hi, Qt_lo, N, D, k_chunk, dst);
+    else
+        sub_xq_mfma_kernel<false><<<grid, dim3(256), xq_lds_bytes<false>(), s>>>(X, ldx, Qt_hi, Qt_lo, N, D, k_chunk, dst);
     if (splits > 1) {
         const int64_t total = (int64_t)N * kP;
         sub_sum_parts_kernel<<<dim3((unsigned)((total / 4 + 255) / 256)), dim3(256), 0, s>>>(Zpart, splits, total, Z);
@@ -307,15 +391,26 @@ hipError_t launch_xq_mfma(const bf16_bits* X, int64_t ldx, const float* Q, int N
     return hipGetLastError();
 }
 
-// Wpart[tc][D][128] = partial X^T Z over token chunks; Zh / Zl are scratch for the two halves of Z.
+// Wpart[tc][D][128] = partial X^T Z over token chunks (t_chunk a multiple of 128); Zh / Zl are scratch for the
+// two transposed halves of Z, [128][n_pad] bf16 each with n_pad = N rounded up to 128.
 hipError_t launch_xtz_mfma(const bf16_bits* X, int64_t ldx, const float* Z, int N, int D, bf16_bits* Zh, bf16_bits* Zl,
                            int t_chunk, int n_tchunks, float* Wpart, hipStream_t s, bool precise) {
-    const int64_t total = (int64_t)N * kP;
-    sub_z_split_kernel<<<dim3((unsigned)((total / 4 + 255) / 256)), dim3(256), 0, s>>>(Z, total, Zh, Zl);
-    const dim3 grid((unsigned)(D / 128), (unsigned)n_tchunks);
-    if (precise) sub_xtz_mfma_kernel<true><<<grid, dim3(256), 0, s>>>(X, ldx, Zh, Zl, N, D, t_chunk, Wpart);
-    else sub_xtz_mfma_kernel<false><<<grid, dim3(256), 0, s>>>(X, ldx, Zh, Zl, N, D, t_chunk, Wpart);
+    const int64_t n_pad = ((int64_t)N + 127) / 128 * 128;
+    const dim3 sgrid((unsigned)(n_pad / 64), kP / 32);
+    const int n_slabs = D / 128;
+    const dim3 grid((unsigned)(n_slabs * n_tchunks));
+    if (precise) {
+        sub_z_split_kernel<true><<<sgrid, dim3(256), 0, s>>>(Z, N, n_pad, Zh, Zl);
+        sub_xtz_mfma_kernel<true><<<grid, dim3(256), 0, s>>>(X, ldx, Zh, Zl, n_pad, N, D, n_slabs, t_chunk, Wpart);
+    } else {
+        sub_z_split_kernel<false><<<sgrid, dim3(256), 0, s>>>(Z, N, n_pad, Zh, Zl);
+        sub_xtz_mfma_kernel<false><<<grid, dim3(256), 0, s>>>(X, ldx, Zh, Zl, n_pad, N, D, n_slabs, t_chunk, Wpart);
+    }
     return hipGetLastError();
+}
+
+hipError_t init_subspace_mfma_kernels() {
+    return allow_dynamic_lds(reinterpret_cast<const void*>(sub_xq_mfma_kernel<true>), xq_lds_bytes<true>());
 }
 
 }  // namespace uncomp
