@@ -44,37 +44,52 @@ __global__ __launch_bounds__(256) void sub_start_kernel(float* __restrict__ W, i
 }
 
 // Column sums and sums of squares of X over a chunk of tokens, in fp64: part[chunk][2][D].
-// A thread owns 8 consecutive columns (D is a multiple of 128) and reads them with load8.
+// A workgroup covers 512 columns: thread = 8 consecutive columns (read with load8) x one of four row phases,
+// eight rows in flight per thread; the four phases are added up in LDS in a fixed order.
 template <typename T>
 __global__ __launch_bounds__(256) void sub_colstats_kernel(const T* __restrict__ X, int N, int D, int64_t ldx,
                                                            int chunk, double* __restrict__ part) {
-    const int d = (blockIdx.x * 256 + threadIdx.x) * 8;
+    __shared__ double red[3][16][64];
+    const int cg = threadIdx.x & 63, ph = threadIdx.x >> 6;
+    const int d = (blockIdx.x * 64 + cg) * 8;
     const int c = blockIdx.y;
-    if (d >= D) return;
+    const bool live = d < D;
     const int t0 = c * chunk, t1 = min(N, t0 + chunk);
     double s[8], q[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) s[i] = q[i] = 0.0;
-    for (int t = t0; t < t1; t += 4) {                              // four rows in flight
-        float v[4][8];
+    if (live) {
+        for (int t = t0 + ph; t < t1; t += 32) {
+            float v[8][8];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) load8(X + (int64_t)min(t + u, t1 - 1) * ldx + d, v[u]);
+            for (int u = 0; u < 8; ++u) load8(X + (int64_t)min(t + 4 * u, t1 - 1) * ldx + d, v[u]);
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            if (t + u < t1) {
+            for (int u = 0; u < 8; ++u) {
+                if (t + 4 * u < t1) {
 #pragma unroll
-                for (int i = 0; i < 8; ++i) {
-                    const double x = (double)v[u][i];
-                    s[i] += x;
-                    q[i] = fma(x, x, q[i]);
+                    for (int i = 0; i < 8; ++i) {
+                        const double x = (double)v[u][i];
+                        s[i] += x;
+                        q[i] = fma(x, x, q[i]);
+                    }
                 }
             }
         }
     }
+    if (ph > 0) {
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        part[((int64_t)c * 2 + 0) * D + d + i] = s[i];
-        part[((int64_t)c * 2 + 1) * D + d + i] = q[i];
+        for (int i = 0; i < 8; ++i) {
+            red[ph - 1][i][cg] = s[i];
+            red[ph - 1][8 + i][cg] = q[i];
+        }
+    }
+    __syncthreads();
+    if (ph == 0 && live) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            part[((int64_t)c * 2 + 0) * D + d + i] = ((s[i] + red[0][i][cg]) + red[1][i][cg]) + red[2][i][cg];
+            part[((int64_t)c * 2 + 1) * D + d + i] = ((q[i] + red[0][8 + i][cg]) + red[1][8 + i][cg]) + red[2][8 + i][cg];
+        }
     }
 }
 
@@ -87,6 +102,7 @@ __global__ __launch_bounds__(256) void sub_colstats_finish_kernel(const double* 
     double tc = 0.0, tu = 0.0;
     if (d < D) {
         double a = 0.0, q = 0.0;
+#pragma unroll 8
         for (int c = 0; c < n_chunks; ++c) {
             a += part[((int64_t)c * 2 + 0) * D + d];
             q += part[((int64_t)c * 2 + 1) * D + d];
@@ -613,7 +629,7 @@ static hipError_t run_matrix_entropy(const T* X, int n_mat, int N, int D, int64_
     for (int m = 0; m < n_mat; ++m) {
         const T* Xm = X + (int64_t)m * mat_stride;
         env.begin("matrix_colstats");
-        sub_colstats_kernel<T><<<dim3((unsigned)((D / 8 + 255) / 256), (unsigned)p.stat_chunks), dim3(256), 0, s>>>(
+        sub_colstats_kernel<T><<<dim3((unsigned)((D / 8 + 63) / 64), (unsigned)p.stat_chunks), dim3(256), 0, s>>>(
             Xm, N, D, ldx, p.stat_chunk, statpart);
         sub_colstats_finish_kernel<<<dim3((unsigned)((D + 255) / 256)), dim3(256), 0, s>>>(statpart, p.stat_chunks, D, N, sv,
                                                                                           trace + 2);
