@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libuncomp.so")
-SOURCES = ["api.hip", "gram.hip", "jacobi.hip", "tridiag.hip", "budgets.hip", "score.hip", "select.hip", "decode.hip", "hidden.hip", "prepare.hip", "subspace.hip", "subspace_mfma.hip", "peaks.hip", "noalloc.hip"]
+SOURCES = ["api.hip", "gram.hip", "jacobi.hip", "tridiag.hip", "budgets.hip", "score.hip", "select.hip", "select_wide.hip", "decode.hip", "hidden.hip", "prepare.hip", "subspace.hip", "subspace_mfma.hip", "peaks.hip", "noalloc.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",   # no packed-fp32 VALU forms

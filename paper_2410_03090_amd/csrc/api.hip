@@ -335,7 +335,9 @@ namespace {
 struct HiddenPlan {
     ScorePlan sp;
     LastTokenPlan lt;            // the bf16 path's regions start where the general path's scoring region does
-    size_t score_off, sum_off, bytes;
+    SelectWidePlan sw;
+    bool wide_select;            // few rows, long ones: the selection is split over many workgroups
+    size_t score_off, sum_off, sw_off, bytes;
 };
 HiddenPlan plan_hidden(int B, int H, int G, int N, int w) {
     HiddenPlan p;
@@ -344,7 +346,10 @@ HiddenPlan plan_hidden(int B, int H, int G, int N, int w) {
     const size_t scoring = p.sp.bytes > p.lt.bytes ? p.sp.bytes : p.lt.bytes;
     p.score_off = align_up(kBudgetScratch + scoring, 256);
     p.sum_off = align_up(p.score_off + (size_t)B * H * (N - 1) * sizeof(float), 256);
-    p.bytes = align_up(p.sum_off + (size_t)B * (N - w) * sizeof(float), 256);
+    p.sw_off = align_up(p.sum_off + (size_t)B * (N - w) * sizeof(float), 256);
+    p.sw = plan_select_wide(B, N, w);
+    p.wide_select = B <= 32 && N - w >= 32768;
+    p.bytes = p.sw_off + (p.wide_select ? p.sw.bytes : 0);
     return p;
 }
 }  // namespace
@@ -436,7 +441,12 @@ uncomp_status uncomp_hidden_evict(uncomp_ctx* ctx, const void* q_last, const voi
                                 env);
         if (e == hipSuccess) e = launch_head_sum(score, B, H, N - 1, N - w, sum, env);
     }
-    if (e == hipSuccess) e = launch_select_rows(sum, n_keep, 0, B, N, w, cap, idx_out, len_out, env);
+    if (e == hipSuccess) {
+        if (p.wide_select)
+            e = launch_select_rows_wide(sum, n_keep, 0, B, N, w, cap, p.sw, ctx->ws + p.sw_off, idx_out, len_out, env);
+        else
+            e = launch_select_rows(sum, n_keep, 0, B, N, w, cap, idx_out, len_out, env);
+    }
     if (e == hipSuccess && Hs != nullptr)
         e = launch_gather_rows(Hs, idx_out, len_out, B, cap, N, Dm * esz, hs_strides[0] * esz, hs_strides[1] * esz,
                                Hs_out, env);

@@ -127,6 +127,15 @@ hipError_t launch_select_gather(const float* score, const int32_t* budget, const
                                 const int64_t ks[3], int cap, void* K_out, void* V_out,
                                 int32_t* idx_out, int32_t* len_out, const Env& env,
                                 const uint32_t* tile_range = nullptr, int n_range_tiles = 0, int D = kD);
+// The same selection for a few long rows, each split over n_wg workgroups (select_wide.hip); ws: p.bytes.
+struct SelectWidePlan {
+    int n_wg;            // workgroups (chunks of 2048 positions) per row
+    size_t bytes;
+};
+SelectWidePlan plan_select_wide(int n_groups, int N, int w);
+hipError_t launch_select_rows_wide(const float* score, const int32_t* budget, int budget_stride, int n_groups, int N,
+                                   int w, int cap, const SelectWidePlan& p, char* ws, int32_t* idx_out, int32_t* len_out,
+                                   const Env& env);
 hipError_t launch_select_rows(const float* score, const int32_t* budget, int budget_stride, int n_groups,
                               int N, int w, int cap, int32_t* idx_out, int32_t* len_out, const Env& env);
 hipError_t launch_gather_rows(const void* src, const int32_t* idx, const int32_t* len, int n_groups, int cap,

@@ -107,6 +107,36 @@ def test_hidden_evict_full_size_llama3_8b_128k(ctx):
     assert torch.equal(Ho[0].view(torch.int16), Hs[0, idx[0, :n_keep].long()].view(torch.int16))
 
 
+@pytest.mark.parametrize("N,w", [(40007, 4), (36872, 8), (75000, 1)])
+def test_hidden_evict_long_rows_split_over_workgroups(ctx, N, w):
+    """Rows of 32768 scores or more are selected by many workgroups per row.  The keys are drawn from 40
+    distinct vectors, so thousands of scores are exactly equal and the threshold falls inside a run of
+    ties: the kept positions must be those of the one-workgroup selection on the same scores (the earliest
+    positions among equals), and agree with the oracle up to its tie band."""
+    B, H, G = 2, 1, 2
+    g = torch.Generator().manual_seed(N)
+    pool = torch.randn(40, D, generator=g) * 1.2
+    pick = torch.randint(0, 40, (B, H, N), generator=g)
+    K = pool[pick].to(torch.float32)
+    K[:, :, ::7] += 0.05 * torch.randn(B, H, (N + 6) // 7, D, generator=g)            # some distinct scores in between
+    q = (torch.randn(B, H * G, D, generator=g) * 1.2).to(torch.float32)
+    P = N - w
+    for n_keep in (0, w, w + 1, 17, N // 3, N - 5000, N - 1, N, N + 3):
+        nk = torch.tensor([n_keep], dtype=torch.int32, device=DEV)
+        _, idx, ln, score = ctx.hidden_evict(q.to(DEV), K.to(DEV), G, nk, w, None, cap=N, want_score=True)
+        bud = torch.full((B, 1), n_keep, dtype=torch.int32, device=DEV)
+        _, _, idx_one, ln_one = ctx.select_gather(score.view(B, 1, P).contiguous(), bud, None, None, w, cap=N, N=N)
+        torch.cuda.synchronize()
+        assert torch.equal(ln.view(-1), ln_one.view(-1))
+        assert torch.equal(idx.view(B, -1), idx_one.view(B, -1)), f"n_keep {n_keep}"
+    _, idx_ref, score_ref = O.hidden_evict(to_f64(q), to_f64(K), np.zeros((B, N, 1)), N // 3, w, G)
+    nk = torch.tensor([N // 3], dtype=torch.int32, device=DEV)
+    _, idx, ln, _ = ctx.hidden_evict(q.to(DEV), K.to(DEV), G, nk, w, None, cap=N)
+    torch.cuda.synchronize()
+    for b in range(B):
+        check_index_sets(idx.cpu().numpy()[b], int(ln[b]), idx_ref[b], N // 3, score_ref[b, :P], w)
+
+
 def test_hidden_evict_argument_errors(ctx):
     from paper_2410_03090_amd import binding
     q, K, Hs = _inputs(1, 2, 2, 100, 64, torch.bfloat16, seed=1)
