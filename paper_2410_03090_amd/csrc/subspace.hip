@@ -373,10 +373,13 @@ __device__ __forceinline__ double lane_value(double x, int src) {
 // per block instead of two per column:
 //   factor   the 16 x 16 diagonal block in the registers of one wave (lane = row, values of other
 //            rows by v_readlane), the rows below it by forward substitution (one thread per row),
-//            the trailing triangle by a rank-16 update;
+//            the trailing triangle by a rank-16 update in 16 x 16 tiles (v_mfma_f64_16x16x4_f64);
 //   invert   X = L^-1 block row by block row: the part that earlier block rows determine is a
-//            product of known blocks (all threads), the 16 x 16 rest a forward substitution (one
+//            product of known blocks (same tiles), the 16 x 16 rest a forward substitution (one
 //            thread per column).  X[k][c], k > c, lives at G[c][k] in the unused upper triangle.
+// Phase times of one call (100 MHz wall clock, warm input): diagonal blocks 25 us, rows below 8,
+// trailing tiles 9, products of the inverse 9, substitutions of the inverse 19: 71 us, of which
+// the two tiled parts took 48 before they ran on the matrix cores.
 __global__ __launch_bounds__(256) void sub_chol_kernel(const double* __restrict__ gsum, float* __restrict__ Rinv) {
     extern __shared__ __align__(16) double G[];                // [128][129]
     __shared__ double dinv[kP];
@@ -434,13 +437,16 @@ __global__ __launch_bounds__(256) void sub_chol_kernel(const double* __restrict_
             // rows below the block: L[r][j0 + j] = (G[r][j0 + j] - sum_{k<j} L[r][j0 + k] L[j0 + j][j0 + k]) / L[j0 + j][j0 + j]
             const int r = j0 + B + tid;
             if (r < kP) {
+                // column by column: once l[j] is known, the entries to its right take their updates, which do not
+                // depend on one another (the chain through the row is 16 multiplications long, not 120 FMAs)
                 double l[B];
 #pragma unroll
-                for (int j = 0; j < B; ++j) {
-                    double acc = G[r * LD + j0 + j];
+                for (int j = 0; j < B; ++j) l[j] = G[r * LD + j0 + j];
 #pragma unroll
-                    for (int k = 0; k < j; ++k) acc -= l[k] * G[(j0 + j) * LD + j0 + k];
-                    l[j] = acc * dinv[j0 + j];
+                for (int j = 0; j < B; ++j) {
+                    l[j] *= dinv[j0 + j];
+#pragma unroll
+                    for (int k = j + 1; k < B; ++k) l[k] = fma(-l[j], G[(j0 + k) * LD + j0 + j], l[k]);
                 }
 #pragma unroll
                 for (int j = 0; j < B; ++j) G[r * LD + j0 + j] = l[j];
@@ -448,18 +454,31 @@ __global__ __launch_bounds__(256) void sub_chol_kernel(const double* __restrict_
         }
         __syncthreads();
         {
-            // trailing lower triangle: G[i][k] -= sum_j L[i][j0 + j] L[k][j0 + j], j0 + B <= k <= i
-            const int ti = tid >> 4, tk = tid & 15;
-            for (int i = j0 + B + ti; i < kP; i += 16) {
-                double li[B];
-#pragma unroll
-                for (int j = 0; j < B; ++j) li[j] = G[i * LD + j0 + j];
-                for (int k = j0 + B + tk; k <= i; k += 16) {
-                    double acc = 0.0;
-#pragma unroll
-                    for (int j = 0; j < B; ++j) acc = fma(li[j], G[k * LD + j0 + j], acc);
-                    G[i * LD + k] -= acc;
+            // trailing lower triangle by 16 x 16 tiles on the fp64 matrix cores, tiles dealt to the waves in turn:
+            // tile (I, K), p < K <= I, -= L[I][p] L[K][p]^T.  Operand lane (c, kk) holds row c of its factor at
+            // column 4 s + kk of the panel; result register v is row 4 v + kk, column c.  Diagonal tiles are
+            // computed whole: what lands above the diagonal is not read by the factorisation.
+            const int m = NB - 1 - p;
+            const int n_tiles = m * (m + 1) / 2;
+            const int c = lane & 15, kk = lane >> 4;
+            for (int t = wv; t < n_tiles; t += 4) {
+                int ti = 0, rem = t;
+                while (rem > ti) {                                   // t = ti (ti + 1) / 2 + tk, tk <= ti
+                    rem -= ti + 1;
+                    ++ti;
                 }
+                const int r0 = B * (p + 1 + ti), c0 = B * (p + 1 + rem);
+                f64x4_t acc;
+#pragma unroll
+                for (int v = 0; v < 4; ++v) acc[v] = G[(r0 + 4 * v + kk) * LD + c0 + c];
+#pragma unroll
+                for (int sx = 0; sx < 4; ++sx) {
+                    const double av = -G[(r0 + c) * LD + j0 + 4 * sx + kk];
+                    const double bv = G[(c0 + c) * LD + j0 + 4 * sx + kk];
+                    acc = __builtin_amdgcn_mfma_f64_16x16x4f64(av, bv, acc, 0, 0, 0);
+                }
+#pragma unroll
+                for (int v = 0; v < 4; ++v) G[(r0 + 4 * v + kk) * LD + c0 + c] = acc[v];
             }
         }
         __syncthreads();
@@ -467,44 +486,54 @@ __global__ __launch_bounds__(256) void sub_chol_kernel(const double* __restrict_
     // X = L^-1, block row I at a time.  X[k][c] (k > c) is kept at G[c][k]; X[c][c] = dinv[c].
     for (int I = 0; I < NB; ++I) {
         const int i0 = B * I;
-        // what the earlier block rows contribute: S[i][c] = -sum_{k=c}^{i0-1} L[i][k] X[k][c], c < i0 <= i; parked at G[c][i]
-        for (int e = tid; e < B * i0; e += 256) {
-            const int c = e / B, i = i0 + e % B;
-            double acc = -G[i * LD + c] * dinv[c], acc1 = 0.0, acc2 = 0.0, acc3 = 0.0;
-            int k = c + 1;
-            for (; k + 3 < i0; k += 4) {                             // four independent chains hide the LDS latency
-                acc = fma(-G[i * LD + k], G[c * LD + k], acc);
-                acc1 = fma(-G[i * LD + k + 1], G[c * LD + k + 1], acc1);
-                acc2 = fma(-G[i * LD + k + 2], G[c * LD + k + 2], acc2);
-                acc3 = fma(-G[i * LD + k + 3], G[c * LD + k + 3], acc3);
+        // what the earlier block rows contribute: S[i][c] = -sum_{k=c}^{i0-1} L[i][k] X[k][c], c < i0 <= i; parked at G[c][i].
+        // By tiles on the fp64 matrix cores: S(I, C) = -sum_{K=C}^{I-1} L(I, K) X(K, C); wave w takes the column
+        // tiles C = w, w + 4.  X(K, C) sits transposed in the upper triangle, so both operands are read along rows
+        // of G; the diagonal tile X(C, C) is lower triangular with 1 / L[c][c] on its diagonal.
+        {
+            const int c = lane & 15, kk = lane >> 4;
+            for (int C = wv; C < I; C += 4) {
+                f64x4_t acc = {0.0, 0.0, 0.0, 0.0};
+                for (int K = C; K < I; ++K) {
+#pragma unroll
+                    for (int sx = 0; sx < 4; ++sx) {
+                        const int k = 4 * sx + kk;                   // row of X / column of L inside tile K
+                        const double av = -G[(i0 + c) * LD + B * K + k];
+                        double bv = G[(B * C + c) * LD + B * K + k];
+                        if (K == C) bv = k > c ? bv : (k == c ? dinv[B * C + c] : 0.0);
+                        acc = __builtin_amdgcn_mfma_f64_16x16x4f64(av, bv, acc, 0, 0, 0);
+                    }
+                }
+#pragma unroll
+                for (int v = 0; v < 4; ++v) G[(B * C + c) * LD + i0 + 4 * v + kk] = acc[v];
             }
-            for (; k < i0; ++k) acc = fma(-G[i * LD + k], G[c * LD + k], acc);
-            G[c * LD + i] = (acc + acc1) + (acc2 + acc3);
         }
         __syncthreads();
         // the block itself: x_i = (S_i - sum_{k = max(i0, c)}^{i-1} L[i][k] x_k) / L[i][i], column c by thread c
-        if (tid >= i0 + B && tid < kP) {
-#pragma unroll
-            for (int ii = 0; ii < B; ++ii) Rinv[(int64_t)tid * kP + i0 + ii] = 0.f;      // rows above column tid
-        } else if (tid < i0 + B) {
+        if (tid < i0 + B) {
             const int c = tid;
-            double x[B];
+            double x[B];                                     // right-hand side, then the solution (same short chain as above)
+#pragma unroll
+            for (int ii = 0; ii < B; ++ii) x[ii] = c < i0 ? G[c * LD + i0 + ii] : (i0 + ii == c ? 1.0 : 0.0);
 #pragma unroll
             for (int ii = 0; ii < B; ++ii) {
-                const int i = i0 + ii;
-                double acc = c < i0 ? G[c * LD + i] : (i == c ? 1.0 : 0.0);
+                x[ii] = i0 + ii < c ? 0.0 : x[ii] * dinv[i0 + ii];                              // 0 above column c
 #pragma unroll
-                for (int kk = 0; kk < ii; ++kk) acc = fma(-G[i * LD + i0 + kk], x[kk], acc);     // x[kk] is 0 above column c
-                x[ii] = i < c ? 0.0 : acc * dinv[i];
+                for (int jj = ii + 1; jj < B; ++jj) x[jj] = fma(-G[(i0 + jj) * LD + i0 + ii], x[ii], x[jj]);
             }
 #pragma unroll
             for (int ii = 0; ii < B; ++ii) {
                 const int i = i0 + ii;
                 if (i > c) G[c * LD + i] = x[ii];
-                Rinv[(int64_t)c * kP + i] = (float)x[ii];      // Rinv = (L^-1)^T: Rinv[c][i] = X[i][c], zero for i < c
             }
         }
         __syncthreads();
+    }
+    // Rinv = (L^-1)^T: Rinv[c][i] = X[i][c], zero for i < c.  Written once, in rows, after the loop: a store to
+    // global memory inside it would be waited for at every workgroup barrier.
+    for (int e = tid; e < kP * kP; e += 256) {
+        const int c = e >> 7, i = e & (kP - 1);
+        Rinv[e] = i > c ? (float)G[c * LD + i] : (i == c ? (float)dinv[c] : 0.f);
     }
 }
 
