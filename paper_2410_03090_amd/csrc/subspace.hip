@@ -374,12 +374,12 @@ __device__ __forceinline__ double lane_value(double x, int src) {
 //   factor   the 16 x 16 diagonal block in the registers of one wave (lane = row, values of other
 //            rows by v_readlane), the rows below it by forward substitution (one thread per row),
 //            the trailing triangle by a rank-16 update in 16 x 16 tiles (v_mfma_f64_16x16x4_f64);
-//   invert   X = L^-1 block row by block row: the part that earlier block rows determine is a
-//            product of known blocks (same tiles), the 16 x 16 rest a forward substitution (one
-//            thread per column).  X[k][c], k > c, lives at G[c][k] in the unused upper triangle.
-// Phase times of one call (100 MHz wall clock, warm input): diagonal blocks 25 us, rows below 8,
-// trailing tiles 9, products of the inverse 9, substitutions of the inverse 19: 71 us, of which
-// the two tiled parts took 48 before they ran on the matrix cores.
+//   invert   X = L^-1: the eight 16 x 16 inverses of the diagonal blocks at once (one thread per
+//            column), then block row by block row as products of tiles.  X[k][c], k > c, lives at
+//            G[c][k] in the unused upper triangle.
+// Phase times of one call (100 MHz wall clock, warm input): diagonal blocks 22 us, rows below 8,
+// trailing tiles 9, diagonal inverses 2, block rows of the inverse 12: 55 us.  With the tiled parts on
+// the vector ALUs and a substitution per block row it was 101.
 __global__ __launch_bounds__(256) void sub_chol_kernel(const double* __restrict__ gsum, float* __restrict__ Rinv) {
     extern __shared__ __align__(16) double G[];                // [128][129]
     __shared__ double dinv[kP];
@@ -417,12 +417,11 @@ __global__ __launch_bounds__(256) void sub_chol_kernel(const double* __restrict_
                 const bool live = piv > tol;
                 const double di = live ? rsqrt(piv) : 0.0;              // one reciprocal square root instead of a root and a division
                 const double d = piv * di;
-                if (i == j) a[j] = d;
-                else if (i > j) a[j] *= di;
+                a[j] = i == j ? d : a[j] * di;                           // rows i < j: values nobody reads
 #pragma unroll
                 for (int k = j + 1; k < B; ++k) {
                     const double lkj = lane_value(a[j], k);              // L[k][j]
-                    if (i >= k) a[k] -= a[j] * lkj;                      // G[i][k] -= L[i][j] L[k][j], j < k <= i
+                    a[k] = fma(-a[j], lkj, a[k]);                        // G[i][k] -= L[i][j] L[k][j]; only j < k <= i is read later
                 }
                 if (lane == 0) dinv[j0 + j] = di;
             }
@@ -483,49 +482,54 @@ __global__ __launch_bounds__(256) void sub_chol_kernel(const double* __restrict_
         }
         __syncthreads();
     }
-    // X = L^-1, block row I at a time.  X[k][c] (k > c) is kept at G[c][k]; X[c][c] = dinv[c].
-    for (int I = 0; I < NB; ++I) {
-        const int i0 = B * I;
-        // what the earlier block rows contribute: S[i][c] = -sum_{k=c}^{i0-1} L[i][k] X[k][c], c < i0 <= i; parked at G[c][i].
-        // By tiles on the fp64 matrix cores: S(I, C) = -sum_{K=C}^{I-1} L(I, K) X(K, C); wave w takes the column
-        // tiles C = w, w + 4.  X(K, C) sits transposed in the upper triangle, so both operands are read along rows
-        // of G; the diagonal tile X(C, C) is lower triangular with 1 / L[c][c] on its diagonal.
-        {
-            const int c = lane & 15, kk = lane >> 4;
-            for (int C = wv; C < I; C += 4) {
-                f64x4_t acc = {0.0, 0.0, 0.0, 0.0};
-                for (int K = C; K < I; ++K) {
+    // X = L^-1.  X[k][c] (k > c) is kept at G[c][k], in the unused upper triangle; X[c][c] = dinv[c].
+    // First the eight diagonal tiles T_I = L_II^-1, all at once: thread c solves column c of its tile (the chain
+    // through the 16 rows is paid once, not once per block row).
+    if (tid < kP) {
+        const int c = tid, i0 = c & ~(B - 1);
+        double x[B];
 #pragma unroll
-                    for (int sx = 0; sx < 4; ++sx) {
-                        const int k = 4 * sx + kk;                   // row of X / column of L inside tile K
-                        const double av = -G[(i0 + c) * LD + B * K + k];
-                        double bv = G[(B * C + c) * LD + B * K + k];
-                        if (K == C) bv = k > c ? bv : (k == c ? dinv[B * C + c] : 0.0);
-                        acc = __builtin_amdgcn_mfma_f64_16x16x4f64(av, bv, acc, 0, 0, 0);
-                    }
-                }
+        for (int ii = 0; ii < B; ++ii) x[ii] = i0 + ii == c ? 1.0 : 0.0;
 #pragma unroll
-                for (int v = 0; v < 4; ++v) G[(B * C + c) * LD + i0 + 4 * v + kk] = acc[v];
-            }
+        for (int ii = 0; ii < B; ++ii) {
+            x[ii] = i0 + ii < c ? 0.0 : x[ii] * dinv[i0 + ii];
+#pragma unroll
+            for (int jj = ii + 1; jj < B; ++jj) x[jj] = fma(-G[(i0 + jj) * LD + i0 + ii], x[ii], x[jj]);
         }
-        __syncthreads();
-        // the block itself: x_i = (S_i - sum_{k = max(i0, c)}^{i-1} L[i][k] x_k) / L[i][i], column c by thread c
-        if (tid < i0 + B) {
-            const int c = tid;
-            double x[B];                                     // right-hand side, then the solution (same short chain as above)
 #pragma unroll
-            for (int ii = 0; ii < B; ++ii) x[ii] = c < i0 ? G[c * LD + i0 + ii] : (i0 + ii == c ? 1.0 : 0.0);
+        for (int ii = 0; ii < B; ++ii)
+            if (i0 + ii > c) G[c * LD + i0 + ii] = x[ii];
+    }
+    __syncthreads();
+    // Then block row I by tiles on the fp64 matrix cores:
+    //   S(I, C) = -sum_{K=C}^{I-1} L(I, K) X(K, C)   (X(K, C) sits transposed in the upper triangle, so both operands
+    //                                                 are read along rows of G; X(C, C) = T_C is lower triangular)
+    //   X(I, C) = T_I S(I, C)                         (register v of the result S is row 4 v + kk: exactly the lane's
+    //                                                 operand of contraction step v, so S never leaves the registers)
+    for (int I = 1; I < NB; ++I) {
+        const int i0 = B * I;
+        const int c = lane & 15, kk = lane >> 4;
+        for (int C = wv; C < I; C += 4) {                            // wave w takes the column tiles w and w + 4
+            f64x4_t acc = {0.0, 0.0, 0.0, 0.0};
+            for (int K = C; K < I; ++K) {
 #pragma unroll
-            for (int ii = 0; ii < B; ++ii) {
-                x[ii] = i0 + ii < c ? 0.0 : x[ii] * dinv[i0 + ii];                              // 0 above column c
+                for (int sx = 0; sx < 4; ++sx) {
+                    const int k = 4 * sx + kk;                       // row of X / column of L inside tile K
+                    const double av = -G[(i0 + c) * LD + B * K + k];
+                    double bv = G[(B * C + c) * LD + B * K + k];
+                    if (K == C) bv = k > c ? bv : (k == c ? dinv[B * C + c] : 0.0);
+                    acc = __builtin_amdgcn_mfma_f64_16x16x4f64(av, bv, acc, 0, 0, 0);
+                }
+            }
+            f64x4_t xt = {0.0, 0.0, 0.0, 0.0};
 #pragma unroll
-                for (int jj = ii + 1; jj < B; ++jj) x[jj] = fma(-G[(i0 + jj) * LD + i0 + ii], x[ii], x[jj]);
+            for (int sx = 0; sx < 4; ++sx) {
+                const int k = 4 * sx + kk;                           // T_I[c][k], kept at G[i0 + k][i0 + c] for k < c
+                const double tv = k < c ? G[(i0 + k) * LD + i0 + c] : (k == c ? dinv[i0 + c] : 0.0);
+                xt = __builtin_amdgcn_mfma_f64_16x16x4f64(tv, acc[sx], xt, 0, 0, 0);
             }
 #pragma unroll
-            for (int ii = 0; ii < B; ++ii) {
-                const int i = i0 + ii;
-                if (i > c) G[c * LD + i] = x[ii];
-            }
+            for (int v = 0; v < 4; ++v) G[(B * C + c) * LD + i0 + 4 * v + kk] = xt[v];
         }
         __syncthreads();
     }
