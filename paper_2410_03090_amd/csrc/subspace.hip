@@ -650,10 +650,13 @@ static hipError_t run_matrix_entropy(const T* X, int n_mat, int N, int D, int64_
     // of the tilt that is left.  The last round and the final projection use both halves (measured against the
     // fp64 reference: entropy off by 1e-6 relative at most with one such round, 5e-5 with none).
     const int first_precise = n_iter - 1;
-    auto project = [&](const T* Xm, bool precise) {       // Z = X Q
+    bool zt_ready = false;                                // the last projection left the transposed halves of Z, not Z
+    auto project = [&](const T* Xm, bool precise, bool for_round) {       // Z = X Q
+        zt_ready = false;
         if constexpr (sizeof(T) == 2) {
             if (mfma) {
-                hipError_t e = launch_xq_mfma(Xm, ldx, Q, N, D, Qt_hi, Qt_lo, p.z_splits, Zpart, Z, s, precise);
+                hipError_t e = launch_xq_mfma(Xm, ldx, Q, N, D, Qt_hi, Qt_lo, p.z_splits, Zpart, Z, s, precise, for_round, Zh,
+                                              Zl, &zt_ready);
                 if (e != hipSuccess) perr = e;
                 return;
             }
@@ -674,7 +677,7 @@ static hipError_t run_matrix_entropy(const T* X, int n_mat, int N, int D, int64_
         orth();
         for (int it = 0; it < n_iter; ++it) {
             const bool precise = it >= first_precise;
-            project(Xm, precise);
+            project(Xm, precise, true);
             if (center) {
                 sub_zsum_part_kernel<<<dim3(kZsumParts), dim3(1024), 0, s>>>(sv, Q, D, zsum + kP);
                 sub_zsum_kernel<<<dim3(1), dim3(128), 0, s>>>(zsum + kP, zsum);
@@ -683,7 +686,7 @@ static hipError_t run_matrix_entropy(const T* X, int n_mat, int N, int D, int64_
             bool done = false;
             if constexpr (sizeof(T) == 2) {
                 if (mfma) {
-                    hipError_t e = launch_xtz_mfma(Xm, ldx, Z, N, D, Zh, Zl, p.t_chunk, p.t_chunks, Wpart, s, precise);
+                    hipError_t e = launch_xtz_mfma(Xm, ldx, Z, N, D, Zh, Zl, p.t_chunk, p.t_chunks, Wpart, s, precise, zt_ready);
                     if (e != hipSuccess) return e;
                     w_parts = p.t_chunks;
                     done = true;
@@ -701,7 +704,7 @@ static hipError_t run_matrix_entropy(const T* X, int n_mat, int N, int D, int64_
                 orth();
             }
         }
-        project(Xm, true);
+        project(Xm, true, false);
         env.end();
         if (perr != hipSuccess) return perr;
         // the projected tokens go through the 128-wide entropy path; trace(C) replaces its own trace

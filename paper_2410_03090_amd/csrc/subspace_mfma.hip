@@ -59,11 +59,16 @@ constexpr size_t xq_lds_bytes() {
     return (size_t)2 * (LO ? 2 : 1) * kP * kQtRow * sizeof(bf16_bits);
 }
 
-template <bool LO>
+// ZT: the result goes out as the transposed bf16 halves that the X^T Z kernel streams (Zt_hi, and Zt_lo when
+// LO, [128][n_pad] with zeros for the tokens from N to n_pad) instead of as fp32 rows: the rounds of the
+// iteration need nothing else of Z, which saves writing it as fp32 and reading it back to split it.
+template <bool LO, bool ZT>
 __global__ __launch_bounds__(256) void sub_xq_mfma_kernel(const bf16_bits* __restrict__ X, int64_t ldx,
                                                           const bf16_bits* __restrict__ Qt_hi,
                                                           const bf16_bits* __restrict__ Qt_lo, int N, int D,
-                                                          int k_chunk, float* __restrict__ out) {
+                                                          int k_chunk, float* __restrict__ out,
+                                                          bf16_bits* __restrict__ Zt_hi, bf16_bits* __restrict__ Zt_lo,
+                                                          int64_t n_pad) {
     extern __shared__ __align__(16) bf16_bits qs_raw[];              // [buffer][half][column][kQtRow]
     constexpr int kHalf = kP * kQtRow, kBuf = (LO ? 2 : 1) * kHalf;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
@@ -173,6 +178,30 @@ __global__ __launch_bounds__(256) void sub_xq_mfma_kernel(const bf16_bits* __res
         body(phase_t<1>{}, s0 + 1);
     }
     // accumulator lane: column 16 cb + n, rows 16 rb + 4 kq + v
+    if constexpr (ZT) {
+        // four consecutive tokens of one column = 8 bytes of a row of Zt; groups of four never straddle N's
+        // padding end (n_pad is a multiple of 128, the groups start at multiples of 4)
+#pragma unroll
+        for (int rb = 0; rb < 4; ++rb) {
+            const int r = row0 + 16 * rb + 4 * kq;
+            if (r < n_pad) {
+#pragma unroll
+                for (int cb = 0; cb < 8; ++cb) {
+                    uint32_t h[4], l[4];
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        const float z = r + v < N ? acc[rb][cb][v] : 0.f;
+                        h[v] = bf16_rne(z);
+                        l[v] = bf16_rne(z - __uint_as_float(h[v] << 16));
+                    }
+                    const int64_t at = (int64_t)(16 * cb + n) * n_pad + r;
+                    *reinterpret_cast<uint2*>(Zt_hi + at) = make_uint2(h[0] | (h[1] << 16), h[2] | (h[3] << 16));
+                    if (LO) *reinterpret_cast<uint2*>(Zt_lo + at) = make_uint2(l[0] | (l[1] << 16), l[2] | (l[3] << 16));
+                }
+            }
+        }
+        return;
+    }
     float* o = out + (int64_t)kc * N * kP;
 #pragma unroll
     for (int rb = 0; rb < 4; ++rb)
@@ -373,17 +402,27 @@ __global__ __launch_bounds__(256) void sub_sum_parts_kernel(const float* __restr
     *reinterpret_cast<float4*>(out + e) = a;
 }
 
+// Z = X Q.  want_zt: the caller only needs Z as the operand of launch_xtz_mfma; when the sum over d is not split
+// the kernel then writes the transposed bf16 halves itself and *zt_written tells launch_xtz_mfma to skip its split.
 hipError_t launch_xq_mfma(const bf16_bits* X, int64_t ldx, const float* Q, int N, int D, bf16_bits* Qt_hi,
-                          bf16_bits* Qt_lo, int n_split, float* Zpart, float* Z, hipStream_t s, bool precise) {
+                          bf16_bits* Qt_lo, int n_split, float* Zpart, float* Z, hipStream_t s, bool precise,
+                          bool want_zt, bf16_bits* Zh, bf16_bits* Zl, bool* zt_written) {
     sub_qt_split_kernel<<<dim3((unsigned)(D / 32), kP / 32), dim3(256), 0, s>>>(Q, D, Qt_hi, Qt_lo);
     const int k_chunk = ((D + n_split - 1) / n_split + kQStep - 1) / kQStep * kQStep;
     const int splits = (D + k_chunk - 1) / k_chunk;
     float* dst = splits == 1 ? Z : Zpart;
     const dim3 grid((unsigned)((N + 255) / 256), (unsigned)splits);
-    if (precise)
-        sub_xq_mfma_kernel<true><<<grid, dim3(256), xq_lds_bytes<true>(), s>>>(X, ldx, Qt_hi, Qt_lo, N, D, k_chunk, dst);
+    const int64_t n_pad = ((int64_t)N + 127) / 128 * 128;
+    const bool zt = want_zt && splits == 1;
+    if (zt_written != nullptr) *zt_written = zt;
+    if (zt && precise)
+        sub_xq_mfma_kernel<true, true><<<grid, dim3(256), xq_lds_bytes<true>(), s>>>(X, ldx, Qt_hi, Qt_lo, N, D, k_chunk, dst, Zh, Zl, n_pad);
+    else if (zt)
+        sub_xq_mfma_kernel<false, true><<<grid, dim3(256), xq_lds_bytes<false>(), s>>>(X, ldx, Qt_hi, Qt_lo, N, D, k_chunk, dst, Zh, Zl, n_pad);
+    else if (precise)
+        sub_xq_mfma_kernel<true, false><<<grid, dim3(256), xq_lds_bytes<true>(), s>>>(X, ldx, Qt_hi, Qt_lo, N, D, k_chunk, dst, Zh, Zl, n_pad);
     else
-        sub_xq_mfma_kernel<false><<<grid, dim3(256), xq_lds_bytes<false>(), s>>>(X, ldx, Qt_hi, Qt_lo, N, D, k_chunk, dst);
+        sub_xq_mfma_kernel<false, false><<<grid, dim3(256), xq_lds_bytes<false>(), s>>>(X, ldx, Qt_hi, Qt_lo, N, D, k_chunk, dst, Zh, Zl, n_pad);
     if (splits > 1) {
         const int64_t total = (int64_t)N * kP;
         sub_sum_parts_kernel<<<dim3((unsigned)((total / 4 + 255) / 256)), dim3(256), 0, s>>>(Zpart, splits, total, Z);
@@ -391,26 +430,28 @@ hipError_t launch_xq_mfma(const bf16_bits* X, int64_t ldx, const float* Q, int N
     return hipGetLastError();
 }
 
-// Wpart[tc][D][128] = partial X^T Z over token chunks (t_chunk a multiple of 128); Zh / Zl are scratch for the
-// two transposed halves of Z, [128][n_pad] bf16 each with n_pad = N rounded up to 128.
+// Wpart[tc][D][128] = partial X^T Z over token chunks (t_chunk a multiple of 128); Zh / Zl: the two transposed
+// halves of Z, [128][n_pad] bf16 each with n_pad = N rounded up to 128, made here from Z unless zt_ready.
 hipError_t launch_xtz_mfma(const bf16_bits* X, int64_t ldx, const float* Z, int N, int D, bf16_bits* Zh, bf16_bits* Zl,
-                           int t_chunk, int n_tchunks, float* Wpart, hipStream_t s, bool precise) {
+                           int t_chunk, int n_tchunks, float* Wpart, hipStream_t s, bool precise, bool zt_ready) {
     const int64_t n_pad = ((int64_t)N + 127) / 128 * 128;
     const dim3 sgrid((unsigned)(n_pad / 64), kP / 32);
     const int n_slabs = D / 128;
     const dim3 grid((unsigned)(n_slabs * n_tchunks));
     if (precise) {
-        sub_z_split_kernel<true><<<sgrid, dim3(256), 0, s>>>(Z, N, n_pad, Zh, Zl);
+        if (!zt_ready) sub_z_split_kernel<true><<<sgrid, dim3(256), 0, s>>>(Z, N, n_pad, Zh, Zl);
         sub_xtz_mfma_kernel<true><<<grid, dim3(256), 0, s>>>(X, ldx, Zh, Zl, n_pad, N, D, n_slabs, t_chunk, Wpart);
     } else {
-        sub_z_split_kernel<false><<<sgrid, dim3(256), 0, s>>>(Z, N, n_pad, Zh, Zl);
+        if (!zt_ready) sub_z_split_kernel<false><<<sgrid, dim3(256), 0, s>>>(Z, N, n_pad, Zh, Zl);
         sub_xtz_mfma_kernel<false><<<grid, dim3(256), 0, s>>>(X, ldx, Zh, Zl, n_pad, N, D, n_slabs, t_chunk, Wpart);
     }
     return hipGetLastError();
 }
 
 hipError_t init_subspace_mfma_kernels() {
-    return allow_dynamic_lds(reinterpret_cast<const void*>(sub_xq_mfma_kernel<true>), xq_lds_bytes<true>());
+    hipError_t e = allow_dynamic_lds(reinterpret_cast<const void*>(sub_xq_mfma_kernel<true, false>), xq_lds_bytes<true>());
+    if (e != hipSuccess) return e;
+    return allow_dynamic_lds(reinterpret_cast<const void*>(sub_xq_mfma_kernel<true, true>), xq_lds_bytes<true>());
 }
 
 }  // namespace uncomp
