@@ -208,29 +208,103 @@ __global__ __launch_bounds__(256) void sub_gemm_kernel(const T* __restrict__ A, 
     }
 }
 
-// zsum[j] = sum_d s[d] Q[d][j] (= column sums of Z = X Q), fp64, in two steps: workgroup b adds the
-// rows d = b, b + 32, ... (thread (slice, j): every eighth of those), then the 32 partial rows are
-// added in a fixed order.
-constexpr int kZsumParts = 32;
-__global__ __launch_bounds__(1024) void sub_zsum_part_kernel(const double* __restrict__ s, const float* __restrict__ Q,
-                                                             int D, double* __restrict__ zpart) {
-    __shared__ double part[8][kP];
-    const int j = threadIdx.x & (kP - 1), sl = threadIdx.x >> 7;
-    double a = 0.0;
-    for (int d = blockIdx.x + kZsumParts * sl; d < D; d += kZsumParts * 8) a += s[d] * (double)Q[(int64_t)d * kP + j];
-    part[sl][j] = a;
-    __syncthreads();
-    if (sl == 0) {
-        double t = part[0][j];
+// Q = W Rinv for 32 rows of W per workgroup (fp32 ALUs, a thread owns 2 rows x 8 columns, Rinv staged 16 rows
+// at a time), together with what the next round needs of Q besides: its transposed bf16 halves Qt_hi / Qt_lo
+// [128][D] (the operand that the MFMA version of Z = X Q streams; skipped when Qt_hi is null) and, when centring
+// (s not null), this row block's share of s^T Q in fp64: zpart[block][128].  D is a multiple of 128.
+constexpr int kQRows = 32;
+__global__ __launch_bounds__(256) void sub_q_kernel(const float* __restrict__ W, const float* __restrict__ Rinv, int D,
+                                                    const double* __restrict__ s, float* __restrict__ Q,
+                                                    uint16_t* __restrict__ Qt_hi, uint16_t* __restrict__ Qt_lo,
+                                                    double* __restrict__ zpart) {
+    __shared__ __align__(16) float Ws[kQRows][kP + 4];
+    __shared__ __align__(16) float Rs[16][kP];
+    __shared__ float Qs[kQRows][kP + 1];
+    const int d0 = blockIdx.x * kQRows;
+    const int tid = threadIdx.x, ty = tid >> 4, tx = tid & 15;
 #pragma unroll
-        for (int x = 1; x < 8; ++x) t += part[x][j];
-        zpart[blockIdx.x * kP + j] = t;
+    for (int e = 0; e < 4; ++e) {
+        const int idx = tid + 256 * e, r = idx >> 5, q = idx & 31;
+        *reinterpret_cast<float4*>(&Ws[r][4 * q]) = *reinterpret_cast<const float4*>(W + (int64_t)(d0 + r) * kP + 4 * q);
+    }
+    float acc[2][8];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[i][j] = 0.f;
+    for (int k0 = 0; k0 < kP; k0 += 16) {
+        __syncthreads();                                             // Ws written / the previous 16 rows of Rinv read
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+            const int idx = tid + 256 * e, k = idx >> 5, q = idx & 31;
+            *reinterpret_cast<float4*>(&Rs[k][4 * q]) = *reinterpret_cast<const float4*>(Rinv + (int64_t)(k0 + k) * kP + 4 * q);
+        }
+        __syncthreads();
+#pragma unroll
+        for (int k = 0; k < 16; ++k) {
+            const float a0 = Ws[2 * ty][k0 + k], a1 = Ws[2 * ty + 1][k0 + k];
+            const float4 b0 = *reinterpret_cast<const float4*>(&Rs[k][8 * tx]);
+            const float4 b1 = *reinterpret_cast<const float4*>(&Rs[k][8 * tx + 4]);
+            const float bv[8] = {b0.x, b0.y, b0.z, b0.w, b1.x, b1.y, b1.z, b1.w};
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                acc[0][j] = fmaf(a0, bv[j], acc[0][j]);
+                acc[1][j] = fmaf(a1, bv[j], acc[1][j]);
+            }
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        float* o = Q + (int64_t)(d0 + 2 * ty + i) * kP + 8 * tx;
+        *reinterpret_cast<float4*>(o) = make_float4(acc[i][0], acc[i][1], acc[i][2], acc[i][3]);
+        *reinterpret_cast<float4*>(o + 4) = make_float4(acc[i][4], acc[i][5], acc[i][6], acc[i][7]);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) Qs[2 * ty + i][8 * tx + j] = acc[i][j];
+    }
+    __syncthreads();
+    if (Qt_hi != nullptr) {
+        // thread = (column, half of the 32 rows): 16 consecutive d of one column = 32 bytes per bf16 half
+        const int col = tid >> 1, r0 = 16 * (tid & 1);
+        uint32_t h[8], l[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const float v0 = Qs[r0 + 2 * e][col], v1 = Qs[r0 + 2 * e + 1][col];
+            const uint32_t h0 = __float_as_uint(v0), h1 = __float_as_uint(v1);
+            const uint32_t hi0 = (h0 + 0x7fffu + ((h0 >> 16) & 1u)) >> 16, hi1 = (h1 + 0x7fffu + ((h1 >> 16) & 1u)) >> 16;   // round to nearest even
+            const uint32_t g0 = __float_as_uint(v0 - __uint_as_float(hi0 << 16)), g1 = __float_as_uint(v1 - __uint_as_float(hi1 << 16));
+            const uint32_t lo0 = (g0 + 0x7fffu + ((g0 >> 16) & 1u)) >> 16, lo1 = (g1 + 0x7fffu + ((g1 >> 16) & 1u)) >> 16;
+            h[e] = hi0 | (hi1 << 16);
+            l[e] = lo0 | (lo1 << 16);
+        }
+        uint4* ph = reinterpret_cast<uint4*>(Qt_hi + (int64_t)col * D + d0 + r0);
+        uint4* pl = reinterpret_cast<uint4*>(Qt_lo + (int64_t)col * D + d0 + r0);
+        ph[0] = make_uint4(h[0], h[1], h[2], h[3]);
+        ph[1] = make_uint4(h[4], h[5], h[6], h[7]);
+        pl[0] = make_uint4(l[0], l[1], l[2], l[3]);
+        pl[1] = make_uint4(l[4], l[5], l[6], l[7]);
+    }
+    if (s != nullptr && tid < kP) {
+        double t = 0.0;
+#pragma unroll 8
+        for (int r = 0; r < kQRows; ++r) t += s[d0 + r] * (double)Qs[r][tid];
+        zpart[(int64_t)blockIdx.x * kP + tid] = t;
     }
 }
-__global__ __launch_bounds__(128) void sub_zsum_kernel(const double* __restrict__ zpart, double* __restrict__ zsum) {
+
+// zsum[j] = sum_d s[d] Q[d][j] (= column sums of Z = X Q): the row blocks' shares added in a fixed order
+// (eight interleaved partial sums side by side, then those in order).
+__global__ __launch_bounds__(1024) void sub_zsum_kernel(const double* __restrict__ zpart, int n_parts, double* __restrict__ zsum) {
+    __shared__ double part[8][kP];
+    const int j = threadIdx.x & (kP - 1), q = threadIdx.x >> 7;
     double t = 0.0;
-    for (int b = 0; b < kZsumParts; ++b) t += zpart[b * kP + threadIdx.x];
-    zsum[threadIdx.x] = t;
+    for (int b = q; b < n_parts; b += 8) t += zpart[(int64_t)b * kP + j];
+    part[q][j] = t;
+    __syncthreads();
+    if (q == 0) {
+#pragma unroll
+        for (int x = 1; x < 8; ++x) t += part[x][j];
+        zsum[j] = t;
+    }
 }
 
 // W[d][j] = sum over chunks of part[c][d][j] - s[d] zsum[j] / N   (the mean correction of C Q)
@@ -576,7 +650,7 @@ MatrixPlan plan_matrix(int N, int D) {
     p.statpart_off = take((size_t)p.stat_chunks * 2 * D * sizeof(double));
     p.s_off = take((size_t)D * sizeof(double));
     p.trace_off = take((size_t)(2 + 2 * ((D + 255) / 256)) * sizeof(double));     // the traces, then per-workgroup shares
-    p.zsum_off = take((size_t)(1 + kZsumParts) * kP * sizeof(double));     // the sums, then the partial rows
+    p.zsum_off = take((size_t)(1 + D / kQRows) * kP * sizeof(double));     // the sums, then the row blocks' shares
     p.q_off = take((size_t)D * kP * sizeof(float));
     p.w_off = take((size_t)D * kP * sizeof(float));
     // token chunks of the MFMA version of W = X^T Z (whole rounds of 128 tokens)
@@ -625,13 +699,6 @@ static hipError_t run_matrix_entropy(const T* X, int n_mat, int N, int D, int64_
     float* Rinv = reinterpret_cast<float*>(ws + p.rinv_off);
     const size_t chol_lds = (size_t)kP * (kP + 1) * sizeof(double);
     const unsigned dp_blocks = (unsigned)(((int64_t)D * kP + 255) / 256);
-    // Q = orth(W): Cholesky QR with the Gram in fp64
-    auto orth = [&]() {
-        sub_gram64_kernel<<<dim3((unsigned)p.gram_slices), dim3(256), 0, s>>>(W, D, p.gram_rows, gpart, nullptr);
-        sub_gram64_sum_kernel<<<dim3(kP * kP / 256), dim3(256), 0, s>>>(gpart, p.gram_slices, gsum);
-        sub_chol_kernel<<<dim3(1), dim3(256), chol_lds, s>>>(gsum, Rinv);
-        sub_gemm_kernel<float, false><<<dim3((unsigned)((D + 63) / 64), 1), dim3(256), 0, s>>>(W, kP, Rinv, D, kP, kP, Q);
-    };
     // bf16 inputs with 16-byte aligned rows take the MFMA products, everything else the fp32 ALUs
     // (rows at most 2^22 elements apart: those kernels address 256 rows with 32-bit byte offsets)
     bool mfma = false;
@@ -640,6 +707,15 @@ static hipError_t run_matrix_entropy(const T* X, int n_mat, int N, int D, int64_
                ldx <= ((int64_t)1 << 22);
     bf16_bits* Qt_hi = reinterpret_cast<bf16_bits*>(ws + p.qt_off);
     bf16_bits* Qt_lo = Qt_hi + (size_t)kP * D;
+    // Q = orth(W): Cholesky QR with the Gram in fp64; the last kernel also leaves the bf16 halves of Q^T and the
+    // shares of s^T Q for the round that follows
+    auto orth = [&]() {
+        sub_gram64_kernel<<<dim3((unsigned)p.gram_slices), dim3(256), 0, s>>>(W, D, p.gram_rows, gpart, nullptr);
+        sub_gram64_sum_kernel<<<dim3(kP * kP / 256), dim3(256), 0, s>>>(gpart, p.gram_slices, gsum);
+        sub_chol_kernel<<<dim3(1), dim3(256), chol_lds, s>>>(gsum, Rinv);
+        sub_q_kernel<<<dim3((unsigned)(D / kQRows)), dim3(256), 0, s>>>(W, Rinv, D, center ? sv : nullptr, Q,
+                                                                       mfma ? Qt_hi : nullptr, Qt_lo, zsum + kP);
+    };
     float* Zpart = reinterpret_cast<float*>(ws + p.zpart_off);
     bf16_bits* Zh = reinterpret_cast<bf16_bits*>(ws + p.zsplit_off);
     bf16_bits* Zl = Zh + (((size_t)N + 127) / 128 * 128) * kP;
@@ -679,8 +755,7 @@ static hipError_t run_matrix_entropy(const T* X, int n_mat, int N, int D, int64_
             const bool precise = it >= first_precise;
             project(Xm, precise, true);
             if (center) {
-                sub_zsum_part_kernel<<<dim3(kZsumParts), dim3(1024), 0, s>>>(sv, Q, D, zsum + kP);
-                sub_zsum_kernel<<<dim3(1), dim3(128), 0, s>>>(zsum + kP, zsum);
+                sub_zsum_kernel<<<dim3(1), dim3(1024), 0, s>>>(zsum + kP, D / kQRows, zsum);
             }
             int w_parts = p.w_chunks;
             bool done = false;

@@ -21,23 +21,6 @@ __device__ __forceinline__ uint32_t bf16_rne(float f) {
 
 }  // namespace
 
-// Qt_hi / Qt_lo [128][D] bf16 from Q [D][128] fp32: the transposed halves that the X Q kernel streams.
-__global__ __launch_bounds__(256) void sub_qt_split_kernel(const float* __restrict__ Q, int D, bf16_bits* __restrict__ Qt_hi,
-                                                           bf16_bits* __restrict__ Qt_lo) {
-    __shared__ float tile[32][33];
-    const int d0 = blockIdx.x * 32, j0 = blockIdx.y * 32;
-    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;           // 32 x 8
-    for (int r = ty; r < 32; r += 8) tile[r][tx] = Q[(int64_t)(d0 + r) * kP + j0 + tx];
-    __syncthreads();
-    for (int r = ty; r < 32; r += 8) {
-        const float v = tile[tx][r];                                  // Q[d0 + tx][j0 + r]
-        const uint32_t hi = bf16_rne(v);
-        const uint32_t lo = bf16_rne(v - __uint_as_float(hi << 16));
-        Qt_hi[(int64_t)(j0 + r) * D + d0 + tx] = (bf16_bits)hi;
-        Qt_lo[(int64_t)(j0 + r) * D + d0 + tx] = (bf16_bits)lo;
-    }
-}
-
 // out[kc][t][j] = sum over the k chunk of X[t][d] (Qt_hi[j][d] + Qt_lo[j][d]).
 // Workgroup: 256 rows of X; wave: 64 rows (four 16-row blocks) x 128 columns.  Per step of 64 d (one whole
 // 128-byte line of every row: with half lines a sixth of X came from HBM twice, the other half having left
@@ -402,12 +385,11 @@ __global__ __launch_bounds__(256) void sub_sum_parts_kernel(const float* __restr
     *reinterpret_cast<float4*>(out + e) = a;
 }
 
-// Z = X Q.  want_zt: the caller only needs Z as the operand of launch_xtz_mfma; when the sum over d is not split
+// Z = X Q, given Q^T as two bf16 halves [128][D] (left by the orthonormalisation).  want_zt: the caller only needs Z as the operand of launch_xtz_mfma; when the sum over d is not split
 // the kernel then writes the transposed bf16 halves itself and *zt_written tells launch_xtz_mfma to skip its split.
 hipError_t launch_xq_mfma(const bf16_bits* X, int64_t ldx, const float* Q, int N, int D, bf16_bits* Qt_hi,
                           bf16_bits* Qt_lo, int n_split, float* Zpart, float* Z, hipStream_t s, bool precise,
                           bool want_zt, bf16_bits* Zh, bf16_bits* Zl, bool* zt_written) {
-    sub_qt_split_kernel<<<dim3((unsigned)(D / 32), kP / 32), dim3(256), 0, s>>>(Q, D, Qt_hi, Qt_lo);
     const int k_chunk = ((D + n_split - 1) / n_split + kQStep - 1) / kQStep * kQStep;
     const int splits = (D + k_chunk - 1) / k_chunk;
     float* dst = splits == 1 ? Z : Zpart;
