@@ -327,11 +327,17 @@ __global__ __launch_bounds__(256) void sub_reduce_kernel(const float* __restrict
 // wave (tile rows w and 7 - w); the write-out mirrors them.
 constexpr int kGramRows = 64;
 constexpr int kGramLd = 144;             // floats per staged row: four consecutive rows start 16 banks apart
+constexpr int kGramTiles = 36;           // 16 x 16 tiles on and above the diagonal
 
 typedef double f64x4_t __attribute__((ext_vector_type(4)));
 
+// PACKED (the Gram of the projected tokens, whose partials only feed an fp32 result): the 36 computed tiles go
+// out as fp32, tile after tile (fpart[slice][36][16][16], tiles in the order (0,0) (0,1) ... (0,7) (1,1) ...),
+// a quarter of the bytes of the mirrored fp64 matrix that the Cholesky step needs.
+template <bool PACKED>
 __global__ __launch_bounds__(256) void sub_gram64_kernel(const float* __restrict__ A, int n_rows, int rows_per_wg,
-                                                         double* __restrict__ gpart, double* __restrict__ spart) {
+                                                         double* __restrict__ gpart, float* __restrict__ fpart,
+                                                         double* __restrict__ spart) {
     __shared__ __align__(16) float rows[kGramRows][kGramLd];
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int c = lane & 15, kk = lane >> 4;
@@ -377,16 +383,22 @@ __global__ __launch_bounds__(256) void sub_gram64_kernel(const float* __restrict
             }
         }
     }
-    double* o = gpart + (int64_t)blockIdx.x * kP * kP;
 #pragma unroll
     for (int sl = 0; sl < 9; ++sl) {
         const bool first = sl < n1;
         const int I = first ? I1 : I2, J = first ? I1 + sl : I2 + sl - n1;
+        if constexpr (PACKED) {
+            float* o = fpart + ((int64_t)blockIdx.x * kGramTiles + (I * 8 - I * (I - 1) / 2 + J - I)) * 256;
 #pragma unroll
-        for (int v = 0; v < 4; ++v) {
-            const int r = 16 * I + 4 * v + kk, col = 16 * J + c;
-            o[r * kP + col] = acc[sl][v];
-            if (I != J) o[col * kP + r] = acc[sl][v];
+            for (int v = 0; v < 4; ++v) o[(4 * v + kk) * 16 + c] = (float)acc[sl][v];
+        } else {
+            double* o = gpart + (int64_t)blockIdx.x * kP * kP;
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int r = 16 * I + 4 * v + kk, col = 16 * J + c;
+                o[r * kP + col] = acc[sl][v];
+                if (I != J) o[col * kP + r] = acc[sl][v];
+            }
         }
     }
     if (spart != nullptr && tid < kP) spart[(int64_t)blockIdx.x * kP + tid] = csum;
@@ -408,30 +420,49 @@ __global__ __launch_bounds__(256) void sub_gram64_sum_kernel(const double* __res
     gsum[e] = a;
 }
 
-// The same sums for the Gram of the projected tokens, rounded to the fp32 single-chunk layout that the
-// 128-wide eigenvalue kernels read: gram[128*128], then the column sums sums[128] (block 64 of the grid).
-__global__ __launch_bounds__(256) void sub_zgram_finish_kernel(const double* __restrict__ gpart,
+// The sums for the Gram of the projected tokens, from the packed fp32 tiles, mirrored into the fp32 single-chunk
+// layout that the 128-wide eigenvalue kernel reads: gram[128*128], then the column sums sums[128] (last block of
+// the grid).  Slices are added in fp64 in a fixed order.
+__global__ __launch_bounds__(256) void sub_zgram_finish_kernel(const float* __restrict__ fpart,
                                                                const double* __restrict__ spart, int n_slices,
                                                                float* __restrict__ gram, float* __restrict__ sums) {
-    if (blockIdx.x == kP * kP / 256) {
+    __shared__ double quarter[3][64];
+    if (blockIdx.x == kP * kP / 64) {
         if (threadIdx.x < kP) {
             double a = 0.0;
+#pragma unroll 8
             for (int sl = 0; sl < n_slices; ++sl) a += spart[(int64_t)sl * kP + threadIdx.x];
             sums[threadIdx.x] = (float)a;
         }
         return;
     }
-    const int e = blockIdx.x * 256 + threadIdx.x;
-    const double* g = gpart + e;
+    // a workgroup adds 64 entries: four quarters of the slices side by side (sixteen loads in flight per thread:
+    // the sum is a chain of memory round trips, not of bytes), then the quarters in order
+    const int i = threadIdx.x & 63, q = threadIdx.x >> 6;
+    const int e = blockIdx.x * 64 + i;
+    const int r = e >> 7, col = e & (kP - 1);
+    const int I = min(r, col) >> 4, J = max(r, col) >> 4;          // the tile that holds (r, col) or its mirror image
+    const int ri = r <= col ? r : col, ci = r <= col ? col : r;    // inside an off-diagonal tile: (row of I, column of J)
+    int at;
+    if (I == J) at = (r & 15) * 16 + (col & 15);                    // diagonal tiles are stored whole
+    else at = (ri & 15) * 16 + (ci & 15);
+    const float* g = fpart + (int64_t)(I * 8 - I * (I - 1) / 2 + J - I) * 256 + at;
+    const int64_t stride = (int64_t)kGramTiles * 256;
+    const int per = (n_slices + 3) / 4;
+    const int s0 = q * per, s1 = min(n_slices, s0 + per);
     double a = 0.0;
-    int sl = 0;
-    for (; sl + 3 < n_slices; sl += 4) {
-        const double v0 = g[(int64_t)sl * kP * kP], v1 = g[(int64_t)(sl + 1) * kP * kP];
-        const double v2 = g[(int64_t)(sl + 2) * kP * kP], v3 = g[(int64_t)(sl + 3) * kP * kP];
-        a = (((a + v0) + v1) + v2) + v3;
+    int sl = s0;
+    for (; sl + 15 < s1; sl += 16) {
+        float v[16];
+#pragma unroll
+        for (int u = 0; u < 16; ++u) v[u] = g[(sl + u) * stride];
+#pragma unroll
+        for (int u = 0; u < 16; ++u) a += (double)v[u];
     }
-    for (; sl < n_slices; ++sl) a += g[(int64_t)sl * kP * kP];
-    gram[e] = (float)a;
+    for (; sl < s1; ++sl) a += (double)g[sl * stride];
+    if (q > 0) quarter[q - 1][i] = a;
+    __syncthreads();
+    if (q == 0) gram[e] = (float)(((a + quarter[0][i]) + quarter[1][i]) + quarter[2][i]);
 }
 
 // value of x in lane `src` (a compile-time constant after unrolling) as a wave-uniform double
@@ -710,7 +741,7 @@ static hipError_t run_matrix_entropy(const T* X, int n_mat, int N, int D, int64_
     // Q = orth(W): Cholesky QR with the Gram in fp64; the last kernel also leaves the bf16 halves of Q^T and the
     // shares of s^T Q for the round that follows
     auto orth = [&]() {
-        sub_gram64_kernel<<<dim3((unsigned)p.gram_slices), dim3(256), 0, s>>>(W, D, p.gram_rows, gpart, nullptr);
+        sub_gram64_kernel<false><<<dim3((unsigned)p.gram_slices), dim3(256), 0, s>>>(W, D, p.gram_rows, gpart, nullptr, nullptr);
         sub_gram64_sum_kernel<<<dim3(kP * kP / 256), dim3(256), 0, s>>>(gpart, p.gram_slices, gsum);
         sub_chol_kernel<<<dim3(1), dim3(256), chol_lds, s>>>(gsum, Rinv);
         sub_q_kernel<<<dim3((unsigned)(D / kQRows)), dim3(256), 0, s>>>(W, Rinv, D, center ? sv : nullptr, Q,
@@ -784,9 +815,10 @@ static hipError_t run_matrix_entropy(const T* X, int n_mat, int N, int D, int64_
         if (perr != hipSuccess) return perr;
         // the projected tokens go through the 128-wide entropy path; trace(C) replaces its own trace
         env.begin("matrix_gram");
-        sub_gram64_kernel<<<dim3((unsigned)p.zgram_slices), dim3(256), 0, s>>>(Z, N, p.zgram_rows, gpart, spart);
-        sub_zgram_finish_kernel<<<dim3(kP * kP / 256 + 1), dim3(256), 0, s>>>(
-            gpart, spart, p.zgram_slices, reinterpret_cast<float*>(ws + p.ep_off + p.ep.gram_off),
+        float* fpart = reinterpret_cast<float*>(gpart);          // the region of the fp64 slices, free by now
+        sub_gram64_kernel<true><<<dim3((unsigned)p.zgram_slices), dim3(256), 0, s>>>(Z, N, p.zgram_rows, nullptr, fpart, spart);
+        sub_zgram_finish_kernel<<<dim3(kP * kP / 64 + 1), dim3(256), 0, s>>>(
+            fpart, spart, p.zgram_slices, reinterpret_cast<float*>(ws + p.ep_off + p.ep.gram_off),
             reinterpret_cast<float*>(ws + p.ep_off + p.ep.sum_off));
         env.end();
         hipError_t e = launch_tridiag_entropy(1, N, k_trunc, flags, p.ep, ws + p.ep_off, entropy_out + m,
