@@ -474,7 +474,7 @@ __device__ __forceinline__ double lane_value(double x, int src) {
 
 // One workgroup: Cholesky G = L L^T in LDS (fp64), then Rinv = L^-T as fp32 so that Q = W Rinv has
 // orthonormal columns.  A pivot below 1e-12 of the largest diagonal entry retires its column (its
-// row and column of Rinv are zero).  Both halves work on 16-wide blocks, three workgroup barriers
+// row and column of Rinv are zero).  Both halves work on 16-wide blocks, two workgroup barriers
 // per block instead of two per column:
 //   factor   the 16 x 16 diagonal block in the registers of one wave (lane = row, values of other
 //            rows by v_readlane), the rows below it by forward substitution (one thread per row),
@@ -482,9 +482,10 @@ __device__ __forceinline__ double lane_value(double x, int src) {
 //   invert   X = L^-1: the eight 16 x 16 inverses of the diagonal blocks at once (one thread per
 //            column), then block row by block row as products of tiles.  X[k][c], k > c, lives at
 //            G[c][k] in the unused upper triangle.
-// Phase times of one call (100 MHz wall clock, warm input): diagonal blocks 22 us, rows below 8,
-// trailing tiles 9, diagonal inverses 2, block rows of the inverse 12: 55 us.  With the tiled parts on
-// the vector ALUs and a substitution per block row it was 101.
+// Phase times of one call (100 MHz wall clock, warm input): first diagonal block 3 us, rows below 9,
+// trailing tiles with the next diagonal block beside them 22, diagonal inverses 2, block rows of the
+// inverse 12: 49 us.  With the tiled parts on the vector ALUs, a substitution per block row and the
+// diagonal blocks on their own it was 101.
 __global__ __launch_bounds__(256) void sub_chol_kernel(const double* __restrict__ gsum, float* __restrict__ Rinv) {
     extern __shared__ __align__(16) double G[];                // [128][129]
     __shared__ double dinv[kP];
@@ -492,12 +493,16 @@ __global__ __launch_bounds__(256) void sub_chol_kernel(const double* __restrict_
     constexpr int LD = kP + 1, B = 16, NB = kP / B;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const double2* g2 = reinterpret_cast<const double2*>(gsum);
-#pragma unroll 8
-    for (int e = tid; e < kP * kP / 2; e += 256) {                 // 32 loads per thread, eight in flight
-        const double2 v = g2[e];
-        const int row = e >> 6, col = 2 * (e & 63);
-        G[row * LD + col] = v.x;
-        G[row * LD + col + 1] = v.y;
+    for (int e0 = tid; e0 < kP * kP / 2; e0 += 256 * 16) {         // 32 loads per thread, sixteen in flight
+        double2 v[16];
+#pragma unroll
+        for (int u = 0; u < 16; ++u) v[u] = g2[e0 + 256 * u];
+#pragma unroll
+        for (int u = 0; u < 16; ++u) {
+            const int e = e0 + 256 * u, row = e >> 6, col = 2 * (e & 63);
+            G[row * LD + col] = v[u].x;
+            G[row * LD + col + 1] = v[u].y;
+        }
     }
     __syncthreads();
     if (wv == 0) {
@@ -508,35 +513,62 @@ __global__ __launch_bounds__(256) void sub_chol_kernel(const double* __restrict_
     }
     __syncthreads();
     const double tol = maxdiag * 1e-12;
+    // diagonal block p, by one wave: lane i (and its copies in the upper lanes) holds row 16 p + i
+    auto factor_diagonal = [&](int p) {
+        const int j0 = B * p;
+        const int i = lane & (B - 1);
+        double a[B];
+#pragma unroll
+        for (int k = 0; k < B; ++k) a[k] = G[(j0 + i) * LD + j0 + k];
+#pragma unroll
+        for (int j = 0; j < B; ++j) {
+            const double piv = lane_value(a[j], j);
+            const bool live = piv > tol;
+            const double di = live ? rsqrt(piv) : 0.0;              // one reciprocal square root instead of a root and a division
+            const double d = piv * di;
+            a[j] = i == j ? d : a[j] * di;                           // rows i < j: values nobody reads
+#pragma unroll
+            for (int k = j + 1; k < B; ++k) {
+                const double lkj = lane_value(a[j], k);              // L[k][j]
+                a[k] = fma(-a[j], lkj, a[k]);                        // G[i][k] -= L[i][j] L[k][j]; only j < k <= i is read later
+            }
+            if (lane == 0) dinv[j0 + j] = di;
+        }
+        if (lane < B) {
+#pragma unroll
+            for (int k = 0; k < B; ++k)
+                if (k <= i) G[(j0 + i) * LD + j0 + k] = a[k];
+        }
+    };
+    // Trailing tile t of block p (t = ti (ti + 1) / 2 + tk, tk <= ti: tile (p + 1 + ti, p + 1 + tk)) on the fp64
+    // matrix cores: -= L[I][p] L[K][p]^T.  Operand lane (c, kk) holds row c of its factor at column 4 s + kk of the
+    // panel; result register v is row 4 v + kk, column c.  Diagonal tiles are computed whole: what lands above
+    // the diagonal is not read by the factorisation.
+    auto update_tile = [&](int p, int t) {
+        const int j0 = B * p;
+        const int c = lane & 15, kk = lane >> 4;
+        int ti = 0, rem = t;
+        while (rem > ti) {
+            rem -= ti + 1;
+            ++ti;
+        }
+        const int r0 = B * (p + 1 + ti), c0 = B * (p + 1 + rem);
+        f64x4_t acc;
+#pragma unroll
+        for (int v = 0; v < 4; ++v) acc[v] = G[(r0 + 4 * v + kk) * LD + c0 + c];
+#pragma unroll
+        for (int sx = 0; sx < 4; ++sx) {
+            const double av = -G[(r0 + c) * LD + j0 + 4 * sx + kk];
+            const double bv = G[(c0 + c) * LD + j0 + 4 * sx + kk];
+            acc = __builtin_amdgcn_mfma_f64_16x16x4f64(av, bv, acc, 0, 0, 0);
+        }
+#pragma unroll
+        for (int v = 0; v < 4; ++v) G[(r0 + 4 * v + kk) * LD + c0 + c] = acc[v];
+    };
+    if (wv == 0) factor_diagonal(0);
+    __syncthreads();
     for (int p = 0; p < NB; ++p) {
         const int j0 = B * p;
-        if (wv == 0) {
-            // diagonal block: lane i (and its copies in the upper lanes) holds row j0 + i
-            const int i = lane & (B - 1);
-            double a[B];
-#pragma unroll
-            for (int k = 0; k < B; ++k) a[k] = G[(j0 + i) * LD + j0 + k];
-#pragma unroll
-            for (int j = 0; j < B; ++j) {
-                const double piv = lane_value(a[j], j);
-                const bool live = piv > tol;
-                const double di = live ? rsqrt(piv) : 0.0;              // one reciprocal square root instead of a root and a division
-                const double d = piv * di;
-                a[j] = i == j ? d : a[j] * di;                           // rows i < j: values nobody reads
-#pragma unroll
-                for (int k = j + 1; k < B; ++k) {
-                    const double lkj = lane_value(a[j], k);              // L[k][j]
-                    a[k] = fma(-a[j], lkj, a[k]);                        // G[i][k] -= L[i][j] L[k][j]; only j < k <= i is read later
-                }
-                if (lane == 0) dinv[j0 + j] = di;
-            }
-            if (lane < B) {
-#pragma unroll
-                for (int k = 0; k < B; ++k)
-                    if (k <= i) G[(j0 + i) * LD + j0 + k] = a[k];
-            }
-        }
-        __syncthreads();
         {
             // rows below the block: L[r][j0 + j] = (G[r][j0 + j] - sum_{k<j} L[r][j0 + k] L[j0 + j][j0 + k]) / L[j0 + j][j0 + j]
             const int r = j0 + B + tid;
@@ -558,31 +590,18 @@ __global__ __launch_bounds__(256) void sub_chol_kernel(const double* __restrict_
         }
         __syncthreads();
         {
-            // trailing lower triangle by 16 x 16 tiles on the fp64 matrix cores, tiles dealt to the waves in turn:
-            // tile (I, K), p < K <= I, -= L[I][p] L[K][p]^T.  Operand lane (c, kk) holds row c of its factor at
-            // column 4 s + kk of the panel; result register v is row 4 v + kk, column c.  Diagonal tiles are
-            // computed whole: what lands above the diagonal is not read by the factorisation.
+            // Trailing lower triangle.  Wave 0 updates the next diagonal tile (tile 0) and factors it straight away,
+            // while the other three waves share the remaining tiles: the one-wave factorisation, the longest step of
+            // a block, runs beside the update instead of after it.
             const int m = NB - 1 - p;
             const int n_tiles = m * (m + 1) / 2;
-            const int c = lane & 15, kk = lane >> 4;
-            for (int t = wv; t < n_tiles; t += 4) {
-                int ti = 0, rem = t;
-                while (rem > ti) {                                   // t = ti (ti + 1) / 2 + tk, tk <= ti
-                    rem -= ti + 1;
-                    ++ti;
+            if (wv == 0) {
+                if (n_tiles > 0) {
+                    update_tile(p, 0);
+                    factor_diagonal(p + 1);
                 }
-                const int r0 = B * (p + 1 + ti), c0 = B * (p + 1 + rem);
-                f64x4_t acc;
-#pragma unroll
-                for (int v = 0; v < 4; ++v) acc[v] = G[(r0 + 4 * v + kk) * LD + c0 + c];
-#pragma unroll
-                for (int sx = 0; sx < 4; ++sx) {
-                    const double av = -G[(r0 + c) * LD + j0 + 4 * sx + kk];
-                    const double bv = G[(c0 + c) * LD + j0 + 4 * sx + kk];
-                    acc = __builtin_amdgcn_mfma_f64_16x16x4f64(av, bv, acc, 0, 0, 0);
-                }
-#pragma unroll
-                for (int v = 0; v < 4; ++v) G[(r0 + 4 * v + kk) * LD + c0 + c] = acc[v];
+            } else {
+                for (int t = wv; t < n_tiles; t += 3) update_tile(p, t);
             }
         }
         __syncthreads();
