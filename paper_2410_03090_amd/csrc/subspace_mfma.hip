@@ -161,9 +161,9 @@ __global__ __launch_bounds__(256) void sub_xq_mfma_kernel(const bf16_bits* __res
         body(phase_t<1>{}, s0 + 1);
     }
     // accumulator lane: column 16 cb + n, rows 16 rb + 4 kq + v
-    if constexpr (ZT) {
-        // four consecutive tokens of one column = 8 bytes of a row of Zt; groups of four never straddle N's
-        // padding end (n_pad is a multiple of 128, the groups start at multiples of 4)
+    if constexpr (ZT && LO) {
+        // both halves straight from the registers: four consecutive tokens of one column = 8 bytes of a row of Zt
+        // (this variant runs once per matrix and has no registers to spare for the staged way out below)
 #pragma unroll
         for (int rb = 0; rb < 4; ++rb) {
             const int r = row0 + 16 * rb + 4 * kq;
@@ -179,9 +179,48 @@ __global__ __launch_bounds__(256) void sub_xq_mfma_kernel(const bf16_bits* __res
                     }
                     const int64_t at = (int64_t)(16 * cb + n) * n_pad + r;
                     *reinterpret_cast<uint2*>(Zt_hi + at) = make_uint2(h[0] | (h[1] << 16), h[2] | (h[3] << 16));
-                    if (LO) *reinterpret_cast<uint2*>(Zt_lo + at) = make_uint2(l[0] | (l[1] << 16), l[2] | (l[3] << 16));
+                    *reinterpret_cast<uint2*>(Zt_lo + at) = make_uint2(l[0] | (l[1] << 16), l[2] | (l[3] << 16));
                 }
             }
+        }
+        return;
+    } else if constexpr (ZT) {
+        // Transposed on the way out through the staging buffers, which are free after the loop's last barrier: a
+        // wave packs 64 columns x its 64 tokens of one bf16 half into its quarter of them (8 bytes = four tokens
+        // of a column per lane and accumulator block), then writes them out as 16-byte pieces, eight lanes to a
+        // 128-byte run of one row of Zt (stored straight from the registers the same bytes went out as 32-byte
+        // runs, 10 us slower per pass).  Tokens from N to n_pad are zeros; n_pad is a multiple of 128.
+        bf16_bits* tile = qs_raw + wv * (64 * kQtRow);                // [64 columns][64 tokens + 8 of padding]
+        constexpr int kPasses = LO ? 4 : 2;
+#pragma unroll
+        for (int pass = 0; pass < kPasses; ++pass) {
+            const int ch = pass & 1;                                 // columns 64 ch .. + 64
+            const bool low = (pass >> 1) != 0;
+#pragma unroll
+            for (int cbh = 0; cbh < 4; ++cbh)
+#pragma unroll
+                for (int rb = 0; rb < 4; ++rb) {
+                    const int r = row0 + 16 * rb + 4 * kq;
+                    uint32_t w4[4];
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        const float z = r + v < N ? acc[rb][4 * ch + cbh][v] : 0.f;
+                        const uint32_t hi = bf16_rne(z);
+                        w4[v] = low ? bf16_rne(z - __uint_as_float(hi << 16)) : hi;
+                    }
+                    *reinterpret_cast<uint2*>(&tile[(16 * cbh + n) * kQtRow + 16 * rb + 4 * kq]) =
+                        make_uint2(w4[0] | (w4[1] << 16), w4[2] | (w4[3] << 16));
+                }
+            __syncthreads();
+            bf16_bits* dst = low ? Zt_lo : Zt_hi;
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int idx = lane + 64 * u, col = idx >> 3, piece = idx & 7;
+                const uint4 v = *reinterpret_cast<const uint4*>(&tile[col * kQtRow + 8 * piece]);
+                const int t = row0 + 8 * piece;
+                if (t < n_pad) *reinterpret_cast<uint4*>(dst + (int64_t)(64 * ch + col) * n_pad + t) = v;
+            }
+            __syncthreads();                                         // before the tile is packed again
         }
         return;
     }
