@@ -105,6 +105,29 @@ def test_matrix_entropy_hidden_state_width(ctx):
     np.testing.assert_allclose(eig.cpu().numpy()[:, :32], eref[:, :32], rtol=0, atol=2e-5)
 
 
+def test_matrix_entropy_maximum_width(ctx):
+    """D = 16384, the widest matrix the call takes.  Only 384 columns, scattered over the width, are non-zero:
+    the covariance is then the 384 x 384 covariance of those columns bordered by zeros, so the oracle on the
+    columns alone gives the same eigenvalues, trace and entropy without a 16384 x 16384 eigendecomposition."""
+    from paper_2410_03090_amd import binding
+    N, D, live = 1500, 16384, 384
+    g = torch.Generator().manual_seed(16384)
+    cols = torch.randperm(D, generator=g)[:live].sort().values
+    Xs = _lowrank(1, N, live, 48, torch.bfloat16, seed=77, offset=0.2)
+    X = torch.zeros(1, N, D, dtype=torch.bfloat16)
+    X[:, :, cols] = Xs
+    wide = binding.Context(0, binding.Context.matrix_workspace_bytes(N, D) + (16 << 20))
+    try:
+        for flags in (O.DEFAULT_FLAGS, 0):
+            H, eig = wide.matrix_entropy(X.to(DEV), k_trunc=32, flags=flags, n_iter=8, want_eig=True)
+            torch.cuda.synchronize()
+            Href, eref = O.head_entropy(to_f64(Xs), k_trunc=32, flags=flags)
+            np.testing.assert_allclose(H.cpu().numpy(), Href, rtol=1e-4)
+            np.testing.assert_allclose(eig.cpu().numpy()[:, :32], eref[:, :32], rtol=0, atol=2e-5)
+    finally:
+        wide.close()
+
+
 def test_matrix_entropy_is_deterministic(ctx):
     """Fixed start block, fixed-order reductions, no atomics: two runs give the same bits."""
     X = _lowrank(2, 1500, 768, 50, torch.bfloat16, seed=12).to(DEV)
