@@ -28,7 +28,10 @@
  *     context, stride arrays and strings are HOST memory.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only
  *     enqueue work on it and never synchronise; outputs are valid once the stream has
- *     reached the end of the call's work.
+ *     reached the end of the call's work.  What they enqueue is kernel launches (and, in
+ *     uncomp_matrix_entropy, device-to-device copies): no allocation, no memset, no host
+ *     wait, so with the profiler and the overlap mode off a sequence of calls can be
+ *     captured into a HIP graph and replayed on new contents of the same buffers.
  *   - All temporary device memory comes from the context's workspace, allocated once in
  *     uncomp_create.  A call that needs more returns UNCOMP_ERR_WORKSPACE and launches
  *     nothing.  One context serves one stream at a time (calls on it share the workspace).

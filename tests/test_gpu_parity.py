@@ -395,6 +395,42 @@ def test_end_to_end_config0(ctx):
     print(f"config 0: near-tie swaps {swaps}")
 
 
+def _four_calls(ctx, cfg, K, V, Q):
+    nl, B, H, N, D = K.shape
+    ent = ctx.head_entropy(K.reshape(nl * B * H, N, D), k_trunc=cfg.k_trunc).reshape(nl, B, H)
+    hb, hg, lg, lt = ctx.assign_budgets(ent, cfg.M, cfg.n_max, cfg.step, N, cfg.w, 0.4, 512)
+    score = ctx.window_score(Q.reshape(nl * B, H * cfg.G, cfg.w, D), K.reshape(nl * B, H, N, D), cfg.G, cfg.pool)
+    Ko, Vo, idx, ln = ctx.select_gather(score, hb.reshape(nl * B, H), K.reshape(nl * B, H, N, D),
+                                        V.reshape(nl * B, H, N, D), cfg.w, cfg.cap)
+    return ent, hb, score, Ko, Vo, idx, ln
+
+
+def test_four_calls_replayed_from_a_hip_graph(ctx):
+    """The four calls captured once into a HIP graph (they launch kernels only: no allocation, no memset, no
+    host synchronisation) and replayed on new inputs written into the same buffers, with eager calls and
+    synchronisations between the replays: every replay must give the bits of the eager calls on the same inputs."""
+    cfg = synth.tiny_config(dtype="bf16", B=1, H=4, G=4, N=3000, w=32, avg_budget=256, M=4)
+    K0, V0, Q0 = synth.gen_all(cfg, seed0=31)
+    Kd, Vd, Qd = K0.to(DEV), V0.to(DEV), Q0.to(DEV)
+    _four_calls(ctx, cfg, Kd, Vd, Qd)                          # warm-up outside the capture
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        held = _four_calls(ctx, cfg, Kd, Vd, Qd)
+    torch.cuda.synchronize()
+    for seed in (31, 32, 33, 34):
+        K, V, Q = synth.gen_all(cfg, seed0=seed)
+        Kd.copy_(K.to(DEV)); Vd.copy_(V.to(DEV)); Qd.copy_(Q.to(DEV))
+        graph.replay()
+        torch.cuda.synchronize()
+        replayed = [t.clone() for t in held]
+        eager = _four_calls(ctx, cfg, Kd, Vd, Qd)              # the program's own eager work between the replays
+        torch.cuda.synchronize()
+        for name, x, y in zip(("entropy", "budget", "score", "K_out", "V_out", "idx", "len"), replayed, eager):
+            assert torch.equal(x, y), f"seed {seed}: {name} differs between the graph replay and the eager calls"
+
+
 def test_determinism(ctx):
     cfg = synth.tiny_config(dtype="bf16", B=1, H=4, G=4, N=3000, w=32, avg_budget=256, M=4)
     K, V, Q = synth.gen_all(cfg, seed0=11)
