@@ -132,8 +132,9 @@ uncomp_status uncomp_join(uncomp_ctx* ctx, void* stream);
 
 /* Kernel selection for testing: plain_alu != 0 makes the bf16 calls use the plain-ALU
  * kernels (the ones fp32 inputs always use) instead of the MFMA kernels, the eigen stage the
- * fp32 Jacobi iteration instead of the fp64 tridiagonalisation, and uncomp_decode_step its
- * one-kernel path.  Default 0. */
+ * fp32 Jacobi iteration instead of the fp64 tridiagonalisation, uncomp_decode_step its
+ * one-kernel path, and uncomp_select_gather the one-workgroup-per-head selection also for a
+ * few long rows (which it otherwise splits over many workgroups).  Default 0. */
 uncomp_status uncomp_set_kernel_path(uncomp_ctx* ctx, int plain_alu);
 
 /*

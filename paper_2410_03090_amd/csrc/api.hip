@@ -323,10 +323,19 @@ uncomp_status uncomp_select_gather(uncomp_ctx* ctx, const float* score, const in
     // key ranges of these very scores, if uncomp_window_score has just left them in the workspace
     const bool ranged = ctx->key_range.ptr != nullptr && ctx->key_range.score == score &&
                         ctx->key_range.groups == B * H && ctx->key_range.P == N - w;
+    // A layer's worth of heads with long rows (the call as a layer-by-layer prefill makes it) would leave most of
+    // the chip idle with one workgroup per head: split every row over many workgroups.  Their scratch takes the
+    // front of the workspace, which is free on this stream after the join; the key ranges there are not needed.
+    const SelectWidePlan sw = plan_select_wide(B * H, N, w);
+    const bool wide = !ctx->force_alu && B * H <= kWideSelectRows && N - w >= kWideSelectScores &&
+                      kBudgetScratch + sw.bytes <= ctx->ws_bytes;
+    if (wide) ctx->key_range.ptr = nullptr;
     hipError_t e = launch_select_gather(score, budget, all_kv ? K : nullptr, V, dtype, B, H, N, w,
                                         all_kv ? kv_strides : zero_strides, cap, K_out, V_out, idx_out, len_out,
                                         Env{static_cast<hipStream_t>(stream), &ctx->prof, ctx->force_alu},
-                                        ranged ? ctx->key_range.ptr : nullptr, ranged ? ctx->key_range.n_tiles : 0, D);
+                                        ranged && !wide ? ctx->key_range.ptr : nullptr,
+                                        ranged && !wide ? ctx->key_range.n_tiles : 0, D, wide ? &sw : nullptr,
+                                        ctx->ws + kBudgetScratch);
     if (e != hipSuccess) return hip_fail(ctx, e, "select_gather: launch");
     return UNCOMP_OK;
 }
@@ -348,7 +357,7 @@ HiddenPlan plan_hidden(int B, int H, int G, int N, int w) {
     p.sum_off = align_up(p.score_off + (size_t)B * H * (N - 1) * sizeof(float), 256);
     p.sw_off = align_up(p.sum_off + (size_t)B * (N - w) * sizeof(float), 256);
     p.sw = plan_select_wide(B, N, w);
-    p.wide_select = B <= 32 && N - w >= 32768;
+    p.wide_select = B <= kWideSelectRows && N - w >= kWideSelectScores;
     p.bytes = p.sw_off + (p.wide_select ? p.sw.bytes : 0);
     return p;
 }

@@ -126,12 +126,15 @@ hipError_t launch_select_gather(const float* score, const int32_t* budget, const
                                 const void* V, uncomp_dtype dt, int B, int H, int N, int w,
                                 const int64_t ks[3], int cap, void* K_out, void* V_out,
                                 int32_t* idx_out, int32_t* len_out, const Env& env,
-                                const uint32_t* tile_range = nullptr, int n_range_tiles = 0, int D = kD);
+                                const uint32_t* tile_range = nullptr, int n_range_tiles = 0, int D = kD,
+                                const struct SelectWidePlan* wide = nullptr, char* wide_ws = nullptr);
 // The same selection for a few long rows, each split over n_wg workgroups (select_wide.hip); ws: p.bytes.
 struct SelectWidePlan {
     int n_wg;            // workgroups (chunks of 2048 positions) per row
     size_t bytes;
 };
+// few rows (at most kWideSelectRows), long ones (at least kWideSelectScores scores): worth splitting
+constexpr int kWideSelectRows = 32, kWideSelectScores = 32768;
 SelectWidePlan plan_select_wide(int n_groups, int N, int w);
 hipError_t launch_select_rows_wide(const float* score, const int32_t* budget, int budget_stride, int n_groups, int N,
                                    int w, int cap, const SelectWidePlan& p, char* ws, int32_t* idx_out, int32_t* len_out,

@@ -464,14 +464,20 @@ hipError_t launch_select_gather(const float* score, const int32_t* budget, const
                                 const void* V, uncomp_dtype dt, int B, int H, int N, int w,
                                 const int64_t ks[3], int cap, void* K_out, void* V_out,
                                 int32_t* idx_out, int32_t* len_out, const Env& env, const uint32_t* tile_range,
-                                int n_range_tiles, int D) {
+                                int n_range_tiles, int D, const SelectWidePlan* wide, char* wide_ws) {
     hipStream_t s = env.s;
     const int BH = B * H;
-    env.begin("select");
-    select_kernel<<<dim3(BH), dim3(kSelThreads), kSelDynLds, s>>>(score, budget, 1, N, w, cap, tile_range, n_range_tiles,
-                                                                  idx_out, len_out);
-    env.end();
-    hipError_t e = hipGetLastError();
+    hipError_t e;
+    if (wide != nullptr) {
+        // a layer's few heads with long rows: many workgroups per row (same indices as select_kernel)
+        e = launch_select_rows_wide(score, budget, 1, BH, N, w, cap, *wide, wide_ws, idx_out, len_out, env);
+    } else {
+        env.begin("select");
+        select_kernel<<<dim3(BH), dim3(kSelThreads), kSelDynLds, s>>>(score, budget, 1, N, w, cap, tile_range, n_range_tiles,
+                                                                      idx_out, len_out);
+        env.end();
+        e = hipGetLastError();
+    }
     if (e != hipSuccess || K == nullptr) return e;
     const int esz = dt == UNCOMP_BF16 ? 2 : 4;
     const int per16 = 16 / esz;                       // elements per 16-byte unit

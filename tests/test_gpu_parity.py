@@ -216,7 +216,8 @@ def test_score_strided_keys(ctx):
 
 # ------------------------------------------------------------------------- select + gather
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
-@pytest.mark.parametrize("N,w,cap", [(40, 4, 40), (200, 16, 64), (5000, 32, 700), (4200, 8, 4200), (9000, 64, 1024)])
+@pytest.mark.parametrize("N,w,cap", [(40, 4, 40), (200, 16, 64), (5000, 32, 700), (4200, 8, 4200), (9000, 64, 1024),
+                                     (40007, 7, 3000), (70000, 32, 70000)])       # the last two: rows split over workgroups
 def test_select_gather_exact(ctx, dtype, N, w, cap):
     B, H, D = 2, 3, 128
     P = N - w
@@ -267,13 +268,20 @@ def test_select_paths(ctx, case):
     else:
         budget = np.array([[w + 1, w + 2, w]], dtype=np.int32)
     cap = int(budget.max())
-    _, _, idx, ln = ctx.select_gather(torch.from_numpy(score).to(DEV), torch.from_numpy(budget).to(DEV),
-                                      None, None, w, cap, N=N)
-    torch.cuda.synchronize()
-    for h in range(H):
-        ref = O.select_indices(score[0, h].astype(np.float64), budget[0, h], N, w)
-        assert int(ln[0, h]) == len(ref)
-        assert np.array_equal(idx[0, h, : len(ref)].cpu().numpy(), ref), (case, h)
+    # three long rows are selected by many workgroups per row; the switch to the plain kernels also selects the
+    # one-workgroup kernel, whose routes the cases are named after: both must be exact
+    for one_workgroup in (False, True):
+        ctx.set_kernel_path(one_workgroup)
+        try:
+            _, _, idx, ln = ctx.select_gather(torch.from_numpy(score).to(DEV), torch.from_numpy(budget).to(DEV),
+                                              None, None, w, cap, N=N)
+            torch.cuda.synchronize()
+        finally:
+            ctx.set_kernel_path(False)
+        for h in range(H):
+            ref = O.select_indices(score[0, h].astype(np.float64), budget[0, h], N, w)
+            assert int(ln[0, h]) == len(ref)
+            assert np.array_equal(idx[0, h, : len(ref)].cpu().numpy(), ref), (case, h, one_workgroup)
 
 
 def test_select_after_scores_changed_in_place(ctx):
