@@ -331,21 +331,43 @@ __global__ __launch_bounds__(256) void score_lse_import_kernel(const float* __re
     if (e < n) lse[e] = lse_nat[e] * kLog2e;
 }
 
-// merge: one thread per (head, row)
+// merge of the partial (maximum, sum) pairs of every query row: a workgroup takes 64 rows, four threads per row
+// each fold every fourth partial (four loads in flight; with a layer's few heads there are hundreds of partials
+// per row and one thread walking them all was 114 us of latency), then the four are folded in order.
+__device__ __forceinline__ void lse_fold(float& m, float& sum, float2 v) {
+    if (v.y > 0.f) {
+        const float M = fmaxf(m, v.x);
+        sum = sum * exp2f(m - M) + v.y * exp2f(v.x - M);         // m = -inf, sum = 0 at the start: 0 * 0 + ...
+        m = M;
+    }
+}
 __global__ __launch_bounds__(256) void score_lse_kernel(const float2* __restrict__ stats, int n_rows_total,
                                                         int R, int n_chunks, float* __restrict__ lse) {
-    const int e = blockIdx.x * blockDim.x + threadIdx.x;
-    if (e >= n_rows_total) return;
-    const int bh = e / R, row = e % R;
-    const float2* st = stats + (int64_t)bh * n_chunks * R + row;
-    float mx = -INFINITY;
-    for (int c = 0; c < n_chunks; ++c) mx = fmaxf(mx, st[(int64_t)c * R].x);
-    float sum = 0.f;
-    for (int c = 0; c < n_chunks; ++c) {
-        float2 v = st[(int64_t)c * R];
-        if (v.y > 0.f) sum += v.y * exp2f(v.x - mx);
+    __shared__ float2 part[3][64];
+    const int i = threadIdx.x & 63, q = threadIdx.x >> 6;
+    const int e = blockIdx.x * 64 + i;
+    float m = -INFINITY, sum = 0.f;
+    if (e < n_rows_total) {
+        const int bh = e / R, row = e % R;
+        const float2* st = stats + (int64_t)bh * n_chunks * R + row;
+        int c = q;
+        for (; c + 12 < n_chunks; c += 16) {
+            const float2 v0 = st[(int64_t)c * R], v1 = st[(int64_t)(c + 4) * R];
+            const float2 v2 = st[(int64_t)(c + 8) * R], v3 = st[(int64_t)(c + 12) * R];
+            lse_fold(m, sum, v0);
+            lse_fold(m, sum, v1);
+            lse_fold(m, sum, v2);
+            lse_fold(m, sum, v3);
+        }
+        for (; c < n_chunks; c += 4) lse_fold(m, sum, st[(int64_t)c * R]);
     }
-    lse[e] = mx + log2f(sum);
+    if (q > 0) part[q - 1][i] = make_float2(m, sum);
+    __syncthreads();
+    if (q == 0 && e < n_rows_total) {
+#pragma unroll
+        for (int x = 0; x < 3; ++x) lse_fold(m, sum, part[x][i]);
+        lse[e] = m + log2f(sum);
+    }
 }
 
 // ---------------------------------------------------------------------------------------
@@ -582,7 +604,7 @@ static hipError_t run_score(const T* Q, const T* K, int B, int H, int G, int N, 
     }
     if (own_stats) {
         env.begin("score_lse");
-        score_lse_kernel<<<dim3((rows + 255) / 256), dim3(256), 0, s>>>(stats, rows, p.R, n_parts, lse);
+        score_lse_kernel<<<dim3((rows + 63) / 64), dim3(256), 0, s>>>(stats, rows, p.R, n_parts, lse);
         env.end();
     }
     const int n_tiles = (P + 255) / 256;
