@@ -163,9 +163,10 @@ uncomp_status uncomp_head_entropy(uncomp_ctx* ctx, const void* X, uncomp_dtype d
  * largest eigenvalues are taken as the Ritz values of a 128-dimensional subspace after n_iter
  * rounds of block power iteration (each round reads X twice).  Their error falls like
  * (sigma_129 / sigma_k)^(2 n_iter): a few rounds when the spectrum drops before the 129th
- * eigenvalue, many when it is flat there.  For bf16 inputs all rounds but the last multiply by
- * factors rounded to bf16 (the last round and the final projection keep 17 bits): the Ritz values
- * change by the square of what a round gets wrong, below 2e-6 relative on the tested spectra.
+ * eigenvalue, many when it is flat there.  For bf16 inputs the rounds multiply by factors rounded
+ * to bf16 (the iterated block keeps 17 bits only in the last round and in the final projection):
+ * the Ritz values change by the square of what a round gets wrong, below 2e-6 relative on the
+ * tested spectra.
  * entropy_out [n_mat]; eig_out, if not NULL, receives
  * the 128 Ritz values of each matrix as shares of the full trace, descending ([n_mat][128]).
  * X as in uncomp_head_entropy (ldx >= D, strides multiples of 8 elements, 16-byte aligned).

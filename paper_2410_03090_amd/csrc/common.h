@@ -176,13 +176,11 @@ struct MatrixPlan {
     size_t bytes;
 };
 MatrixPlan plan_matrix(int N, int D);
-hipError_t launch_xtz_mfma(const uint16_t* X, int64_t ldx, const float* Z, int N, int D, uint16_t* Zh, uint16_t* Zl,
-                           int t_chunk, int n_tchunks, float* Wpart, hipStream_t s, bool precise = true,
-                           bool zt_ready = false);
-hipError_t launch_xq_mfma(const uint16_t* X, int64_t ldx, const float* Q, int N, int D, uint16_t* Qt_hi,
-                          uint16_t* Qt_lo, int n_split, float* Zpart, float* Z, hipStream_t s, bool precise = true,
-                          bool want_zt = false, uint16_t* Zh = nullptr, uint16_t* Zl = nullptr,
-                          bool* zt_written = nullptr);
+hipError_t launch_xtz_mfma(const uint16_t* X, int64_t ldx, const float* Z, int N, int D, uint16_t* Zt, int t_chunk,
+                           int n_tchunks, float* Wpart, hipStream_t s, bool zt_ready);
+hipError_t launch_xq_mfma(const uint16_t* X, int64_t ldx, int N, int D, const uint16_t* Qt_hi, const uint16_t* Qt_lo,
+                          int n_split, float* Zpart, float* Z, hipStream_t s, bool precise, bool want_zt, uint16_t* Zt,
+                          bool* zt_written);
 hipError_t launch_matrix_entropy(const void* X, uncomp_dtype dt, int n_mat, int N, int D, int64_t mat_stride,
                                  int64_t ldx, int k_trunc, unsigned flags, int n_iter, const MatrixPlan& p, char* ws,
                                  float* entropy_out, float* eig_out, const Env& env);

@@ -724,7 +724,7 @@ MatrixPlan plan_matrix(int N, int D) {
     p.z_splits = zs;
     p.qt_off = take((size_t)2 * kP * D * sizeof(bf16_bits));
     p.zpart_off = take(zs > 1 ? (size_t)zs * N * kP * sizeof(float) : 0);
-    p.zsplit_off = take((size_t)2 * (((size_t)N + 127) / 128 * 128) * kP * sizeof(bf16_bits));
+    p.zsplit_off = take((((size_t)N + 127) / 128 * 128) * kP * sizeof(bf16_bits));      // Z^T rounded to bf16
     p.bytes = off;
     return p;
 }
@@ -767,22 +767,23 @@ static hipError_t run_matrix_entropy(const T* X, int n_mat, int N, int D, int64_
                                                                        mfma ? Qt_hi : nullptr, Qt_lo, zsum + kP);
     };
     float* Zpart = reinterpret_cast<float*>(ws + p.zpart_off);
-    bf16_bits* Zh = reinterpret_cast<bf16_bits*>(ws + p.zsplit_off);
-    bf16_bits* Zl = Zh + (((size_t)N + 127) / 128 * 128) * kP;
+    bf16_bits* Zt = reinterpret_cast<bf16_bits*>(ws + p.zsplit_off);
     hipError_t perr = hipSuccess;
-    // All rounds but the last multiply by the high bf16 half of Q and Z only (relative error 2^-9 per product):
-    // what they get wrong is a small tilt of the iterated subspace, which the next round removes like any other
-    // component outside the dominant subspace, and the eigenvalues of the projection move only with the square
-    // of the tilt that is left.  The last round and the final projection use both halves (measured against the
-    // fp64 reference: entropy off by 1e-6 relative at most with one such round, 5e-5 with none).
+    // Z is always rounded to bf16 on its way into W = X^T Z (2^-9 relative error per element, averaged over the
+    // tokens of the sum); Q enters Z = X Q as its high bf16 half in all rounds but the last, and as both halves in
+    // the last round and in the final projection.  What a round with rounded factors gets wrong is a small tilt of
+    // the iterated subspace, which the next round removes like any other component outside the dominant subspace,
+    // and the eigenvalues of the projection move only with the square of the tilt that is left (measured against
+    // the fp64 reference: entropy off by 1.6e-6 relative at most; 5e-5 if the last round rounds Q as well; keeping
+    // both halves of Z in the last round too changes nothing).
     const int first_precise = n_iter - 1;
     bool zt_ready = false;                                // the last projection left the transposed halves of Z, not Z
     auto project = [&](const T* Xm, bool precise, bool for_round) {       // Z = X Q
         zt_ready = false;
         if constexpr (sizeof(T) == 2) {
             if (mfma) {
-                hipError_t e = launch_xq_mfma(Xm, ldx, Q, N, D, Qt_hi, Qt_lo, p.z_splits, Zpart, Z, s, precise, for_round, Zh,
-                                              Zl, &zt_ready);
+                hipError_t e = launch_xq_mfma(Xm, ldx, N, D, Qt_hi, Qt_lo, p.z_splits, Zpart, Z, s, precise, for_round, Zt,
+                                              &zt_ready);
                 if (e != hipSuccess) perr = e;
                 return;
             }
@@ -811,7 +812,7 @@ static hipError_t run_matrix_entropy(const T* X, int n_mat, int N, int D, int64_
             bool done = false;
             if constexpr (sizeof(T) == 2) {
                 if (mfma) {
-                    hipError_t e = launch_xtz_mfma(Xm, ldx, Z, N, D, Zh, Zl, p.t_chunk, p.t_chunks, Wpart, s, precise, zt_ready);
+                    hipError_t e = launch_xtz_mfma(Xm, ldx, Z, N, D, Zt, p.t_chunk, p.t_chunks, Wpart, s, zt_ready);
                     if (e != hipSuccess) return e;
                     w_parts = p.t_chunks;
                     done = true;

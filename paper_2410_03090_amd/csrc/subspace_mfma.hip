@@ -42,16 +42,15 @@ constexpr size_t xq_lds_bytes() {
     return (size_t)2 * (LO ? 2 : 1) * kP * kQtRow * sizeof(bf16_bits);
 }
 
-// ZT: the result goes out as the transposed bf16 halves that the X^T Z kernel streams (Zt_hi, and Zt_lo when
-// LO, [128][n_pad] with zeros for the tokens from N to n_pad) instead of as fp32 rows: the rounds of the
-// iteration need nothing else of Z, which saves writing it as fp32 and reading it back to split it.
+// ZT: the result goes out as what the X^T Z kernel streams, Z^T rounded to bf16 (Zt [128][n_pad] with zeros for
+// the tokens from N to n_pad), instead of as fp32 rows: the rounds of the iteration need nothing else of Z,
+// which saves writing it as fp32 and reading it back to round it.
 template <bool LO, bool ZT>
 __global__ __launch_bounds__(256) void sub_xq_mfma_kernel(const bf16_bits* __restrict__ X, int64_t ldx,
                                                           const bf16_bits* __restrict__ Qt_hi,
                                                           const bf16_bits* __restrict__ Qt_lo, int N, int D,
                                                           int k_chunk, float* __restrict__ out,
-                                                          bf16_bits* __restrict__ Zt_hi, bf16_bits* __restrict__ Zt_lo,
-                                                          int64_t n_pad) {
+                                                          bf16_bits* __restrict__ Zt_hi, int64_t n_pad) {
     extern __shared__ __align__(16) bf16_bits qs_raw[];              // [buffer][half][column][kQtRow]
     constexpr int kHalf = kP * kQtRow, kBuf = (LO ? 2 : 1) * kHalf;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
@@ -161,41 +160,15 @@ __global__ __launch_bounds__(256) void sub_xq_mfma_kernel(const bf16_bits* __res
         body(phase_t<1>{}, s0 + 1);
     }
     // accumulator lane: column 16 cb + n, rows 16 rb + 4 kq + v
-    if constexpr (ZT && LO) {
-        // both halves straight from the registers: four consecutive tokens of one column = 8 bytes of a row of Zt
-        // (this variant runs once per matrix and has no registers to spare for the staged way out below)
-#pragma unroll
-        for (int rb = 0; rb < 4; ++rb) {
-            const int r = row0 + 16 * rb + 4 * kq;
-            if (r < n_pad) {
-#pragma unroll
-                for (int cb = 0; cb < 8; ++cb) {
-                    uint32_t h[4], l[4];
-#pragma unroll
-                    for (int v = 0; v < 4; ++v) {
-                        const float z = r + v < N ? acc[rb][cb][v] : 0.f;
-                        h[v] = bf16_rne(z);
-                        l[v] = bf16_rne(z - __uint_as_float(h[v] << 16));
-                    }
-                    const int64_t at = (int64_t)(16 * cb + n) * n_pad + r;
-                    *reinterpret_cast<uint2*>(Zt_hi + at) = make_uint2(h[0] | (h[1] << 16), h[2] | (h[3] << 16));
-                    *reinterpret_cast<uint2*>(Zt_lo + at) = make_uint2(l[0] | (l[1] << 16), l[2] | (l[3] << 16));
-                }
-            }
-        }
-        return;
-    } else if constexpr (ZT) {
+    if constexpr (ZT) {
         // Transposed on the way out through the staging buffers, which are free after the loop's last barrier: a
-        // wave packs 64 columns x its 64 tokens of one bf16 half into its quarter of them (8 bytes = four tokens
+        // wave packs 64 columns x its 64 tokens, rounded to bf16, into its quarter of them (8 bytes = four tokens
         // of a column per lane and accumulator block), then writes them out as 16-byte pieces, eight lanes to a
         // 128-byte run of one row of Zt (stored straight from the registers the same bytes went out as 32-byte
         // runs, 10 us slower per pass).  Tokens from N to n_pad are zeros; n_pad is a multiple of 128.
         bf16_bits* tile = qs_raw + wv * (64 * kQtRow);                // [64 columns][64 tokens + 8 of padding]
-        constexpr int kPasses = LO ? 4 : 2;
 #pragma unroll
-        for (int pass = 0; pass < kPasses; ++pass) {
-            const int ch = pass & 1;                                 // columns 64 ch .. + 64
-            const bool low = (pass >> 1) != 0;
+        for (int ch = 0; ch < 2; ++ch) {                             // columns 64 ch .. + 64
 #pragma unroll
             for (int cbh = 0; cbh < 4; ++cbh)
 #pragma unroll
@@ -205,20 +178,18 @@ __global__ __launch_bounds__(256) void sub_xq_mfma_kernel(const bf16_bits* __res
 #pragma unroll
                     for (int v = 0; v < 4; ++v) {
                         const float z = r + v < N ? acc[rb][4 * ch + cbh][v] : 0.f;
-                        const uint32_t hi = bf16_rne(z);
-                        w4[v] = low ? bf16_rne(z - __uint_as_float(hi << 16)) : hi;
+                        w4[v] = bf16_rne(z);
                     }
                     *reinterpret_cast<uint2*>(&tile[(16 * cbh + n) * kQtRow + 16 * rb + 4 * kq]) =
                         make_uint2(w4[0] | (w4[1] << 16), w4[2] | (w4[3] << 16));
                 }
             __syncthreads();
-            bf16_bits* dst = low ? Zt_lo : Zt_hi;
 #pragma unroll
             for (int u = 0; u < 8; ++u) {
                 const int idx = lane + 64 * u, col = idx >> 3, piece = idx & 7;
                 const uint4 v = *reinterpret_cast<const uint4*>(&tile[col * kQtRow + 8 * piece]);
                 const int t = row0 + 8 * piece;
-                if (t < n_pad) *reinterpret_cast<uint4*>(dst + (int64_t)(64 * ch + col) * n_pad + t) = v;
+                if (t < n_pad) *reinterpret_cast<uint4*>(Zt_hi + (int64_t)(64 * ch + col) * n_pad + t) = v;
             }
             __syncthreads();                                         // before the tile is packed again
         }
@@ -238,11 +209,11 @@ __global__ __launch_bounds__(256) void sub_xq_mfma_kernel(const bf16_bits* __res
 }
 
 
-// Zt_hi / Zt_lo [128][n_pad] bf16 from Z [N][128] fp32: the transposed halves that the X^T Z kernel streams
-// (n_pad = N rounded up to 128; the tokens past N are written as zeros).  Tile: 64 tokens x 32 columns.
-template <bool LO>
+// Zt [128][n_pad] bf16 from Z [N][128] fp32: Z^T rounded to bf16, as the X^T Z kernel streams it (n_pad = N rounded
+// up to 128; the tokens past N are written as zeros).  Tile: 64 tokens x 32 columns.  Only for matrices so short
+// that the sum over d of Z = X Q is split over workgroups; otherwise the X Q kernel writes Zt itself.
 __global__ __launch_bounds__(256) void sub_z_split_kernel(const float* __restrict__ Z, int N, int64_t n_pad,
-                                                          bf16_bits* __restrict__ Zt_hi, bf16_bits* __restrict__ Zt_lo) {
+                                                          bf16_bits* __restrict__ Zt) {
     __shared__ float tile[64][33];
     const int t0 = blockIdx.x * 64, j0 = blockIdx.y * 32;
     const int tid = threadIdx.x;
@@ -257,23 +228,15 @@ __global__ __launch_bounds__(256) void sub_z_split_kernel(const float* __restric
         tile[r][4 * q + 3] = v.w;
     }
     __syncthreads();
-    const int col = tid >> 3, piece = tid & 7;                        // 8 tokens of one column: 16 bytes per half
-    uint32_t h[8], l[8];
+    const int col = tid >> 3, piece = tid & 7;                        // 8 tokens of one column: 16 bytes
+    uint32_t h[8];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        const float v = tile[8 * piece + i][col];
-        h[i] = bf16_rne(v);
-        l[i] = bf16_rne(v - __uint_as_float(h[i] << 16));
-    }
-    const int64_t at = (int64_t)(j0 + col) * n_pad + t0 + 8 * piece;
-    *reinterpret_cast<uint4*>(Zt_hi + at) =
+    for (int i = 0; i < 8; ++i) h[i] = bf16_rne(tile[8 * piece + i][col]);
+    *reinterpret_cast<uint4*>(Zt + (int64_t)(j0 + col) * n_pad + t0 + 8 * piece) =
         make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
-    if (LO)
-        *reinterpret_cast<uint4*>(Zt_lo + at) =
-            make_uint4(l[0] | (l[1] << 16), l[2] | (l[3] << 16), l[4] | (l[5] << 16), l[6] | (l[7] << 16));
 }
 
-// out[tc][d][j] = sum over the token chunk of X[t][d] (Zh[t][j] + Zl[t][j]) for the 128 features d of
+// out[tc][d][j] = sum over the token chunk of X[t][d] bf16(Z[t][j]) for the 128 features d of
 // one slab.  The contraction runs over tokens, the slow index of X, so X is transposed in registers: a
 // lane loads 8 tokens x 8 features (16 bytes per token) and byte permutes turn them into 8 operands
 // "feature 8 i + c over 8 tokens".  The four waves of a workgroup share one slab of X: per round of 128
@@ -283,10 +246,8 @@ __global__ __launch_bounds__(256) void sub_z_split_kernel(const float* __restric
 // round ahead.  Accumulator block (c, b): feature 8 i + c, column 32 w + 16 b + n.
 // Workgroups that share a token chunk are placed on one XCD (the hardware deals consecutive workgroup ids
 // round-robin over the 8 XCDs), so each L2 fetches only its own chunks of Z.
-template <bool LO>
 __global__ __launch_bounds__(256) void sub_xtz_mfma_kernel(const bf16_bits* __restrict__ X, int64_t ldx,
-                                                           const bf16_bits* __restrict__ Zh,
-                                                           const bf16_bits* __restrict__ Zl, int64_t n_pad, int N, int D,
+                                                           const bf16_bits* __restrict__ Zh, int64_t n_pad, int N, int D,
                                                            int n_slabs, int t_chunk, float* __restrict__ out) {
     __shared__ __align__(16) uint4 xs[2][4][8][64];                   // [buffer][step][operand][lane]: 64 KB
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
@@ -299,7 +260,6 @@ __global__ __launch_bounds__(256) void sub_xtz_mfma_kernel(const bf16_bits* __re
     const int n_rounds = (t_end - t_begin + 127) >> 7;
     const bf16_bits* xbase = X + (int64_t)slab * 128 + 8 * m;
     const bf16_bits* zh_base = Zh + (int64_t)(32 * wv + m) * n_pad + 8 * g;    // column 32 w + n, then + 16 columns
-    const bf16_bits* zl_base = Zl + (int64_t)(32 * wv + m) * n_pad + 8 * g;
     f32x4_t acc[8][2];
 #pragma unroll
     for (int c = 0; c < 8; ++c) {
@@ -308,7 +268,6 @@ __global__ __launch_bounds__(256) void sub_xtz_mfma_kernel(const bf16_bits* __re
     }
     uint4 x0, x1, x2, x3, x4, x5, x6, x7;                            // this wave's step of the next round (named: no scratch)
     uint4 zc[4][2], zn[4][2];                                        // Z operands [step][column block]: this round, the next
-    uint4 lc[4][2], ln[4][2];                                        // their low halves
     // tokens past the end contribute nothing: their X rows are taken as zero
     auto row_or_zero = [&](int t) {
         uint4 v = make_uint4(0u, 0u, 0u, 0u);
@@ -327,15 +286,13 @@ __global__ __launch_bounds__(256) void sub_xtz_mfma_kernel(const bf16_bits* __re
         x7 = row_or_zero(t0 + 7);
     };
     // t_begin and the rounds are multiples of 128 and n_pad covers whole rounds: every load stays inside Zt
-    auto load_z = [&](uint4 (&zd)[4][2], uint4 (&ld)[4][2], int round) {
+    auto load_z = [&](uint4 (&zd)[4][2], int round) {
         const int64_t t0 = t_begin + 128 * round;
 #pragma unroll
         for (int st = 0; st < 4; ++st)
 #pragma unroll
-            for (int b = 0; b < 2; ++b) {
+            for (int b = 0; b < 2; ++b)
                 zd[st][b] = *reinterpret_cast<const uint4*>(zh_base + (int64_t)16 * b * n_pad + t0 + 32 * st);
-                if (LO) ld[st][b] = *reinterpret_cast<const uint4*>(zl_base + (int64_t)16 * b * n_pad + t0 + 32 * st);
-            }
     };
     // operand c, dword j = feature 8m + c of tokens (2j, 2j+1) of this lane's 8 tokens
     auto store_x = [&](int buf) {
@@ -356,7 +313,7 @@ __global__ __launch_bounds__(256) void sub_xtz_mfma_kernel(const bf16_bits* __re
     };
     if (n_rounds > 0) {
         load_x(0);
-        load_z(zc, lc, 0);
+        load_z(zc, 0);
         store_x(0);
     }
     __syncthreads();
@@ -365,23 +322,16 @@ __global__ __launch_bounds__(256) void sub_xtz_mfma_kernel(const bf16_bits* __re
         const bool more = round + 1 < n_rounds;
         if (more) {
             load_x(round + 1);
-            load_z(zn, ln, round + 1);
+            load_z(zn, round + 1);
         }
 #pragma unroll
         for (int st = 0; st < 4; ++st) {
             const bf16x8_t bh0 = __builtin_bit_cast(bf16x8_t, zc[st][0]), bh1 = __builtin_bit_cast(bf16x8_t, zc[st][1]);
-            bf16x8_t bl0 = bh0, bl1 = bh1;
-            if (LO) {
-                bl0 = __builtin_bit_cast(bf16x8_t, lc[st][0]);
-                bl1 = __builtin_bit_cast(bf16x8_t, lc[st][1]);
-            }
 #pragma unroll
             for (int c = 0; c < 8; ++c) {
                 const bf16x8_t av = __builtin_bit_cast(bf16x8_t, xs[buf][st][c][lane]);
                 acc[c][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, bh0, acc[c][0], 0, 0, 0);
-                if (LO) acc[c][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, bl0, acc[c][0], 0, 0, 0);
                 acc[c][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, bh1, acc[c][1], 0, 0, 0);
-                if (LO) acc[c][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, bl1, acc[c][1], 0, 0, 0);
             }
         }
         if (more) {
@@ -389,10 +339,7 @@ __global__ __launch_bounds__(256) void sub_xtz_mfma_kernel(const bf16_bits* __re
 #pragma unroll
             for (int st = 0; st < 4; ++st)
 #pragma unroll
-                for (int b = 0; b < 2; ++b) {
-                    zc[st][b] = zn[st][b];
-                    if (LO) lc[st][b] = ln[st][b];
-                }
+                for (int b = 0; b < 2; ++b) zc[st][b] = zn[st][b];
         }
         __syncthreads();
     }
@@ -424,11 +371,12 @@ __global__ __launch_bounds__(256) void sub_sum_parts_kernel(const float* __restr
     *reinterpret_cast<float4*>(out + e) = a;
 }
 
-// Z = X Q, given Q^T as two bf16 halves [128][D] (left by the orthonormalisation).  want_zt: the caller only needs Z as the operand of launch_xtz_mfma; when the sum over d is not split
-// the kernel then writes the transposed bf16 halves itself and *zt_written tells launch_xtz_mfma to skip its split.
-hipError_t launch_xq_mfma(const bf16_bits* X, int64_t ldx, const float* Q, int N, int D, bf16_bits* Qt_hi,
-                          bf16_bits* Qt_lo, int n_split, float* Zpart, float* Z, hipStream_t s, bool precise,
-                          bool want_zt, bf16_bits* Zh, bf16_bits* Zl, bool* zt_written) {
+// Z = X Q, given Q^T as two bf16 halves [128][D] (left by the orthonormalisation); precise: multiply by both.
+// want_zt: the caller only needs Z as the operand of launch_xtz_mfma; when the sum over d is not split the kernel
+// then writes Zt itself and *zt_written tells launch_xtz_mfma to skip its own rounding pass.
+hipError_t launch_xq_mfma(const bf16_bits* X, int64_t ldx, int N, int D, const bf16_bits* Qt_hi, const bf16_bits* Qt_lo,
+                          int n_split, float* Zpart, float* Z, hipStream_t s, bool precise, bool want_zt, bf16_bits* Zt,
+                          bool* zt_written) {
     const int k_chunk = ((D + n_split - 1) / n_split + kQStep - 1) / kQStep * kQStep;
     const int splits = (D + k_chunk - 1) / k_chunk;
     float* dst = splits == 1 ? Z : Zpart;
@@ -437,13 +385,13 @@ hipError_t launch_xq_mfma(const bf16_bits* X, int64_t ldx, const float* Q, int N
     const bool zt = want_zt && splits == 1;
     if (zt_written != nullptr) *zt_written = zt;
     if (zt && precise)
-        sub_xq_mfma_kernel<true, true><<<grid, dim3(256), xq_lds_bytes<true>(), s>>>(X, ldx, Qt_hi, Qt_lo, N, D, k_chunk, dst, Zh, Zl, n_pad);
+        sub_xq_mfma_kernel<true, true><<<grid, dim3(256), xq_lds_bytes<true>(), s>>>(X, ldx, Qt_hi, Qt_lo, N, D, k_chunk, dst, Zt, n_pad);
     else if (zt)
-        sub_xq_mfma_kernel<false, true><<<grid, dim3(256), xq_lds_bytes<false>(), s>>>(X, ldx, Qt_hi, Qt_lo, N, D, k_chunk, dst, Zh, Zl, n_pad);
+        sub_xq_mfma_kernel<false, true><<<grid, dim3(256), xq_lds_bytes<false>(), s>>>(X, ldx, Qt_hi, Qt_lo, N, D, k_chunk, dst, Zt, n_pad);
     else if (precise)
-        sub_xq_mfma_kernel<true, false><<<grid, dim3(256), xq_lds_bytes<true>(), s>>>(X, ldx, Qt_hi, Qt_lo, N, D, k_chunk, dst, Zh, Zl, n_pad);
+        sub_xq_mfma_kernel<true, false><<<grid, dim3(256), xq_lds_bytes<true>(), s>>>(X, ldx, Qt_hi, Qt_lo, N, D, k_chunk, dst, Zt, n_pad);
     else
-        sub_xq_mfma_kernel<false, false><<<grid, dim3(256), xq_lds_bytes<false>(), s>>>(X, ldx, Qt_hi, Qt_lo, N, D, k_chunk, dst, Zh, Zl, n_pad);
+        sub_xq_mfma_kernel<false, false><<<grid, dim3(256), xq_lds_bytes<false>(), s>>>(X, ldx, Qt_hi, Qt_lo, N, D, k_chunk, dst, Zt, n_pad);
     if (splits > 1) {
         const int64_t total = (int64_t)N * kP;
         sub_sum_parts_kernel<<<dim3((unsigned)((total / 4 + 255) / 256)), dim3(256), 0, s>>>(Zpart, splits, total, Z);
@@ -451,21 +399,14 @@ hipError_t launch_xq_mfma(const bf16_bits* X, int64_t ldx, const float* Q, int N
     return hipGetLastError();
 }
 
-// Wpart[tc][D][128] = partial X^T Z over token chunks (t_chunk a multiple of 128); Zh / Zl: the two transposed
-// halves of Z, [128][n_pad] bf16 each with n_pad = N rounded up to 128, made here from Z unless zt_ready.
-hipError_t launch_xtz_mfma(const bf16_bits* X, int64_t ldx, const float* Z, int N, int D, bf16_bits* Zh, bf16_bits* Zl,
-                           int t_chunk, int n_tchunks, float* Wpart, hipStream_t s, bool precise, bool zt_ready) {
+// Wpart[tc][D][128] = partial X^T bf16(Z) over token chunks (t_chunk a multiple of 128); Zt: Z^T rounded to bf16,
+// [128][n_pad] with n_pad = N rounded up to 128, made here from Z unless zt_ready.
+hipError_t launch_xtz_mfma(const bf16_bits* X, int64_t ldx, const float* Z, int N, int D, bf16_bits* Zt, int t_chunk,
+                           int n_tchunks, float* Wpart, hipStream_t s, bool zt_ready) {
     const int64_t n_pad = ((int64_t)N + 127) / 128 * 128;
-    const dim3 sgrid((unsigned)(n_pad / 64), kP / 32);
     const int n_slabs = D / 128;
-    const dim3 grid((unsigned)(n_slabs * n_tchunks));
-    if (precise) {
-        if (!zt_ready) sub_z_split_kernel<true><<<sgrid, dim3(256), 0, s>>>(Z, N, n_pad, Zh, Zl);
-        sub_xtz_mfma_kernel<true><<<grid, dim3(256), 0, s>>>(X, ldx, Zh, Zl, n_pad, N, D, n_slabs, t_chunk, Wpart);
-    } else {
-        if (!zt_ready) sub_z_split_kernel<false><<<sgrid, dim3(256), 0, s>>>(Z, N, n_pad, Zh, Zl);
-        sub_xtz_mfma_kernel<false><<<grid, dim3(256), 0, s>>>(X, ldx, Zh, Zl, n_pad, N, D, n_slabs, t_chunk, Wpart);
-    }
+    if (!zt_ready) sub_z_split_kernel<<<dim3((unsigned)(n_pad / 64), kP / 32), dim3(256), 0, s>>>(Z, N, n_pad, Zt);
+    sub_xtz_mfma_kernel<<<dim3((unsigned)(n_slabs * n_tchunks)), dim3(256), 0, s>>>(X, ldx, Zt, n_pad, N, D, n_slabs, t_chunk, Wpart);
     return hipGetLastError();
 }
 
