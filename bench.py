@@ -182,7 +182,8 @@ def main():
                          "GBps": round(byt / avg / 1e6, 1) if byt else None,
                          "TFLOPs": round(flops / avg / 1e9, 1) if flops else None}
     # what this machine sustains: a plain streaming read and the bf16 MFMA loop (live and zero operands)
-    read_peak, mfma_live, mfma_zero = ctx.measure_peaks(Kf)
+    peak_buf = Kf if Kf.numel() * Kf.element_size() >= (256 << 20) else torch.zeros(256 << 20, dtype=torch.uint8, device=Kf.device)
+    read_peak, mfma_live, mfma_zero = ctx.measure_peaks(peak_buf)      # the keys, or 256 MiB of its own for a small workload
     peaks = {"stream_read_GBps": round(read_peak, 1), "mfma_bf16_loop_TFLOPs_live_operands": round(mfma_live, 1),
              "mfma_bf16_loop_TFLOPs_zero_operands": round(mfma_zero, 1),
              "note": "measured by uncomp_measure_peaks on this device; the data-sheet peaks are 8000 GB/s and 2500 TFLOP/s"}
