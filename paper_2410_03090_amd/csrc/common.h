@@ -181,6 +181,8 @@ hipError_t launch_xtz_mfma(const uint16_t* X, int64_t ldx, const float* Z, int N
 hipError_t launch_xq_mfma(const uint16_t* X, int64_t ldx, int N, int D, const uint16_t* Qt_hi, const uint16_t* Qt_lo,
                           int n_split, float* Zpart, float* Z, hipStream_t s, bool precise, bool want_zt, uint16_t* Zt,
                           bool* zt_written);
+hipError_t launch_gram_f32_mfma(const float* X, int n_mat, int N, int64_t mat_stride, int64_t ldx, int n_chunks, int chunk,
+                                float* gram_part, float* sum_part, hipStream_t s);
 hipError_t launch_matrix_entropy(const void* X, uncomp_dtype dt, int n_mat, int N, int D, int64_t mat_stride,
                                  int64_t ldx, int k_trunc, unsigned flags, int n_iter, const MatrixPlan& p, char* ws,
                                  float* entropy_out, float* eig_out, const Env& env);

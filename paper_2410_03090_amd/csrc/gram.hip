@@ -148,6 +148,14 @@ hipError_t launch_gram(const void* X, uncomp_dtype dt, int n_mat, int N, int64_t
         env.end();
         return hipGetLastError();
     }
+    if (dt == UNCOMP_F32 && !force_alu && n_mat <= 65535) {
+        // fp32 matrices with 128 features: exact products and fp64 sums on the fp64 matrix cores
+        env.begin("gram_f64");
+        hipError_t e = launch_gram_f32_mfma(static_cast<const float*>(X), n_mat, N, mat_stride, ldx, p.n_chunks, p.chunk, gram,
+                                            sums, s);
+        env.end();
+        return e;
+    }
     env.begin("gram_alu");
     if (dt == UNCOMP_BF16) {
         gram_alu_kernel<bf16_bits><<<grid, block, 0, s>>>(

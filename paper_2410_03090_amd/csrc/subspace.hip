@@ -334,13 +334,20 @@ typedef double f64x4_t __attribute__((ext_vector_type(4)));
 // PACKED (the Gram of the projected tokens, whose partials only feed an fp32 result): the 36 computed tiles go
 // out as fp32, tile after tile (fpart[slice][36][16][16], tiles in the order (0,0) (0,1) ... (0,7) (1,1) ...),
 // a quarter of the bytes of the mirrored fp64 matrix that the Cholesky step needs.
-template <bool PACKED>
-__global__ __launch_bounds__(256) void sub_gram64_kernel(const float* __restrict__ A, int n_rows, int rows_per_wg,
-                                                         double* __restrict__ gpart, float* __restrict__ fpart,
-                                                         double* __restrict__ spart) {
+// MODE 2 (fp32 token matrices of uncomp_head_entropy, 128 features): blockIdx.y is the matrix (mat_stride elements
+// apart, rows lda apart), blockIdx.x its token chunk; the chunk's mirrored Gram and column sums go out as fp32 in
+// the layout the eigenvalue kernels add up: fpart[(matrix, chunk)][128][128], fsum[(matrix, chunk)][128].
+template <int MODE>
+__global__ __launch_bounds__(256) void sub_gram64_kernel(const float* __restrict__ A_all, int64_t mat_stride, int64_t lda,
+                                                         int n_rows, int rows_per_wg, double* __restrict__ gpart,
+                                                         float* __restrict__ fpart, double* __restrict__ spart,
+                                                         float* __restrict__ fsum) {
+    constexpr bool PACKED = MODE == 1;
     __shared__ __align__(16) float rows[kGramRows][kGramLd];
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int c = lane & 15, kk = lane >> 4;
+    const float* A = A_all + (int64_t)blockIdx.y * mat_stride;
+    const int64_t out_idx = (int64_t)blockIdx.y * gridDim.x + blockIdx.x;
     const int r_begin = blockIdx.x * rows_per_wg;
     const int r_end = min(n_rows, r_begin + rows_per_wg);
     const int I1 = wv, I2 = 7 - wv, n1 = 8 - wv;             // slot s < n1: tile (I1, I1 + s); else (I2, I2 + s - n1)
@@ -354,7 +361,7 @@ __global__ __launch_bounds__(256) void sub_gram64_kernel(const float* __restrict
         for (int i = 0; i < 8; ++i) {
             const int e = tid + 256 * i, rr = e >> 5, q = e & 31;
             pre[i] = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (r0 + rr < r_end) pre[i] = *reinterpret_cast<const float4*>(A + (int64_t)(r0 + rr) * kP + 4 * q);
+            if (r0 + rr < r_end) pre[i] = *reinterpret_cast<const float4*>(A + (int64_t)(r0 + rr) * lda + 4 * q);
         }
     };
     if (r_begin < r_end) fetch(r_begin);
@@ -367,7 +374,7 @@ __global__ __launch_bounds__(256) void sub_gram64_kernel(const float* __restrict
         }
         __syncthreads();
         if (r0 + kGramRows < r_end) fetch(r0 + kGramRows);
-        if (spart != nullptr && tid < kP) {
+        if ((MODE == 2 || spart != nullptr) && tid < kP) {
 #pragma unroll 8
             for (int rr = 0; rr < kGramRows; ++rr) csum += (double)rows[rr][tid];
         }
@@ -388,11 +395,19 @@ __global__ __launch_bounds__(256) void sub_gram64_kernel(const float* __restrict
         const bool first = sl < n1;
         const int I = first ? I1 : I2, J = first ? I1 + sl : I2 + sl - n1;
         if constexpr (PACKED) {
-            float* o = fpart + ((int64_t)blockIdx.x * kGramTiles + (I * 8 - I * (I - 1) / 2 + J - I)) * 256;
+            float* o = fpart + (out_idx * kGramTiles + (I * 8 - I * (I - 1) / 2 + J - I)) * 256;
 #pragma unroll
             for (int v = 0; v < 4; ++v) o[(4 * v + kk) * 16 + c] = (float)acc[sl][v];
+        } else if constexpr (MODE == 2) {
+            float* o = fpart + out_idx * kP * kP;
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int r = 16 * I + 4 * v + kk, col = 16 * J + c;
+                o[r * kP + col] = (float)acc[sl][v];
+                if (I != J) o[col * kP + r] = (float)acc[sl][v];
+            }
         } else {
-            double* o = gpart + (int64_t)blockIdx.x * kP * kP;
+            double* o = gpart + out_idx * kP * kP;
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
                 const int r = 16 * I + 4 * v + kk, col = 16 * J + c;
@@ -401,7 +416,20 @@ __global__ __launch_bounds__(256) void sub_gram64_kernel(const float* __restrict
             }
         }
     }
-    if (spart != nullptr && tid < kP) spart[(int64_t)blockIdx.x * kP + tid] = csum;
+    if (MODE == 2) {
+        if (tid < kP) fsum[out_idx * kP + tid] = (float)csum;
+    } else if (spart != nullptr && tid < kP) {
+        spart[out_idx * kP + tid] = csum;
+    }
+}
+
+// Gram partials of fp32 token matrices with 128 features for the 128-wide entropy path (see MODE 2 above):
+// exact products, fp64 sums inside a chunk, on the fp64 matrix cores instead of the fp32 ALUs.
+hipError_t launch_gram_f32_mfma(const float* X, int n_mat, int N, int64_t mat_stride, int64_t ldx, int n_chunks, int chunk,
+                                float* gram_part, float* sum_part, hipStream_t s) {
+    sub_gram64_kernel<2><<<dim3((unsigned)n_chunks, (unsigned)n_mat), dim3(256), 0, s>>>(X, mat_stride, ldx, N, chunk, nullptr,
+                                                                                    gram_part, nullptr, sum_part);
+    return hipGetLastError();
 }
 
 // gsum = sum of the slices (fixed order); four loads in flight per thread.
@@ -760,7 +788,7 @@ static hipError_t run_matrix_entropy(const T* X, int n_mat, int N, int D, int64_
     // Q = orth(W): Cholesky QR with the Gram in fp64; the last kernel also leaves the bf16 halves of Q^T and the
     // shares of s^T Q for the round that follows
     auto orth = [&]() {
-        sub_gram64_kernel<false><<<dim3((unsigned)p.gram_slices), dim3(256), 0, s>>>(W, D, p.gram_rows, gpart, nullptr, nullptr);
+        sub_gram64_kernel<0><<<dim3((unsigned)p.gram_slices), dim3(256), 0, s>>>(W, 0, kP, D, p.gram_rows, gpart, nullptr, nullptr, nullptr);
         sub_gram64_sum_kernel<<<dim3(kP * kP / 256), dim3(256), 0, s>>>(gpart, p.gram_slices, gsum);
         sub_chol_kernel<<<dim3(1), dim3(256), chol_lds, s>>>(gsum, Rinv);
         sub_q_kernel<<<dim3((unsigned)(D / kQRows)), dim3(256), 0, s>>>(W, Rinv, D, center ? sv : nullptr, Q,
@@ -836,7 +864,7 @@ static hipError_t run_matrix_entropy(const T* X, int n_mat, int N, int D, int64_
         // the projected tokens go through the 128-wide entropy path; trace(C) replaces its own trace
         env.begin("matrix_gram");
         float* fpart = reinterpret_cast<float*>(gpart);          // the region of the fp64 slices, free by now
-        sub_gram64_kernel<true><<<dim3((unsigned)p.zgram_slices), dim3(256), 0, s>>>(Z, N, p.zgram_rows, nullptr, fpart, spart);
+        sub_gram64_kernel<1><<<dim3((unsigned)p.zgram_slices), dim3(256), 0, s>>>(Z, 0, kP, N, p.zgram_rows, nullptr, fpart, spart, nullptr);
         sub_zgram_finish_kernel<<<dim3(kP * kP / 64 + 1), dim3(256), 0, s>>>(
             fpart, spart, p.zgram_slices, reinterpret_cast<float*>(ws + p.ep_off + p.ep.gram_off),
             reinterpret_cast<float*>(ws + p.ep_off + p.ep.sum_off));
