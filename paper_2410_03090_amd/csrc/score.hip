@@ -596,11 +596,18 @@ static hipError_t run_score(const T* Q, const T* K, int B, int H, int G, int N, 
                                                                           p.chunk, stats);
         env.end();
     } else if (!mfma) {
+        // This kernel writes one partial per chunk where the wave kernels write four: the statistics region has room
+        // for chunks a quarter as long, which is what a short prompt needs to occupy more than a few CUs.
+        int nca = 4 * p.n_chunks;
+        if (nca > (N + 63) / 64) nca = (N + 63) / 64;
+        const int chunk_a = ((N + nca - 1) / nca + kStatTile - 1) / kStatTile * kStatTile;
+        nca = (N + chunk_a - 1) / chunk_a;
         const int threads1 = (p.R + 63) / 64 * 64;
         env.begin("score_stats_alu");
-        score_stats_alu_kernel<T><<<grid1, dim3(threads1), 0, s>>>(Q, K, H, G, N, D, w, ks[0], ks[1], ks[2],
-                                                                   p.n_chunks, p.chunk, stats);
+        score_stats_alu_kernel<T><<<dim3((unsigned)(BH * nca)), dim3(threads1), 0, s>>>(Q, K, H, G, N, D, w, ks[0], ks[1], ks[2],
+                                                                                    nca, chunk_a, stats);
         env.end();
+        n_parts = nca;
     }
     if (own_stats) {
         env.begin("score_lse");
